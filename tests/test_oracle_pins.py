@@ -1,0 +1,350 @@
+"""Pins for the CPU oracle: each checks it against something other than itself.
+
+The paper prints no worked numerical example (no inside value, log Z or gradient), so the pins are what
+the definitions and the mathematics fix:
+  * brute-force enumeration of every labelled binary tree (paper Sec. 2 rule set) for log Z and for the
+    expected rule / root / emission counts (= the gradients);
+  * a dense inside pass over the materialised rule tensor T[A,B,C] = L[A,B] R[A,C] (first line of the
+    recursion in Sec. 3.1, before eta/zeta are factored out);
+  * closed forms (n = 2; uniform grammar -> Catalan count);
+  * the right-branching special case, which is a linear chain of matrix products;
+  * symmetries, homogeneity, central finite differences and flow-conservation invariants.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+from oracle import spcfg_oracle as O
+
+
+# ----------------------------------------------------------------------------- helpers (not the oracle)
+def random_grammar(rng, N, P, n, scale=1.0, normalised=True):
+    M = N + P
+    L = np.exp(scale * rng.normal(size=(N, M)))
+    R = np.exp(scale * rng.normal(size=(N, M)))
+    root = np.exp(rng.normal(size=N))
+    emit = np.exp(rng.normal(size=(n, P)))  # per-token preterminal weights
+    if normalised:
+        L /= L.sum(1, keepdims=True)
+        R /= R.sum(1, keepdims=True)
+        root /= root.sum()
+    return np.log(root), L, R, np.log(emit)
+
+
+def bracketings(i, j):
+    """All binary bracketings of the fencepost span (i, j) as nested tuples; a leaf is the int i."""
+    if j - i == 1:
+        yield i
+        return
+    for k in range(i + 1, j):
+        for lt in bracketings(i, k):
+            for rt in bracketings(k, j):
+                yield (lt, rt)
+
+
+def brute_force(log_root, L, R, e):
+    """Sum over every bracketing and every labelling.  Returns Z and the weighted counts of each rule use."""
+    n, P = e.shape
+    N = L.shape[0]
+    root, emit = np.exp(log_root), np.exp(e)
+    Z = 0.0
+    cL, cR = np.zeros_like(L), np.zeros_like(R)
+    c_root, c_emit = np.zeros(N), np.zeros((n, P))
+    for tree in bracketings(0, n):
+        # flatten: internal nodes in pre-order; each entry (left, right) refers to ('n', idx) or ('l', pos)
+        nodes = []
+
+        def walk(t):
+            if isinstance(t, int):
+                return ("l", t)
+            me = len(nodes)
+            nodes.append(None)
+            nodes[me] = (walk(t[0]), walk(t[1]))
+            return ("n", me)
+
+        walk(tree)
+        for nt in itertools.product(range(N), repeat=len(nodes)):
+            for pt in itertools.product(range(P), repeat=n):
+                wgt = root[nt[0]]
+                uses = []
+                for idx, (lc, rc) in enumerate(nodes):
+                    A = nt[idx]
+                    lsym = nt[lc[1]] if lc[0] == "n" else N + pt[lc[1]]
+                    rsym = nt[rc[1]] if rc[0] == "n" else N + pt[rc[1]]
+                    wgt *= L[A, lsym] * R[A, rsym]
+                    uses.append((A, lsym, rsym))
+                for i in range(n):
+                    wgt *= emit[i, pt[i]]
+                Z += wgt
+                c_root[nt[0]] += wgt
+                for (A, ls, rs) in uses:
+                    cL[A, ls] += wgt
+                    cR[A, rs] += wgt
+                for i in range(n):
+                    c_emit[i, pt[i]] += wgt
+    return Z, cL, cR, c_root, c_emit
+
+
+def dense_inside(log_root, L, R, e):
+    """Inside pass over the full rule tensor T[A,B,C] = L[A,B] R[A,C], probability space, no factoring."""
+    n, P = e.shape
+    N = L.shape[0]
+    M = N + P
+    T = L[:, :, None] * R[:, None, :]  # [N, M, M]
+    beta = {}
+    for i in range(n):
+        v = np.zeros(M)
+        v[N:] = np.exp(e[i])
+        beta[(i, i + 1)] = v
+    for w in range(2, n + 1):
+        for i in range(n - w + 1):
+            j = i + w
+            v = np.zeros(M)
+            for k in range(i + 1, j):
+                v[:N] += np.einsum("abc,b,c->a", T, beta[(i, k)], beta[(k, j)])
+            beta[(i, j)] = v
+    return float(np.exp(log_root) @ beta[(0, n)][:N])
+
+
+def oracle_all(log_root, L, R, e, g=1.0):
+    return O.inside_backward_sentence(log_root, L, R, e, g, return_marginals=True)
+
+
+# ----------------------------------------------------------------------------- log Z
+@pytest.mark.parametrize("N,P,n", [(2, 2, 2), (2, 3, 3), (3, 2, 4), (2, 2, 5), (2, 2, 6), (3, 3, 4)])
+def test_logZ_matches_tree_enumeration(N, P, n):
+    rng = np.random.default_rng(100 * N + 10 * P + n)
+    lr, L, R, e = random_grammar(rng, N, P, n, normalised=(n % 2 == 0))
+    Z = brute_force(lr, L, R, e)[0]
+    assert O.inside_sentence(lr, L, R, e)[0] == pytest.approx(math.log(Z), rel=1e-12, abs=1e-12)
+
+
+@pytest.mark.parametrize("N,P,n,seed", [(5, 7, 7, 0), (8, 3, 6, 1), (3, 9, 9, 2)])
+def test_logZ_matches_dense_rule_tensor_inside(N, P, n, seed):
+    rng = np.random.default_rng(seed)
+    lr, L, R, e = random_grammar(rng, N, P, n)
+    assert O.inside_sentence(lr, L, R, e)[0] == pytest.approx(math.log(dense_inside(lr, L, R, e)), rel=1e-12)
+
+
+def test_closed_form_two_words():
+    rng = np.random.default_rng(7)
+    N, P = 6, 5
+    lr, L, R, e = random_grammar(rng, N, P, 2, normalised=False)
+    Z = np.sum(np.exp(lr) * (L[:, N:] @ np.exp(e[0])) * (R[:, N:] @ np.exp(e[1])))
+    assert O.inside_sentence(lr, L, R, e)[0] == pytest.approx(math.log(Z), rel=1e-13)
+
+
+@pytest.mark.parametrize("n", [2, 3, 5, 9, 14])
+def test_closed_form_uniform_grammar_counts_trees(n):
+    """L = R = 1/M, root = 1/N, every emission weight c:  Z = C_{n-1} N^{n-2} P^n c^n / M^{2(n-1)}."""
+    N, P, c = 4, 7, 0.3
+    M = N + P
+    L = np.full((N, M), 1.0 / M)
+    lr = np.full(N, -math.log(N))
+    e = np.full((n, P), math.log(c))
+    catalan = math.comb(2 * (n - 1), n - 1) // n
+    expect = math.log(catalan) - 2 * (n - 1) * math.log(M) + (n - 2) * math.log(N) + n * math.log(P * c)
+    assert O.inside_sentence(lr, L, L, e)[0] == pytest.approx(expect, rel=1e-13)
+    # all weights 1: Z counts labelled trees
+    ones = np.ones((N, M))
+    got = O.inside_sentence(np.zeros(N), ones, ones, np.zeros((n, P)))[0]
+    assert got == pytest.approx(math.log(catalan) + (n - 1) * math.log(N) + n * math.log(P), rel=1e-13)
+
+
+@pytest.mark.parametrize("mirror", [False, True])
+def test_right_branching_grammar_is_a_linear_chain(mirror):
+    """If the left child is always a preterminal only the right-branching tree survives (HMM-like chain)."""
+    rng = np.random.default_rng(11)
+    N, P, n = 6, 4, 8
+    lr, L, R, e = random_grammar(rng, N, P, n, normalised=False)
+    if mirror:
+        R[:, :N] = 0.0
+    else:
+        L[:, :N] = 0.0
+    eps = np.exp(e)
+    if not mirror:
+        # beta_{k,n} = (L_P eps_k) * (R_x beta_{k+1,n}),  R_x = R_P for the last leaf else R_N
+        beta = (L[:, N:] @ eps[n - 2]) * (R[:, N:] @ eps[n - 1])
+        for k in range(n - 3, -1, -1):
+            beta = (L[:, N:] @ eps[k]) * (R[:, :N] @ beta)
+    else:
+        beta = (L[:, N:] @ eps[0]) * (R[:, N:] @ eps[1])
+        for k in range(2, n):
+            beta = (L[:, :N] @ beta) * (R[:, N:] @ eps[k])
+    Z = np.exp(lr) @ beta
+    assert O.inside_sentence(lr, L, R, e)[0] == pytest.approx(math.log(Z), rel=1e-13)
+
+
+def test_symmetries_and_homogeneity():
+    rng = np.random.default_rng(5)
+    N, P, n = 7, 5, 9
+    lr, L, R, e = random_grammar(rng, N, P, n)
+    base = O.inside_sentence(lr, L, R, e)[0]
+    # mirror image: reverse the sentence and swap the roles of left and right
+    assert O.inside_sentence(lr, R, L, e[::-1])[0] == pytest.approx(base, rel=1e-13)
+    # relabel nonterminals and preterminals consistently
+    pn, pp = rng.permutation(N), rng.permutation(P)
+    cols = np.concatenate([pn, N + pp])
+    assert O.inside_sentence(lr[pn], L[pn][:, cols], R[pn][:, cols], e[:, pp])[0] == pytest.approx(base, rel=1e-13)
+    # adding c to one token's emissions adds c; scaling L by s adds (n-1) log s; shifting log_root adds the shift
+    e2 = e.copy()
+    e2[3] += 1.7
+    assert O.inside_sentence(lr, L, R, e2)[0] == pytest.approx(base + 1.7, rel=1e-13)
+    assert O.inside_sentence(lr, 0.25 * L, R, e)[0] == pytest.approx(base + (n - 1) * math.log(0.25), rel=1e-13)
+    assert O.inside_sentence(lr - 2.0, L, R, e)[0] == pytest.approx(base - 2.0, rel=1e-13)
+
+
+def test_batch_and_padding_independence():
+    rng = np.random.default_rng(9)
+    N, P = 5, 6
+    lens = [3, 7, 2, 5]
+    n_max = max(lens)
+    lr, L, R, _ = random_grammar(rng, N, P, 2)
+    log_emit = np.full((len(lens), n_max, P), np.nan)
+    singles = []
+    for b, n in enumerate(lens):
+        e = rng.normal(size=(n, P))
+        log_emit[b, :n] = e
+        singles.append(O.inside_sentence(lr, L, R, e)[0])
+    got = O.inside(lr, L, R, log_emit, lens)
+    assert np.allclose(got, singles, rtol=1e-14)
+    full = O.inside_backward(lr, L, R, log_emit, lens)
+    assert np.all(np.isfinite(full["grad_log_emit"]))
+    for b, n in enumerate(lens):
+        assert np.all(full["grad_log_emit"][b, n:] == 0.0)
+
+
+def test_zero_probability_guards():
+    """A grammar that cannot derive the sentence gives log Z = -inf and zero gradients, not NaN."""
+    N, P, n = 3, 2, 4
+    rng = np.random.default_rng(3)
+    lr, L, R, e = random_grammar(rng, N, P, n)
+    L0 = L.copy()
+    L0[:, N:] = 0.0  # no preterminal can ever be a left child -> no tree exists
+    lz, gL, gR, gr, ge = O.inside_backward_sentence(lr, L0, R, e)
+    assert lz == -np.inf
+    assert not np.any(np.isnan(gL)) and np.all(gL == 0) and np.all(ge == 0) and np.all(gr == 0)
+    # partial zeros: still equal to enumeration
+    L1 = L.copy()
+    L1[0, :] = 0.0
+    L1[:, 1] = 0.0
+    Z = brute_force(lr, L1, R, e)[0]
+    assert O.inside_sentence(lr, L1, R, e)[0] == pytest.approx(math.log(Z), rel=1e-12)
+    out = O.inside_backward_sentence(lr, L1, R, e)
+    assert all(np.all(np.isfinite(x)) for x in out[1:])
+
+
+# ----------------------------------------------------------------------------- gradients
+@pytest.mark.parametrize("N,P,n", [(2, 2, 3), (2, 3, 4), (3, 2, 4), (2, 2, 5)])
+def test_gradients_are_expected_counts_from_enumeration(N, P, n):
+    rng = np.random.default_rng(17 * N + 5 * P + n)
+    lr, L, R, e = random_grammar(rng, N, P, n, normalised=False)
+    Z, cL, cR, c_root, c_emit = brute_force(lr, L, R, e)
+    lz, gL, gR, gr, ge = O.inside_backward_sentence(lr, L, R, e)
+    assert np.allclose(L * gL, cL / Z, rtol=1e-11, atol=1e-14)
+    assert np.allclose(R * gR, cR / Z, rtol=1e-11, atol=1e-14)
+    assert np.allclose(gr, c_root / Z, rtol=1e-11)
+    assert np.allclose(ge, c_emit / Z, rtol=1e-11)
+
+
+def test_gradients_match_central_finite_differences():
+    rng = np.random.default_rng(23)
+    N, P, n = 6, 5, 7
+    lr, L, R, e = random_grammar(rng, N, P, n)
+    g = 0.7
+    lz, gL, gR, gr, ge = O.inside_backward_sentence(lr, L, R, e, g)
+
+    def f(lr_, L_, R_, e_):
+        return g * O.inside_sentence(lr_, L_, R_, e_)[0]
+
+    h = 1e-6
+    for _ in range(6):
+        dL, dR = rng.normal(size=L.shape) * L, rng.normal(size=R.shape) * R
+        dr, de = rng.normal(size=lr.shape), rng.normal(size=e.shape)
+        num = (f(lr + h * dr, L + h * dL, R + h * dR, e + h * de)
+               - f(lr - h * dr, L - h * dL, R - h * dR, e - h * de)) / (2 * h)
+        ana = (gL * dL).sum() + (gR * dR).sum() + (gr * dr).sum() + (ge * de).sum()
+        assert ana == pytest.approx(num, rel=1e-6)
+    # selected single entries, including a preterminal column and a nonterminal column
+    for (A, Bc) in [(0, 0), (2, N + 1), (N - 1, N - 1), (3, N + P - 1)]:
+        for which, G in (("L", gL), ("R", gR)):
+            Lp, Lm, Rp, Rm = L.copy(), L.copy(), R.copy(), R.copy()
+            hh = 1e-6 * (L if which == "L" else R)[A, Bc]
+            if which == "L":
+                Lp[A, Bc] += hh
+                Lm[A, Bc] -= hh
+            else:
+                Rp[A, Bc] += hh
+                Rm[A, Bc] -= hh
+            num = (f(lr, Lp, Rp, e) - f(lr, Lm, Rm, e)) / (2 * hh)
+            assert G[A, Bc] == pytest.approx(num, rel=1e-6)
+
+
+def test_gradient_invariants():
+    """Flow conservation of expected counts (Z is homogeneous of degree n-1 in L and in R)."""
+    rng = np.random.default_rng(31)
+    N, P, n = 9, 6, 11
+    lr, L, R, e = random_grammar(rng, N, P, n)
+    lz, gL, gR, gr, ge, obar = oracle_all(lr, L, R, e)
+    EL, ER = L * gL, R * gR
+    assert gr.sum() == pytest.approx(1.0, rel=1e-12)
+    assert np.allclose(ge.sum(axis=1), 1.0, rtol=1e-12)
+    assert EL.sum() == pytest.approx(n - 1, rel=1e-12) and ER.sum() == pytest.approx(n - 1, rel=1e-12)
+    occ = sum(obar.values())  # expected number of width>=2 spans labelled A
+    assert np.allclose(EL.sum(axis=1), occ, rtol=1e-11) and np.allclose(ER.sum(axis=1), occ, rtol=1e-11)
+    assert occ.sum() == pytest.approx(n - 1, rel=1e-12)
+    # every nonterminal occurrence is the root or somebody's child; every preterminal occurrence is a child
+    assert np.allclose((EL + ER)[:, :N].sum(axis=0), occ - gr, rtol=1e-10, atol=1e-13)
+    assert np.allclose((EL + ER)[:, N:].sum(axis=0), ge.sum(axis=0), rtol=1e-11)
+    for s, v in obar.items():
+        assert v.sum() <= 1.0 + 1e-12
+    assert obar[(0, n)].sum() == pytest.approx(1.0, rel=1e-12)
+
+
+def test_upstream_weights_and_batch_sum():
+    rng = np.random.default_rng(41)
+    N, P = 4, 5
+    lens = [4, 6, 3]
+    lr, L, R, _ = random_grammar(rng, N, P, 2)
+    log_emit = rng.normal(size=(3, 6, P))
+    gz = np.array([0.5, -2.0, 1.25])
+    full = O.inside_backward(lr, L, R, log_emit, lens, gz)
+    accL = np.zeros_like(L)
+    for b, n in enumerate(lens):
+        lz, gL, gR, gr, ge = O.inside_backward_sentence(lr, L, R, log_emit[b, :n], 1.0)
+        accL += gz[b] * gL
+        assert np.allclose(full["grad_log_emit"][b, :n], gz[b] * ge, rtol=1e-12)
+    assert np.allclose(full["grad_L"], accL, rtol=1e-12)
+
+
+def test_pcfg_with_shared_left_right_matrix():
+    """L = R (the variant the paper's Sec. 2 footnote mentions) is just the same pointer passed twice."""
+    rng = np.random.default_rng(43)
+    lr, L, _, e = random_grammar(rng, 3, 2, 4)
+    Z = brute_force(lr, L, L, e)[0]
+    assert O.inside_sentence(lr, L, L, e)[0] == pytest.approx(math.log(Z), rel=1e-12)
+
+
+def test_rejects_single_word_sentence():
+    rng = np.random.default_rng(1)
+    lr, L, R, e = random_grammar(rng, 3, 2, 1)
+    with pytest.raises(ValueError):
+        O.inside_sentence(lr, L, R, e)
+
+
+def test_oracle_reproduces_frozen_tiny_fixture():
+    """Regression anchor: the fixture was written by tests/golden/make_golden.py from the oracle alone."""
+    import json
+    import os
+    from paper_2310_14997_amd import synth
+    with open(os.path.join(os.path.dirname(__file__), "golden", "tiny_oracle.json")) as f:
+        fix = json.load(f)
+    d = synth.make_inputs("tiny")
+    out = O.inside_backward(d["log_root"], d["L"], d["R"], d["log_emit"], d["lengths"])
+    assert np.allclose(out["logZ"], fix["logZ"], rtol=1e-12)
+    assert np.allclose(out["grad_log_root"], fix["grad_log_root"], rtol=1e-10)
+    assert np.allclose(out["grad_L"][0, :8], fix["grad_L_row0_first8"], rtol=1e-10)
+    assert np.allclose(out["grad_log_emit"][0, 0, :8], fix["grad_log_emit_b0_i0_first8"], rtol=1e-10)
+    assert fix["expected_left_rule_count"] == pytest.approx(4 * 9, rel=1e-12)  # B * (n - 1)
