@@ -1,0 +1,141 @@
+/*
+ * spcfg.h - C ABI of the MI355X (gfx950) inside / inside-backward library for simple PCFGs.
+ *
+ * A simple PCFG (paper Sec. 2) has rules S -> A, A -> B C, T -> w with the binary rule probability
+ * factored as pi(A -> B C) = L[A,B] * R[A,C].  A is a nonterminal (N of them); children B, C are
+ * nonterminals or preterminals (P of them); M = N + P.  Column order of L and R: nonterminal children
+ * in [0, N), preterminal children in [N, M).
+ *
+ * The library evaluates, for a batch of sentences, the inside recursion of Sec. 3.1
+ *     beta_ij = sum_{i<k<j} (L beta_ik) * (R beta_kj)        (elementwise product, fencepost spans)
+ * with base case beta_{i,i+1} = emission vector of token i, and Z = sum_A pi(S->A) beta_0n[A], in the
+ * hardware-oriented form of Sec. 3.2 (all spans of one width per launch, the L and R projections as one
+ * stacked matrix product, rescaling by the per-span maximum), and the reverse pass that Sec. 3.2
+ * ("Recomputation") sketches: nothing per split point is kept from the forward pass.
+ *
+ * Conventions
+ *   - "dev" pointers are device memory on the current HIP device, "host" pointers ordinary host memory.
+ *   - Matrices are row-major and dense: L, R are [N x M]; log_emit is [B x n_max x P].
+ *   - Every call only enqueues work on `hip_stream` (a hipStream_t, NULL = the default stream); results
+ *     are valid once the caller has synchronised that stream.  Host arrays (lengths) are consumed before
+ *     the call returns.  The library allocates no device memory; the caller owns every buffer.
+ *   - Errors that can be seen on the host (null pointer, bad shape, bad length, workspace too small) are
+ *     returned before anything is launched.  HIP runtime failures map to SPCFG_ERR_HIP.
+ *   - Results are deterministic: no floating-point atomics are used.
+ */
+#ifndef SPCFG_H
+#define SPCFG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  SPCFG_OK = 0,
+  SPCFG_ERR_ARG = -1,         /* null pointer, bad struct_size, negative size                      */
+  SPCFG_ERR_SHAPE = -2,       /* N, P, B or n_max outside the supported range or above capacity      */
+  SPCFG_ERR_LENGTH = -3,      /* some lengths[b] < 2 or > n_max (a tree needs the rule S -> A, A -> B C) */
+  SPCFG_ERR_WORKSPACE = -4,   /* workspace pointer misaligned or workspace_bytes too small            */
+  SPCFG_ERR_UNSUPPORTED = -5, /* precision / flag combination not implemented                         */
+  SPCFG_ERR_HIP = -6          /* a HIP runtime call failed (see spcfg_last_hip_error)                 */
+};
+
+enum { SPCFG_PRECISION_FP32 = 0, SPCFG_PRECISION_BF16 = 1 };
+
+enum {
+  SPCFG_FLAG_ACCUMULATE_GRADS = 1u /* add into grad_L / grad_R / grad_log_root instead of overwriting */
+};
+
+/* Plain-old-data configuration; set struct_size = sizeof(spcfg_config). */
+typedef struct {
+  uint32_t struct_size;
+  int32_t N;         /* number of nonterminals, >= 1                                              */
+  int32_t P;         /* number of preterminals, >= 1                                              */
+  int32_t max_B;     /* capacity: largest batch the workspace is sized for                        */
+  int32_t max_n;     /* capacity: largest sentence length the workspace is sized for              */
+  int32_t precision; /* SPCFG_PRECISION_FP32: fp32 operands on the matrix cores, fp32 accumulate;
+                        SPCFG_PRECISION_BF16: bf16 operands, fp32 accumulate (projections only)   */
+  uint32_t flags;    /* SPCFG_FLAG_*                                                              */
+} spcfg_config;
+
+/* Upper bound of the workspace needed for any batch with B <= max_B, every length <= max_n. */
+int spcfg_workspace_bytes(const spcfg_config* cfg, size_t* out_bytes);
+
+/* Exact workspace need of one batch (host `lengths`); never more than spcfg_workspace_bytes. */
+int spcfg_workspace_bytes_for(const spcfg_config* cfg, const int32_t* lengths, int32_t B, int32_t n_max,
+                              size_t* out_bytes);
+
+/*
+ * Inside pass (Sec. 3.1 recursion, Sec. 3.2 schedule): logZ[b] = log Z of sentence b.
+ *   log_root  dev [N]             log pi(S -> A); any log-weights, -inf allowed
+ *   L, R      dev [N x M]         non-negative weights (probability space), M = N + P
+ *   log_emit  dev [B x n_max x P] log pi(T -> w_{b,i}); positions i >= lengths[b] are never read
+ *   lengths   host [B]            2 <= lengths[b] <= n_max <= max_n
+ *   logZ      dev [B]             out; -inf for a sentence the grammar cannot derive
+ *   workspace dev, 256-byte aligned, >= spcfg_workspace_bytes_for(...) bytes.  After the call it holds
+ *             the chart (scaled inside vectors and their L/R projections for every span) that
+ *             spcfg_inside_backward needs; it must stay untouched until that call has run.
+ */
+int spcfg_inside(const spcfg_config* cfg, const float* log_root, const float* L, const float* R,
+                 const float* log_emit, const int32_t* lengths, int32_t B, int32_t n_max, float* logZ,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Reverse pass (Sec. 3.2 "Recomputation"; chain rule through the stacked projection): gradients of
+ * sum_b grad_logZ[b] * logZ[b].  Must follow spcfg_inside on the same inputs, workspace and stream order.
+ *   grad_logZ      dev [B] or NULL (= all ones)
+ *   grad_L, grad_R dev [N x M]  d/dL[A,B], d/dR[A,C] in probability space, summed over the batch;
+ *                               L*grad_L and R*grad_R are expected rule counts
+ *   grad_log_root  dev [N]      summed over the batch; with grad_logZ = 1 the root posteriors
+ *   grad_log_emit  dev [B x n_max x P]  per sentence (preterminal posteriors); 0 at padded positions
+ * Sentences with Z = 0 contribute nothing.  Gradients are overwritten unless SPCFG_FLAG_ACCUMULATE_GRADS
+ * (which applies to grad_L, grad_R, grad_log_root; grad_log_emit is always overwritten).
+ */
+int spcfg_inside_backward(const spcfg_config* cfg, const float* log_root, const float* L, const float* R,
+                          const float* log_emit, const int32_t* lengths, int32_t B, int32_t n_max,
+                          const float* grad_logZ, float* grad_L, float* grad_R, float* grad_log_root,
+                          float* grad_log_emit, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* spcfg_inside followed by spcfg_inside_backward on the same stream (one call for the fwd+bwd step). */
+int spcfg_inside_forward_backward(const spcfg_config* cfg, const float* log_root, const float* L,
+                                  const float* R, const float* log_emit, const int32_t* lengths, int32_t B,
+                                  int32_t n_max, const float* grad_logZ, float* logZ, float* grad_L,
+                                  float* grad_R, float* grad_log_root, float* grad_log_emit, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream);
+
+/* Static, never-NULL description of an error code. */
+const char* spcfg_strerror(int code);
+
+/* Text of the last HIP runtime error seen by this thread's calls ("" if none). */
+const char* spcfg_last_hip_error(void);
+
+/*
+ * Per-kernel-class timing.  While enabled, every launch is bracketed by HIP events on the caller's stream
+ * (this perturbs the schedule slightly, so whole-step timing should be taken with profiling disabled).
+ * spcfg_profile_read synchronises the recorded events, then fills, for class c in [0, SPCFG_PROF_CLASSES):
+ *   ms[c]      total device time of the class since spcfg_profile_enable(1)
+ *   launches[c] number of launches
+ *   work[c]    algorithmic work enqueued: flop for the GEMM classes, bytes for the others
+ * and resets the counters.  Arrays must hold SPCFG_PROF_CLASSES entries.
+ */
+enum {
+  SPCFG_PROF_SETUP = 0,      /* span plan, weight packing, leaf preparation                            */
+  SPCFG_PROF_GEMM_FWD = 1,   /* stacked [L;R] projection GEMMs of the inside pass                      */
+  SPCFG_PROF_SPLIT_FWD = 2,  /* split-point reduction of the inside pass                               */
+  SPCFG_PROF_ROOT = 3,       /* root reductions (forward and backward)                                 */
+  SPCFG_PROF_SPLIT_BWD = 4,  /* gather of parent adjoints times sibling projections                    */
+  SPCFG_PROF_GEMM_BWD = 5,   /* projection of adjoints back through [L;R]                              */
+  SPCFG_PROF_GEMM_GRAD = 6,  /* rule-gradient GEMMs (reduction over all spans)                         */
+  SPCFG_PROF_CLASSES = 7
+};
+int spcfg_profile_enable(int on);
+int spcfg_profile_read(double* ms, int64_t* launches, double* work);
+const char* spcfg_profile_class_name(int cls);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPCFG_H */

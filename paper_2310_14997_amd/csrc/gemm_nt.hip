@@ -1,0 +1,154 @@
+// fp32 MFMA GEMM for the stacked projections (Sec. 3.2: [eta | zeta] = [L;R] * beta for all spans of one
+// width at once) and for their reverse:  C[r][c] = sum_k A[r][k] * Bm[c][k], both operands K-contiguous.
+//
+// gfx950 mapping: 128x128x32 tile per 256-thread workgroup (4 wavefronts, 2x2, 64x64 each = 2x2 tiles of
+// v_mfma_f32_32x32x2_f32).  Global -> registers -> LDS with two LDS stages and one barrier per K-step.
+// Each lane fetches its MFMA operands as one 16-byte LDS read covering four K values; the K order inside
+// an 8-wide chunk is permuted identically for both operands (lanes 0-31 take k0..k0+3, lanes 32-63
+// k0+4..k0+7), which leaves the sum over K unchanged.
+#include "spcfg_internal.h"
+
+namespace spcfg {
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int LDT = BK + 4;  // LDS row stride in floats: 16-byte aligned rows, conflict-free 16-byte reads
+constexpr int kStage = (BM + BN) * LDT;
+constexpr size_t kLdsBytes = 2 * kStage * sizeof(float);
+
+template <int EPI>
+__global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g) {
+  extern __shared__ __align__(16) float lds[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int tiles_m = (g.rows + BM - 1) / BM;
+  const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
+  const int row0 = tile_m * BM, col0 = tile_n * BN;
+
+  // global -> register staging: each thread moves 4 float4 of A and 4 of Bm per K-step
+  const int lc4 = tid & 7, lr = tid >> 3;  // 8 float4 per tile row, 32 rows per pass
+  const float* ga[4];
+  const float* gb[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int ra = min(row0 + lr + 32 * q, g.rows - 1);
+    const int rb = min(col0 + lr + 32 * q, g.cols - 1);
+    ga[q] = g.A + (int64_t)ra * g.lda + lc4 * 4;
+    gb[q] = g.Bm + (int64_t)rb * g.ldb + lc4 * 4;
+  }
+  float4 ra4[4], rb4[4];
+  auto load_global = [&](int kt) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      ra4[q] = *reinterpret_cast<const float4*>(ga[q] + kt * BK);
+      rb4[q] = *reinterpret_cast<const float4*>(gb[q] + kt * BK);
+    }
+  };
+  auto store_lds = [&](int buf) {
+    float* as = lds + buf * kStage;
+    float* bs = as + BM * LDT;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      *reinterpret_cast<float4*>(as + (lr + 32 * q) * LDT + lc4 * 4) = ra4[q];
+      *reinterpret_cast<float4*>(bs + (lr + 32 * q) * LDT + lc4 * 4) = rb4[q];
+    }
+  };
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+
+  const int KT = g.K / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+
+  const int frag_row = lane & 31, frag_k = (lane >> 5) * 4;
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) load_global(kt + 1);
+    const float* as = lds + buf * kStage + (wm * 64 + frag_row) * LDT + frag_k;
+    const float* bs = lds + buf * kStage + BM * LDT + (wn * 64 + frag_row) * LDT + frag_k;
+#pragma unroll
+    for (int kc = 0; kc < BK / 8; ++kc) {
+      float4 a[2], b[2];
+      a[0] = *reinterpret_cast<const float4*>(as + kc * 8);
+      a[1] = *reinterpret_cast<const float4*>(as + 32 * LDT + kc * 8);
+      b[0] = *reinterpret_cast<const float4*>(bs + kc * 8);
+      b[1] = *reinterpret_cast<const float4*>(bs + 32 * LDT + kc * 8);
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].x, b[ni].x, acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].y, b[ni].y, acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].z, b[ni].z, acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].w, b[ni].w, acc[mi][ni], 0, 0, 0);
+        }
+    }
+    if (kt + 1 < KT) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue.  Accumulator layout of the 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4.
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int r = row0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      if (r >= g.rows) continue;
+      float scale = 1.0f;
+      int64_t drow = r;
+      if (EPI == NT_EPI_ROWSCALE) scale = g.rowscale[r];
+      if (EPI == NT_EPI_MASKROWS) {
+        if (g.rowmask[r]) continue;
+      }
+      if (EPI == NT_EPI_LEAF_EMIT) {
+        const int q = g.qexp[r];
+        scale = (q == kExpZero || q < -160) ? 0.0f : ldexpf(1.0f, min(q, 127));
+        drow = (int64_t)g.row_b[r] * g.n_max + g.row_i[r];
+      }
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int c = col0 + wn * 64 + ni * 32 + (lane & 31);
+        if (c >= g.cols) continue;
+        float val = acc[mi][ni][v] * scale;
+        if (EPI == NT_EPI_LEAF_EMIT) val *= g.E[(int64_t)r * g.lde + c];
+        g.C[drow * g.ldc + c] = val;
+      }
+    }
+  }
+}
+
+template <int EPI>
+void launch(const NtArgs& a, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+    attr_set = true;
+  }
+  const int tiles = ((a.rows + BM - 1) / BM) * ((a.cols + BN - 1) / BN);
+  hipLaunchKernelGGL(k_gemm_nt<EPI>, dim3(tiles), dim3(256), kLdsBytes, st, a);
+}
+
+}  // namespace
+
+void launch_gemm_nt(const NtArgs& a, hipStream_t st) {
+  if (a.rows <= 0 || a.cols <= 0) return;
+  switch (a.epilogue) {
+    case NT_EPI_ROWSCALE: launch<NT_EPI_ROWSCALE>(a, st); break;
+    case NT_EPI_MASKROWS: launch<NT_EPI_MASKROWS>(a, st); break;
+    default: launch<NT_EPI_LEAF_EMIT>(a, st); break;
+  }
+}
+
+}  // namespace spcfg

@@ -1,0 +1,129 @@
+// fp32 MFMA GEMM for the rule gradients:  d/d[L;R][a][b] = sum_s sc[s] * UV[s][a] * X[s][b], where s runs over
+// every span row, UV holds the scaled adjoints of [eta | zeta] and X the stored inside vectors (chain rule
+// through the stacked projection of Sec. 3.2).  Both operands are reduction-major, so tiles go to LDS as
+// they lie in memory ([s][a], [s][b]) and every MFMA operand is a conflict-free 4-byte LDS read.
+// 128x128 output tile, 32 span rows per step, 4 wavefronts (2x2) of 2x2 v_mfma_f32_32x32x2_f32 tiles.
+// The per-row power-of-two scale is applied to the A fragments in registers.
+#include "spcfg_internal.h"
+
+namespace spcfg {
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int TM = 128, TN = 128, TK = 32;
+constexpr int kStageT = (TM + TN) * TK + TK;  // A tile, B tile, scales
+constexpr size_t kLdsBytesT = 2 * kStageT * sizeof(float);
+
+__global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g) {
+  extern __shared__ __align__(16) float lds[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int tiles_a = (2 * g.Np) / TM;
+  const int tile_a = blockIdx.x % tiles_a, tile_b = blockIdx.x / tiles_a;
+  const int a0 = tile_a * TM, b0 = tile_b * TN;
+
+  const int lc4 = tid & 31, lr = tid >> 5;  // 32 float4 per tile row, 8 rows per pass
+  const bool bcol_ok = (b0 + lc4 * 4) < (int)g.ldb;  // ldb is the padded column count of X
+  float4 ra4[4], rb4[4];
+  float rsc = 0.0f;
+  auto load_global = [&](int64_t s0) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int64_t s = s0 + lr + 8 * q;
+      const bool ok = s < g.S;
+      const int64_t sc = ok ? s : g.S - 1;
+      ra4[q] = *reinterpret_cast<const float4*>(g.A + sc * g.lda + a0 + lc4 * 4);
+      rb4[q] = bcol_ok ? *reinterpret_cast<const float4*>(g.Bm + sc * g.ldb + b0 + lc4 * 4)
+                       : make_float4(0.f, 0.f, 0.f, 0.f);
+      if (!ok) {
+        ra4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        rb4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+    if (tid < TK) rsc = (s0 + tid < g.S) ? g.sc[s0 + tid] : 0.0f;
+  };
+  auto store_lds = [&](int buf) {
+    float* as = lds + buf * kStageT;
+    float* bs = as + TM * TK;
+    float* ss = bs + TN * TK;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      *reinterpret_cast<float4*>(as + (lr + 8 * q) * TM + lc4 * 4) = ra4[q];
+      *reinterpret_cast<float4*>(bs + (lr + 8 * q) * TN + lc4 * 4) = rb4[q];
+    }
+    if (tid < TK) ss[tid] = rsc;
+  };
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+
+  const int64_t KT = (g.S + TK - 1) / TK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+
+  const int fcol = lane & 31, fk = lane >> 5;
+  for (int64_t kt = 0; kt < KT; ++kt) {
+    const int buf = (int)(kt & 1);
+    if (kt + 1 < KT) load_global((kt + 1) * TK);
+    const float* as = lds + buf * kStageT + wm * 64 + fcol;
+    const float* bs = lds + buf * kStageT + TM * TK + wn * 64 + fcol;
+    const float* ss = lds + buf * kStageT + (TM + TN) * TK;
+#pragma unroll
+    for (int kk = 0; kk < TK; kk += 2) {
+      const int k = kk + fk;
+      const float s = ss[k];
+      const float a0v = as[k * TM] * s, a1v = as[k * TM + 32] * s;
+      const float b0v = bs[k * TN], b1v = bs[k * TN + 32];
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0v, b0v, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0v, b1v, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1v, b0v, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1v, b1v, acc[1][1], 0, 0, 0);
+    }
+    if (kt + 1 < KT) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int ar = a0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      const int half = ar >= g.Np;
+      const int arow = ar - half * g.Np;
+      if (arow >= g.N) continue;
+      float* dst = (half ? g.gR : g.gL) + (int64_t)arow * g.ldg + g.col0;
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int c = b0 + wn * 64 + ni * 32 + (lane & 31);
+        if (c >= g.cols) continue;
+        const float val = acc[mi][ni][v];
+        dst[c] = g.accumulate ? dst[c] + val : val;
+      }
+    }
+  }
+}
+
+}  // namespace
+
+void launch_gemm_tn(const TnArgs& a, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_tn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)kLdsBytesT);
+    attr_set = true;
+  }
+  const int tiles = ((2 * a.Np) / TM) * ((a.cols + TN - 1) / TN);
+  hipLaunchKernelGGL(k_gemm_tn, dim3(tiles), dim3(256), kLdsBytesT, st, a);
+}
+
+}  // namespace spcfg

@@ -1,0 +1,486 @@
+// Span plan, weight packing, leaf preparation, split-point reductions (forward and reverse) and root
+// reductions for the simple-PCFG inside pass on gfx950.  All kernels are deterministic (no atomics).
+#include "spcfg_internal.h"
+
+namespace spcfg {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ int wave_max_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Block-wide reductions through LDS; `red` needs one slot per wave (<= 16). All threads get the result.
+__device__ __forceinline__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  float r = red[0];
+  for (int i = 1; i < nw; ++i) r = fmaxf(r, red[i]);
+  return r;
+}
+__device__ __forceinline__ int block_max_i(int v, int* red) {
+  v = wave_max_i(v);
+  const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  int r = red[0];
+  for (int i = 1; i < nw; ++i) r = max(r, red[i]);
+  return r;
+}
+__device__ __forceinline__ double block_sum_d(double v, double* red) {
+  v = wave_sum_d(v);
+  const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  double r = 0.0;
+  for (int i = 0; i < nw; ++i) r += red[i];
+  return r;
+}
+
+// 2^d as a float for an integer d (0 below the fp32 range); exact.
+__device__ __forceinline__ float pow2i(int d) { return d < -160 ? 0.0f : ldexpf(1.0f, min(d, 127)); }
+
+__device__ __forceinline__ int add_exp(int a, int b) { return (a == kExpZero || b == kExpZero) ? kExpZero : a + b; }
+
+// ------------------------------------------------------------------------------------------ span plan
+// Width-synchronous schedule (Sec. 3.2, span-level parallelism): rows are ordered by width, sentence, start.
+__global__ void k_plan_rowbase(LenArg la, int B, int n_max, int32_t* __restrict__ lens,
+                               int32_t* __restrict__ rowbase, int32_t* __restrict__ rootrow) {
+  __shared__ int s_w[kMaxLen + 2];
+  for (int b = threadIdx.x; b < B; b += blockDim.x) lens[b] = la.v[b];
+  for (int w = 1 + threadIdx.x; w <= n_max; w += blockDim.x) {
+    int s = 0;
+    for (int b = 0; b < B; ++b) s += max(0, la.v[b] - w + 1);
+    s_w[w] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int w = 1; w <= n_max; ++w) {
+      int s = s_w[w];
+      s_w[w] = run;
+      run += s;
+    }
+  }
+  __syncthreads();
+  for (int w = 1 + threadIdx.x; w <= n_max; w += blockDim.x) {
+    int run = s_w[w];
+    for (int b = 0; b < B; ++b) {
+      const int n = la.v[b];
+      rowbase[w * B + b] = (n >= w) ? run : -1;
+      if (n == w) rootrow[b] = run;
+      run += max(0, n - w + 1);
+    }
+  }
+}
+
+__global__ void k_plan_rows(int B, const int32_t* __restrict__ lens, const int32_t* __restrict__ rowbase,
+                            int32_t* __restrict__ row_b, int32_t* __restrict__ row_i,
+                            int32_t* __restrict__ rootmask) {
+  const int w = blockIdx.x + 1, b = blockIdx.y;
+  const int n = lens[b];
+  if (w > n) return;
+  const int base = rowbase[w * B + b];
+  for (int i = threadIdx.x; i <= n - w; i += blockDim.x) {
+    row_b[base + i] = b;
+    row_i[base + i] = i;
+    rootmask[base + i] = (w == n) ? 1 : 0;
+  }
+}
+
+// ------------------------------------------------------------------------------------------ weights
+// Stacks [L;R] (Sec. 3.2, kernel fusion: one matrix product for both projections) into zero-padded,
+// K-contiguous operands: Wn [2Np x Np] / Wp [2Np x Pp] for the forward products and their transposes
+// Wtn [Np x 2Np] / Wtp [Pp x 2Np] for the reverse products.
+__global__ void k_pack_weights(const float* __restrict__ L, const float* __restrict__ R, int N, int P, int Np,
+                               int Pp, float* __restrict__ Wn, float* __restrict__ Wp, float* __restrict__ Wtn,
+                               float* __restrict__ Wtp) {
+  __shared__ float tile[32][33];
+  const float* src = blockIdx.z ? R : L;
+  const int M = N + P;
+  const int half = blockIdx.z * Np;
+  const int c0 = blockIdx.x * 32;  // padded column: [0,Np) nonterminal part, [Np, Np+Pp) preterminal part
+  const int a0 = blockIdx.y * 32;
+  const bool ppart = c0 >= Np;
+  const int cc0 = ppart ? c0 - Np : c0;
+  const int tx = threadIdx.x, ty = threadIdx.y;  // 32 x 8
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int a = a0 + ty + 8 * q, c = cc0 + tx;
+    float v = 0.0f;
+    if (a < N && c < (ppart ? P : N)) v = src[(int64_t)a * M + (ppart ? N + c : c)];
+    tile[ty + 8 * q][tx] = v;
+    if (ppart) Wp[(int64_t)(half + a) * Pp + c] = v; else Wn[(int64_t)(half + a) * Np + c] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int c = cc0 + ty + 8 * q, a = a0 + tx;
+    const float v = tile[tx][ty + 8 * q];
+    if (ppart) Wtp[(int64_t)c * (2 * Np) + half + a] = v; else Wtn[(int64_t)c * (2 * Np) + half + a] = v;
+  }
+}
+
+// ------------------------------------------------------------------------------------------ leaves
+// Base case (Sec. 3.1): the inside vector of token i is its emission vector; it is stored as
+// exp(e - max e) with the maximum kept aside (it re-enters only in log Z).
+__global__ void k_leaf_prep(const float* __restrict__ log_emit, int P, int Pp, int n_max,
+                            const int32_t* __restrict__ row_b, const int32_t* __restrict__ row_i,
+                            float* __restrict__ leafE, float* __restrict__ xs, int32_t* __restrict__ eexp,
+                            int32_t* __restrict__ mexp, float* __restrict__ fscale) {
+  __shared__ float red[16];
+  const int r = blockIdx.x;
+  const float* e = log_emit + ((int64_t)row_b[r] * n_max + row_i[r]) * P;
+  float mx = -INFINITY;
+  for (int t = threadIdx.x; t < P; t += blockDim.x) mx = fmaxf(mx, e[t]);
+  mx = block_max(mx, red);
+  const bool dead = !(mx > -INFINITY);
+  const float x = dead ? 0.0f : mx;
+  float* out = leafE + (int64_t)r * Pp;
+  for (int t = threadIdx.x; t < Pp; t += blockDim.x) out[t] = (t < P && !dead) ? expf(e[t] - x) : 0.0f;
+  if (threadIdx.x == 0) {
+    xs[r] = x;
+    mexp[r] = 0;
+    eexp[r] = dead ? kExpZero : 1;  // max entry is exactly 1 = 0.5 * 2^1
+    fscale[r] = dead ? 0.0f : 0.5f;
+  }
+}
+
+// ------------------------------------------------------------------------------------------ forward split
+// beta_ij = sum_k eta_ik * zeta_kj (Sec. 3.1 vector form) for every span of one width, in the scaled
+// representation: T = sum_k 2^(d_k - m) etat_ik * zetat_kj with d_k = e_ik + e_kj, m = max_k d_k.
+// One block per span; split-point coefficients are staged in LDS, the per-span maximum (the rescaling of
+// Sec. 3.2) is a wavefront reduction, and nothing per split point goes to HBM.
+__global__ void __launch_bounds__(kThreads)
+k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __restrict__ rowbase,
+            const int32_t* __restrict__ row_b, const int32_t* __restrict__ row_i, const float* __restrict__ HZ,
+            float* __restrict__ T, int32_t* __restrict__ eexp, int32_t* __restrict__ mexp,
+            float* __restrict__ fscale) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* s_c = reinterpret_cast<float*>(smem);                 // [w-1]
+  int32_t* s_l = reinterpret_cast<int32_t*>(s_c + (w - 1));    // [w-1] row of the left child
+  int32_t* s_r = s_l + (w - 1);                                // [w-1] row of the right child
+  __shared__ float redf[16];
+  __shared__ int redi[16];
+
+  const int64_t r = row0 + blockIdx.x;
+  const int b = row_b[r], i = row_i[r];
+  int dmax = kExpZero;
+  for (int k = 1 + threadIdx.x; k < w; k += blockDim.x) {
+    const int lr = rowbase[k * B + b] + i;            // span (i, i+k)
+    const int rr = rowbase[(w - k) * B + b] + i + k;  // span (i+k, i+w)
+    s_l[k - 1] = lr;
+    s_r[k - 1] = rr;
+    const int d = add_exp(eexp[lr], eexp[rr]);
+    s_c[k - 1] = __int_as_float(d);
+    dmax = max(dmax, d);
+  }
+  const int m = block_max_i(dmax, redi);  // (contains the barrier that publishes s_l, s_r, s_c)
+  for (int k = threadIdx.x; k < w - 1; k += blockDim.x) {
+    const int d = __float_as_int(s_c[k]);
+    s_c[k] = (d == kExpZero) ? 0.0f : pow2i(d - m);
+  }
+  __syncthreads();
+
+  const int64_t ld = 2 * (int64_t)Np;
+  float* out = T + (r - S1) * Np;
+  float tmax = 0.0f;
+  for (int a = threadIdx.x * 4; a < Np; a += blockDim.x * 4) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int k = 0; k < w - 1; ++k) {
+      const float c = s_c[k];
+      const float4 h = *reinterpret_cast<const float4*>(HZ + s_l[k] * ld + a);
+      const float4 z = *reinterpret_cast<const float4*>(HZ + s_r[k] * ld + Np + a);
+      acc.x = fmaf(c * h.x, z.x, acc.x);
+      acc.y = fmaf(c * h.y, z.y, acc.y);
+      acc.z = fmaf(c * h.z, z.z, acc.z);
+      acc.w = fmaf(c * h.w, z.w, acc.w);
+    }
+    *reinterpret_cast<float4*>(out + a) = acc;
+    tmax = fmaxf(tmax, fmaxf(fmaxf(acc.x, acc.y), fmaxf(acc.z, acc.w)));
+  }
+  tmax = block_max(tmax, redf);
+  if (threadIdx.x == 0) {
+    int f = 0;
+    const bool dead = !(tmax > 0.0f) || m == kExpZero;
+    if (!dead) { (void)frexpf(tmax, &f); f = max(f, -126); }
+    mexp[r] = dead ? kExpZero : m;
+    eexp[r] = dead ? kExpZero : m + f;
+    fscale[r] = dead ? 0.0f : pow2i(-f);
+  }
+}
+
+// ------------------------------------------------------------------------------------------ root
+// Z = sum_A pi(S->A) beta_0n[A] (rule S -> A, Sec. 2).
+__global__ void k_root_fwd(int B, int N, int Np, int64_t S1, const int32_t* __restrict__ lens,
+                           const int32_t* __restrict__ rowbase, const int32_t* __restrict__ rootrow,
+                           const float* __restrict__ log_root, const float* __restrict__ T,
+                           const int32_t* __restrict__ eexp, const float* __restrict__ fscale,
+                           const float* __restrict__ xs, float* __restrict__ logZ, float* __restrict__ ztil,
+                           float* __restrict__ rmaxs) {
+  __shared__ float redf[16];
+  __shared__ double redd[16];
+  const int b = blockIdx.x;
+  const int64_t r = rootrow[b];
+  float rm = -INFINITY;
+  for (int a = threadIdx.x; a < N; a += blockDim.x) rm = fmaxf(rm, log_root[a]);
+  rm = block_max(rm, redf);
+  const bool deadroot = !(rm > -INFINITY);
+  const float rmx = deadroot ? 0.0f : rm;
+  const float* t = T + (r - S1) * Np;
+  const float fs = fscale[r];
+  double z = 0.0;
+  for (int a = threadIdx.x; a < N; a += blockDim.x) z += (double)expf(log_root[a] - rmx) * (double)(t[a] * fs);
+  z = block_sum_d(z, redd);
+  double sx = 0.0;
+  const int n = lens[b];
+  const int leaf0 = rowbase[1 * B + b];
+  for (int i = threadIdx.x; i < n; i += blockDim.x) sx += (double)xs[leaf0 + i];
+  sx = block_sum_d(sx, redd);
+  if (threadIdx.x == 0) {
+    const int e = eexp[r];
+    const bool dead = deadroot || e == kExpZero || !(z > 0.0);
+    logZ[b] = dead ? -INFINITY : (float)((double)rmx + log(z) + (double)e * 0.6931471805599453094 + sx);
+    ztil[b] = dead ? 0.0f : (float)z;
+    rmaxs[b] = rmx;
+  }
+}
+
+// d logZ / d beta_0n[A] = pi(S->A) / Z.  Scaled adjoint of the root span: BH = g * r[A] / Zt, exponent -e_0n.
+__global__ void k_root_bwd(int N, int Np, int64_t S1, const int32_t* __restrict__ rootrow,
+                           const float* __restrict__ log_root, const float* __restrict__ grad_logZ,
+                           const float* __restrict__ ztil, const float* __restrict__ rmaxs,
+                           const int32_t* __restrict__ eexp, float* __restrict__ BH, float* __restrict__ UV,
+                           int32_t* __restrict__ qexp, float* __restrict__ gsc) {
+  const int b = blockIdx.x;
+  const int64_t r = rootrow[b];
+  const float g = grad_logZ ? grad_logZ[b] : 1.0f;
+  const float zt = ztil[b];
+  const bool dead = !(zt > 0.0f) || g == 0.0f;
+  const float s = dead ? 0.0f : g / zt;
+  const float rmx = rmaxs[b];
+  float* bh = BH + (r - S1) * Np;
+  float* uv = UV + r * 2 * (int64_t)Np;
+  for (int a = threadIdx.x; a < Np; a += blockDim.x) {
+    bh[a] = (a < N && !dead) ? s * expf(log_root[a] - rmx) : 0.0f;
+    uv[a] = 0.0f;
+    uv[Np + a] = 0.0f;
+  }
+  if (threadIdx.x == 0) {
+    qexp[r] = dead ? kExpZero : -eexp[r];
+    gsc[r] = 0.0f;
+  }
+}
+
+// grad_log_root[A] = sum_b g_b * pi(S->A) beta_0n[A] / Z_b  (root posteriors); fixed summation order.
+__global__ void k_grad_log_root(int B, int N, int Np, int64_t S1, const int32_t* __restrict__ rootrow,
+                                const float* __restrict__ log_root, const float* __restrict__ grad_logZ,
+                                const float* __restrict__ ztil, const float* __restrict__ rmaxs,
+                                const float* __restrict__ T, const float* __restrict__ fscale,
+                                float* __restrict__ grad_log_root, int accumulate) {
+  const int a = blockIdx.x * blockDim.x + threadIdx.x;
+  if (a >= N) return;
+  const float lr = log_root[a];
+  float acc = 0.0f;
+  for (int b = 0; b < B; ++b) {
+    const float zt = ztil[b];
+    if (!(zt > 0.0f)) continue;
+    const int64_t r = rootrow[b];
+    const float g = grad_logZ ? grad_logZ[b] : 1.0f;
+    acc += g * expf(lr - rmaxs[b]) * (T[(r - S1) * Np + a] * fscale[r]) / zt;
+  }
+  grad_log_root[a] = accumulate ? grad_log_root[a] + acc : acc;
+}
+
+// ------------------------------------------------------------------------------------------ reverse split
+// Reverse of the split-point sum in gather form (Sec. 3.2 "Recomputation": the per-split products are
+// recomputed from the stored projections, never saved).  For the span (i,j):
+//   adjoint of eta_ij  = sum_{j'>j} adj(beta_ij') * zeta_jj'     (as the left child of (i,j'))
+//   adjoint of zeta_ij = sum_{i'<i} adj(beta_i'j) * eta_i'i      (as the right child of (i',j))
+// Both are written with one common exponent so that they can be projected back through [L;R] together.
+__global__ void __launch_bounds__(kThreads)
+k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __restrict__ lens,
+            const int32_t* __restrict__ rowbase, const int32_t* __restrict__ row_b,
+            const int32_t* __restrict__ row_i, const int32_t* __restrict__ rootmask,
+            const float* __restrict__ HZ, const float* __restrict__ BH, const int32_t* __restrict__ eexp,
+            const int32_t* __restrict__ mexp, float* __restrict__ UV, int32_t* __restrict__ qexp,
+            float* __restrict__ gsc) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ float redf[16];
+  __shared__ int redi[16];
+  const int64_t r = row0 + blockIdx.x;
+  if (rootmask[r]) return;  // the root span has no parent; its adjoint comes from k_root_bwd
+  const int b = row_b[r], i = row_i[r];
+  const int n = lens[b];
+  const int j = i + w;
+  const int nl = n - j;  // parents (i, j'), j' = j+1..n   (this span is their left child)
+  const int nr = i;      // parents (i', j), i' = 0..i-1   (this span is their right child)
+  const int nt = nl + nr;
+  float* s_c = reinterpret_cast<float*>(smem);             // [nt]
+  int32_t* s_p = reinterpret_cast<int32_t*>(s_c + nt);     // [nt] parent row (index into BH: row - S1)
+  int32_t* s_s = s_p + nt;                                 // [nt] sibling row
+
+  int dmax = kExpZero;
+  for (int t = threadIdx.x; t < nt; t += blockDim.x) {
+    int pr, sr;
+    if (t < nl) {
+      const int jp = j + 1 + t;
+      pr = rowbase[(jp - i) * B + b] + i;   // parent (i, j')
+      sr = rowbase[(jp - j) * B + b] + j;   // sibling (j, j'), used through its zeta
+    } else {
+      const int ip = t - nl;
+      pr = rowbase[(j - ip) * B + b] + ip;  // parent (i', j)
+      sr = rowbase[(i - ip) * B + b] + ip;  // sibling (i', i), used through its eta
+    }
+    s_p[t] = pr - (int)S1;
+    s_s[t] = sr;
+    const int d = add_exp(qexp[pr], eexp[sr]);
+    s_c[t] = __int_as_float(d);
+    dmax = max(dmax, d);
+  }
+  const int m = block_max_i(dmax, redi);
+  for (int t = threadIdx.x; t < nt; t += blockDim.x) {
+    const int d = __float_as_int(s_c[t]);
+    s_c[t] = (d == kExpZero) ? 0.0f : pow2i(d - m);
+  }
+  __syncthreads();
+
+  const int64_t ld = 2 * (int64_t)Np;
+  float* out = UV + r * ld;
+  float amax = 0.0f;
+  for (int a = threadIdx.x * 4; a < Np; a += blockDim.x * 4) {
+    float4 u = make_float4(0.f, 0.f, 0.f, 0.f), v = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int t = 0; t < nl; ++t) {
+      const float c = s_c[t];
+      const float4 g = *reinterpret_cast<const float4*>(BH + (int64_t)s_p[t] * Np + a);
+      const float4 z = *reinterpret_cast<const float4*>(HZ + s_s[t] * ld + Np + a);
+      u.x = fmaf(c * g.x, z.x, u.x);
+      u.y = fmaf(c * g.y, z.y, u.y);
+      u.z = fmaf(c * g.z, z.z, u.z);
+      u.w = fmaf(c * g.w, z.w, u.w);
+    }
+#pragma unroll 4
+    for (int t = nl; t < nt; ++t) {
+      const float c = s_c[t];
+      const float4 g = *reinterpret_cast<const float4*>(BH + (int64_t)s_p[t] * Np + a);
+      const float4 h = *reinterpret_cast<const float4*>(HZ + s_s[t] * ld + a);
+      v.x = fmaf(c * g.x, h.x, v.x);
+      v.y = fmaf(c * g.y, h.y, v.y);
+      v.z = fmaf(c * g.z, h.z, v.z);
+      v.w = fmaf(c * g.w, h.w, v.w);
+    }
+    // keep the unscaled sums in the output row; they are rescaled below once the block maximum is known
+    *reinterpret_cast<float4*>(out + a) = u;
+    *reinterpret_cast<float4*>(out + Np + a) = v;
+    amax = fmaxf(amax, fmaxf(fmaxf(fabsf(u.x), fabsf(u.y)), fmaxf(fabsf(u.z), fabsf(u.w))));
+    amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+  }
+  amax = block_max(amax, redf);  // barrier inside: every thread's stores above are its own, re-read below
+  const bool dead = !(amax > 0.0f) || m == kExpZero;
+  int f = 0;
+  if (!dead) { (void)frexpf(amax, &f); f = max(f, -126); }
+  const float sc = dead ? 0.0f : pow2i(-f);
+  for (int a = threadIdx.x * 4; a < Np; a += blockDim.x * 4) {
+    float4 u = *reinterpret_cast<float4*>(out + a);
+    float4 v = *reinterpret_cast<float4*>(out + Np + a);
+    u.x *= sc; u.y *= sc; u.z *= sc; u.w *= sc;
+    v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
+    *reinterpret_cast<float4*>(out + a) = u;
+    *reinterpret_cast<float4*>(out + Np + a) = v;
+  }
+  if (threadIdx.x == 0) {
+    const int q = dead ? kExpZero : m + f;
+    qexp[r] = q;
+    // scale that turns UV[r] (x) (stored inside vector of the row) into its contribution to dZ/d[L;R]
+    const int me = (r < S1) ? 0 : mexp[r];
+    gsc[r] = (dead || me == kExpZero) ? 0.0f : pow2i(max(q + me, -160));
+  }
+}
+
+// grad_log_emit is zero at padded token positions.
+__global__ void k_zero_pad_emit(int P, int n_max, const int32_t* __restrict__ lens, float* __restrict__ g) {
+  const int b = blockIdx.x;
+  const int n = lens[b];
+  float* base = g + ((int64_t)b * n_max + n) * P;
+  const int64_t cnt = (int64_t)(n_max - n) * P;
+  for (int64_t t = threadIdx.x; t < cnt; t += blockDim.x) base[t] = 0.0f;
+}
+
+int pick_threads(int Np) {
+  int t = Np / 4;
+  if (t > kThreads) t = kThreads;
+  if (t < 64) t = 64;
+  return (t + 63) / 64 * 64;
+}
+
+}  // namespace
+
+void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_t st) {
+  hipLaunchKernelGGL(k_plan_rowbase, dim3(1), dim3(256), 0, st, lens, ly.B, ly.n_max, p.lens, p.rowbase, p.rootrow);
+  hipLaunchKernelGGL(k_plan_rows, dim3(ly.n_max, ly.B), dim3(64), 0, st, ly.B, p.lens, p.rowbase, p.row_b, p.row_i,
+                     p.rootmask);
+}
+
+void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const float* R, hipStream_t st) {
+  dim3 grid((ly.Np + ly.Pp) / 32, ly.Np / 32, 2);
+  hipLaunchKernelGGL(k_pack_weights, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp, p.Wn, p.Wp, p.Wtn,
+                     p.Wtp);
+}
+
+void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hipStream_t st) {
+  hipLaunchKernelGGL(k_leaf_prep, dim3((unsigned)ly.S1), dim3(256), 0, st, log_emit, ly.P, ly.Pp, ly.n_max, p.row_b,
+                     p.row_i, p.leafE, p.xs, p.eexp, p.mexp, p.fscale);
+}
+
+void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
+  const size_t sh = (size_t)(w - 1) * 12;
+  hipLaunchKernelGGL(k_split_fwd, dim3((unsigned)rows), dim3(pick_threads(ly.Np)), sh, st, w, row0, ly.B, ly.Np,
+                     ly.S1, p.rowbase, p.row_b, p.row_i, p.HZ, p.T, p.eexp, p.mexp, p.fscale);
+}
+
+void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st) {
+  hipLaunchKernelGGL(k_root_fwd, dim3(ly.B), dim3(256), 0, st, ly.B, ly.N, ly.Np, ly.S1, p.lens, p.rowbase,
+                     p.rootrow, log_root, p.T, p.eexp, p.fscale, p.xs, logZ, p.ztil, p.rmax);
+}
+
+void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, const float* grad_logZ,
+                     float* grad_log_root, int accumulate, hipStream_t st) {
+  hipLaunchKernelGGL(k_root_bwd, dim3(ly.B), dim3(256), 0, st, ly.N, ly.Np, ly.S1, p.rootrow, log_root, grad_logZ,
+                     p.ztil, p.rmax, p.eexp, p.BH, p.UV, p.qexp, p.gsc);
+  hipLaunchKernelGGL(k_grad_log_root, dim3((ly.N + 255) / 256), dim3(256), 0, st, ly.B, ly.N, ly.Np, ly.S1,
+                     p.rootrow, log_root, grad_logZ, p.ztil, p.rmax, p.T, p.fscale, grad_log_root, accumulate);
+}
+
+void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
+  const size_t sh = (size_t)ly.n_max * 12;
+  hipLaunchKernelGGL(k_split_bwd, dim3((unsigned)rows), dim3(pick_threads(ly.Np)), sh, st, w, row0, ly.B, ly.Np,
+                     ly.S1, p.lens, p.rowbase, p.row_b, p.row_i, p.rootmask, p.HZ, p.BH, p.eexp, p.mexp, p.UV,
+                     p.qexp, p.gsc);
+}
+
+void launch_zero_pad_emit(const Layout& ly, const Ptrs& p, float* grad_log_emit, hipStream_t st) {
+  hipLaunchKernelGGL(k_zero_pad_emit, dim3(ly.B), dim3(256), 0, st, ly.P, ly.n_max, p.lens, grad_log_emit);
+}
+
+}  // namespace spcfg

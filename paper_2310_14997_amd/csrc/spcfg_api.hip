@@ -1,0 +1,379 @@
+// C ABI of libspcfg: argument checks, workspace layout, the width-synchronous schedule (Sec. 3.2,
+// span-level parallelism: one launch handles every span of one width across the batch) and optional
+// per-kernel-class timing with HIP events.
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "spcfg_internal.h"
+
+namespace spcfg {
+
+namespace {
+
+thread_local char g_hip_err[256] = "";
+
+struct Plan {            // host-side copy of the span schedule
+  std::vector<int64_t> off;   // off[w] = first row of width w (1-based), off[n_max+1] = Sall
+  std::vector<int64_t> cnt;   // cnt[w] = number of spans of width w
+  LenArg lens;
+};
+
+size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int check_cfg(const spcfg_config* c) {
+  if (!c || c->struct_size != sizeof(spcfg_config)) return SPCFG_ERR_ARG;
+  if (c->N < 1 || c->P < 1 || c->N > (1 << 16) || c->P > (1 << 16)) return SPCFG_ERR_SHAPE;
+  if (c->max_B < 1 || c->max_B > kMaxB || c->max_n < 2 || c->max_n > kMaxLen) return SPCFG_ERR_SHAPE;
+  if (c->precision != SPCFG_PRECISION_FP32) return SPCFG_ERR_UNSUPPORTED;
+  if (c->flags & ~(uint32_t)SPCFG_FLAG_ACCUMULATE_GRADS) return SPCFG_ERR_UNSUPPORTED;
+  return SPCFG_OK;
+}
+
+// Byte layout of the workspace for a batch with S1 leaf rows and S2 rows of width >= 2.
+Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2) {
+  Layout ly{};
+  ly.N = N; ly.P = P; ly.B = B; ly.n_max = n_max;
+  ly.Np = round_up(N, kPad);
+  ly.Pp = round_up(P, kPad);
+  ly.S1 = S1; ly.S2 = S2; ly.Sall = S1 + S2;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+  const size_t i4 = sizeof(int32_t), f4 = sizeof(float);
+  ly.lens = take(i4 * B);
+  ly.rowbase = take(i4 * (size_t)(n_max + 1) * B);
+  ly.rootrow = take(i4 * B);
+  ly.ztil = take(f4 * B);
+  ly.rmax = take(f4 * B);
+  ly.row_b = take(i4 * ly.Sall);
+  ly.row_i = take(i4 * ly.Sall);
+  ly.rootmask = take(i4 * ly.Sall);
+  ly.eexp = take(i4 * ly.Sall);
+  ly.mexp = take(i4 * ly.Sall);
+  ly.qexp = take(i4 * ly.Sall);
+  ly.fscale = take(f4 * ly.Sall);
+  ly.gsc = take(f4 * ly.Sall);
+  ly.xs = take(f4 * S1);
+  ly.Wn = take(f4 * 2 * (size_t)ly.Np * ly.Np);
+  ly.Wp = take(f4 * 2 * (size_t)ly.Np * ly.Pp);
+  ly.Wtn = take(f4 * 2 * (size_t)ly.Np * ly.Np);
+  ly.Wtp = take(f4 * 2 * (size_t)ly.Np * ly.Pp);
+  ly.leafE = take(f4 * (size_t)S1 * ly.Pp);
+  ly.T = take(f4 * (size_t)S2 * ly.Np);
+  ly.BH = take(f4 * (size_t)S2 * ly.Np);
+  ly.HZ = take(f4 * (size_t)ly.Sall * 2 * ly.Np);
+  ly.UV = take(f4 * (size_t)ly.Sall * 2 * ly.Np);
+  ly.total = o;
+  return ly;
+}
+
+Ptrs resolve(const Layout& ly, void* ws) {
+  unsigned char* b = static_cast<unsigned char*>(ws);
+  Ptrs p;
+  p.lens = (int32_t*)(b + ly.lens); p.rowbase = (int32_t*)(b + ly.rowbase); p.rootrow = (int32_t*)(b + ly.rootrow);
+  p.row_b = (int32_t*)(b + ly.row_b); p.row_i = (int32_t*)(b + ly.row_i); p.rootmask = (int32_t*)(b + ly.rootmask);
+  p.eexp = (int32_t*)(b + ly.eexp); p.mexp = (int32_t*)(b + ly.mexp); p.qexp = (int32_t*)(b + ly.qexp);
+  p.fscale = (float*)(b + ly.fscale); p.gsc = (float*)(b + ly.gsc); p.xs = (float*)(b + ly.xs);
+  p.ztil = (float*)(b + ly.ztil); p.rmax = (float*)(b + ly.rmax);
+  p.leafE = (float*)(b + ly.leafE); p.T = (float*)(b + ly.T); p.HZ = (float*)(b + ly.HZ);
+  p.UV = (float*)(b + ly.UV); p.BH = (float*)(b + ly.BH);
+  p.Wn = (float*)(b + ly.Wn); p.Wp = (float*)(b + ly.Wp); p.Wtn = (float*)(b + ly.Wtn); p.Wtp = (float*)(b + ly.Wtp);
+  return p;
+}
+
+int make_plan(const spcfg_config* cfg, const int32_t* lengths, int B, int n_max, Plan* plan, Layout* ly) {
+  if (!lengths) return SPCFG_ERR_ARG;
+  if (B < 1 || B > cfg->max_B || n_max < 2 || n_max > cfg->max_n) return SPCFG_ERR_SHAPE;
+  for (int b = 0; b < B; ++b)
+    if (lengths[b] < 2 || lengths[b] > n_max) return SPCFG_ERR_LENGTH;
+  plan->off.assign(n_max + 2, 0);
+  plan->cnt.assign(n_max + 2, 0);
+  for (int b = 0; b < B; ++b) {
+    plan->lens.v[b] = lengths[b];
+    for (int w = 1; w <= lengths[b]; ++w) plan->cnt[w] += lengths[b] - w + 1;
+  }
+  int64_t run = 0;
+  for (int w = 1; w <= n_max + 1; ++w) {
+    plan->off[w] = run;
+    if (w <= n_max) run += plan->cnt[w];
+  }
+  const int64_t S1 = plan->cnt[1], Sall = run;
+  if (Sall >= (int64_t)1 << 30) return SPCFG_ERR_SHAPE;
+  *ly = make_layout(cfg->N, cfg->P, B, n_max, S1, Sall - S1);
+  return SPCFG_OK;
+}
+
+// ---- profiling -------------------------------------------------------------------------------------
+struct Prof {
+  bool on = false;
+  struct Rec { hipEvent_t a, b; int cls; };
+  std::vector<Rec> recs;
+  std::vector<hipEvent_t> pool;
+  double work[SPCFG_PROF_CLASSES] = {0};
+  int64_t launches[SPCFG_PROF_CLASSES] = {0};
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+} g_prof;
+
+struct Scope {  // brackets the launches of one kernel class with events when profiling is enabled
+  hipStream_t st; int cls; hipEvent_t a = nullptr, b = nullptr;
+  Scope(hipStream_t s, int c, double work, int nlaunch = 1) : st(s), cls(c) {
+    if (!g_prof.on) return;
+    a = g_prof.get(); b = g_prof.get();
+    g_prof.work[c] += work;
+    g_prof.launches[c] += nlaunch;
+    if (a) (void)hipEventRecord(a, st);
+  }
+  ~Scope() {
+    if (!g_prof.on || !a || !b) return;
+    (void)hipEventRecord(b, st);
+    g_prof.recs.push_back({a, b, cls});
+  }
+};
+
+int hip_status() {
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return SPCFG_OK;
+  snprintf(g_hip_err, sizeof(g_hip_err), "%s", hipGetErrorString(e));
+  return SPCFG_ERR_HIP;
+}
+
+int check_ws(const Layout& ly, void* ws, size_t bytes) {
+  if (!ws) return SPCFG_ERR_ARG;
+  if (((uintptr_t)ws & 255) != 0 || bytes < ly.total) return SPCFG_ERR_WORKSPACE;
+  return SPCFG_OK;
+}
+
+int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const Ptrs& p, const float* log_root,
+            const float* L, const float* R, const float* log_emit, float* logZ, hipStream_t st) {
+  const int n_max = ly.n_max;
+  const int64_t Np = ly.Np, Pp = ly.Pp;
+  {
+    Scope s(st, SPCFG_PROF_SETUP, 4.0 * 2 * (double)ly.N * (ly.N + ly.P) * 3 + 8.0 * ly.S1 * ly.P, 4);
+    launch_plan(ly, p, plan.lens, st);
+    launch_pack_weights(ly, p, L, R, st);
+    launch_leaf_prep(ly, p, log_emit, st);
+  }
+  {  // width 1: [eta | zeta] = [L_P ; R_P] * emission vector
+    Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.P * ly.S1);
+    NtArgs a{};
+    a.A = p.leafE; a.lda = Pp; a.Bm = p.Wp; a.ldb = Pp; a.C = p.HZ; a.ldc = 2 * Np;
+    a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
+    a.epilogue = NT_EPI_ROWSCALE; a.rowscale = p.fscale;
+    launch_gemm_nt(a, st);
+  }
+  for (int w = 2; w <= n_max; ++w) {
+    const int64_t row0 = plan.off[w], rows = plan.cnt[w];
+    if (rows == 0) continue;
+    {
+      Scope s(st, SPCFG_PROF_SPLIT_FWD, 4.0 * ly.N * (double)rows * (2.0 * (w - 1) + 1.0));
+      launch_split_fwd(ly, p, w, row0, rows, st);
+    }
+    if (w == n_max) break;  // every span of the largest width is a root span: never a child, not projected
+    Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.N * rows);
+    NtArgs a{};
+    a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
+    a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
+    a.rows = (int)rows; a.cols = (int)(2 * Np); a.K = (int)Np;
+    a.epilogue = NT_EPI_ROWSCALE; a.rowscale = p.fscale + row0;
+    launch_gemm_nt(a, st);
+  }
+  {
+    Scope s(st, SPCFG_PROF_ROOT, 8.0 * ly.N * ly.B);
+    launch_root_fwd(ly, p, log_root, logZ, st);
+  }
+  (void)cfg;
+  return hip_status();
+}
+
+int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const Ptrs& p, const float* log_root,
+             const float* grad_logZ, float* grad_L, float* grad_R, float* grad_log_root, float* grad_log_emit,
+             hipStream_t st) {
+  const int n_max = ly.n_max;
+  const int64_t Np = ly.Np, Pp = ly.Pp;
+  const int acc = (cfg->flags & SPCFG_FLAG_ACCUMULATE_GRADS) ? 1 : 0;
+  {
+    Scope s(st, SPCFG_PROF_ROOT, 16.0 * ly.N * ly.B, 3);
+    launch_root_bwd(ly, p, log_root, grad_logZ, grad_log_root, acc, st);
+    launch_zero_pad_emit(ly, p, grad_log_emit, st);
+  }
+  for (int w = n_max - 1; w >= 1; --w) {  // spans of width n_max are all roots
+    const int64_t row0 = plan.off[w], rows = plan.cnt[w];
+    if (rows == 0) continue;
+    {
+      // per span: (n - w) terms, two vector reads each, plus the two output vectors
+      double terms = 0;
+      for (int b = 0; b < ly.B; ++b) {
+        const int n = plan.lens.v[b];
+        if (n > w) terms += (double)(n - w + 1) * (n - w);
+      }
+      Scope s(st, SPCFG_PROF_SPLIT_BWD, 4.0 * ly.N * (2.0 * terms + 2.0 * rows));
+      launch_split_bwd(ly, p, w, row0, rows, st);
+    }
+    NtArgs a{};
+    a.A = p.UV + row0 * 2 * Np; a.lda = 2 * Np; a.K = (int)(2 * Np); a.rows = (int)rows;
+    if (w >= 2) {
+      Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.N * rows);
+      a.Bm = p.Wtn; a.ldb = 2 * Np; a.C = p.BH + (row0 - ly.S1) * Np; a.ldc = Np; a.cols = (int)Np;
+      a.epilogue = NT_EPI_MASKROWS; a.rowmask = p.rootmask + row0;
+      launch_gemm_nt(a, st);
+    } else {
+      Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.P * rows);
+      a.Bm = p.Wtp; a.ldb = 2 * Np; a.C = grad_log_emit; a.ldc = ly.P; a.cols = ly.P;
+      a.epilogue = NT_EPI_LEAF_EMIT; a.E = p.leafE; a.lde = Pp; a.qexp = p.qexp;
+      a.row_b = p.row_b; a.row_i = p.row_i; a.n_max = n_max;
+      launch_gemm_nt(a, st);
+    }
+  }
+  {
+    Scope s(st, SPCFG_PROF_GEMM_GRAD, 4.0 * ly.N * ((double)ly.N * ly.S2 + (double)ly.P * ly.S1), 2);
+    TnArgs t{};
+    t.Np = (int)Np; t.N = ly.N; t.gL = grad_L; t.gR = grad_R; t.ldg = ly.N + ly.P; t.accumulate = acc;
+    t.A = p.UV + ly.S1 * 2 * Np; t.lda = 2 * Np; t.Bm = p.T; t.ldb = Np; t.sc = p.gsc + ly.S1; t.S = ly.S2;
+    t.cols = ly.N; t.col0 = 0;
+    launch_gemm_tn(t, st);
+    t.A = p.UV; t.Bm = p.leafE; t.ldb = Pp; t.sc = p.gsc; t.S = ly.S1; t.cols = ly.P; t.col0 = ly.N;
+    launch_gemm_tn(t, st);
+  }
+  return hip_status();
+}
+
+}  // namespace
+}  // namespace spcfg
+
+using namespace spcfg;
+
+extern "C" {
+
+int spcfg_workspace_bytes(const spcfg_config* cfg, size_t* out_bytes) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (!out_bytes) return SPCFG_ERR_ARG;
+  const int64_t S1 = (int64_t)cfg->max_B * cfg->max_n;
+  const int64_t Sall = (int64_t)cfg->max_B * cfg->max_n * (cfg->max_n + 1) / 2;
+  if (Sall >= (int64_t)1 << 30) return SPCFG_ERR_SHAPE;
+  *out_bytes = make_layout(cfg->N, cfg->P, cfg->max_B, cfg->max_n, S1, Sall - S1).total;
+  return SPCFG_OK;
+}
+
+int spcfg_workspace_bytes_for(const spcfg_config* cfg, const int32_t* lengths, int32_t B, int32_t n_max,
+                              size_t* out_bytes) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (!out_bytes) return SPCFG_ERR_ARG;
+  Plan plan; Layout ly;
+  rc = make_plan(cfg, lengths, B, n_max, &plan, &ly);
+  if (rc) return rc;
+  *out_bytes = ly.total;
+  return SPCFG_OK;
+}
+
+int spcfg_inside(const spcfg_config* cfg, const float* log_root, const float* L, const float* R,
+                 const float* log_emit, const int32_t* lengths, int32_t B, int32_t n_max, float* logZ,
+                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (!log_root || !L || !R || !log_emit || !logZ) return SPCFG_ERR_ARG;
+  Plan plan; Layout ly;
+  rc = make_plan(cfg, lengths, B, n_max, &plan, &ly);
+  if (rc) return rc;
+  rc = check_ws(ly, workspace, workspace_bytes);
+  if (rc) return rc;
+  return forward(cfg, plan, ly, resolve(ly, workspace), log_root, L, R, log_emit, logZ, (hipStream_t)hip_stream);
+}
+
+int spcfg_inside_backward(const spcfg_config* cfg, const float* log_root, const float* L, const float* R,
+                          const float* log_emit, const int32_t* lengths, int32_t B, int32_t n_max,
+                          const float* grad_logZ, float* grad_L, float* grad_R, float* grad_log_root,
+                          float* grad_log_emit, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (!log_root || !L || !R || !log_emit || !grad_L || !grad_R || !grad_log_root || !grad_log_emit)
+    return SPCFG_ERR_ARG;
+  Plan plan; Layout ly;
+  rc = make_plan(cfg, lengths, B, n_max, &plan, &ly);
+  if (rc) return rc;
+  rc = check_ws(ly, workspace, workspace_bytes);
+  if (rc) return rc;
+  return backward(cfg, plan, ly, resolve(ly, workspace), log_root, grad_logZ, grad_L, grad_R, grad_log_root,
+                  grad_log_emit, (hipStream_t)hip_stream);
+}
+
+int spcfg_inside_forward_backward(const spcfg_config* cfg, const float* log_root, const float* L,
+                                  const float* R, const float* log_emit, const int32_t* lengths, int32_t B,
+                                  int32_t n_max, const float* grad_logZ, float* logZ, float* grad_L,
+                                  float* grad_R, float* grad_log_root, float* grad_log_emit, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (!log_root || !L || !R || !log_emit || !logZ || !grad_L || !grad_R || !grad_log_root || !grad_log_emit)
+    return SPCFG_ERR_ARG;
+  Plan plan; Layout ly;
+  rc = make_plan(cfg, lengths, B, n_max, &plan, &ly);
+  if (rc) return rc;
+  rc = check_ws(ly, workspace, workspace_bytes);
+  if (rc) return rc;
+  const Ptrs p = resolve(ly, workspace);
+  rc = forward(cfg, plan, ly, p, log_root, L, R, log_emit, logZ, (hipStream_t)hip_stream);
+  if (rc) return rc;
+  return backward(cfg, plan, ly, p, log_root, grad_logZ, grad_L, grad_R, grad_log_root, grad_log_emit,
+                  (hipStream_t)hip_stream);
+}
+
+const char* spcfg_strerror(int code) {
+  switch (code) {
+    case SPCFG_OK: return "ok";
+    case SPCFG_ERR_ARG: return "invalid argument (null pointer or bad struct_size)";
+    case SPCFG_ERR_SHAPE: return "shape out of range or above the configured capacity";
+    case SPCFG_ERR_LENGTH: return "sentence length below 2 or above n_max";
+    case SPCFG_ERR_WORKSPACE: return "workspace misaligned or too small";
+    case SPCFG_ERR_UNSUPPORTED: return "precision or flag not supported";
+    case SPCFG_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error code";
+  }
+}
+
+const char* spcfg_last_hip_error(void) { return g_hip_err; }
+
+int spcfg_profile_enable(int on) {
+  g_prof.on = on != 0;
+  if (g_prof.on) {
+    for (auto& r : g_prof.recs) { g_prof.pool.push_back(r.a); g_prof.pool.push_back(r.b); }
+    g_prof.recs.clear();
+    for (int c = 0; c < SPCFG_PROF_CLASSES; ++c) { g_prof.work[c] = 0; g_prof.launches[c] = 0; }
+  }
+  return SPCFG_OK;
+}
+
+int spcfg_profile_read(double* ms, int64_t* launches, double* work) {
+  if (!ms || !launches || !work) return SPCFG_ERR_ARG;
+  for (int c = 0; c < SPCFG_PROF_CLASSES; ++c) ms[c] = 0.0;
+  int rc = SPCFG_OK;
+  for (auto& r : g_prof.recs) {
+    float t = 0.0f;
+    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) rc = SPCFG_ERR_HIP;
+    ms[r.cls] += t;
+    g_prof.pool.push_back(r.a);
+    g_prof.pool.push_back(r.b);
+  }
+  g_prof.recs.clear();
+  for (int c = 0; c < SPCFG_PROF_CLASSES; ++c) {
+    launches[c] = g_prof.launches[c];
+    work[c] = g_prof.work[c];
+    g_prof.launches[c] = 0;
+    g_prof.work[c] = 0;
+  }
+  return rc;
+}
+
+const char* spcfg_profile_class_name(int cls) {
+  static const char* names[SPCFG_PROF_CLASSES] = {"setup", "gemm_fwd", "split_fwd", "root", "split_bwd", "gemm_bwd",
+                                                  "gemm_grad"};
+  return (cls >= 0 && cls < SPCFG_PROF_CLASSES) ? names[cls] : "?";
+}
+
+}  // extern "C"

@@ -1,0 +1,90 @@
+// Internal declarations shared by the host scheduler and the kernel launchers of libspcfg.
+//
+// Representation (paper Sec. 3.2 rescales by the per-span maximum in log space; here the same
+// rescaling is done with exact powers of two):  every chart vector v of a span is stored as an fp32
+// vector vt plus one integer exponent e per span, v = 2^e * vt.  Scaling by a power of two is exact in
+// fp32, so the only rounding is that of the probability-space products and sums themselves.
+//   leaf row r:        leafE[r] = exp(e_i - max e_i)          (exponent 0; the max is added back into logZ)
+//   span row r (w>=2): T[r]     = sum_k 2^(d_k - m) * eta_ik * zeta_kj,  m = max_k d_k   (exponent mexp[r] = m)
+//   every non-root row: HZ[r]   = [eta | zeta] = fscale[r] * [L;R] * (leafE[r] or T[r])   (exponent eexp[r])
+//   reverse pass:      UV[r]    = scaled adjoints of [eta | zeta]                         (exponent qexp[r])
+//                      BH[r]    = UV[r] * [L;R]  = scaled adjoint of beta                 (exponent qexp[r])
+// Rows are ordered by width, then sentence, then start position, so each width is one contiguous block.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/spcfg.h"
+
+namespace spcfg {
+
+constexpr int kPad = 64;                 // N and P are padded to multiples of this (zero filled)
+constexpr int kExpZero = -(1 << 24);     // exponent marking an all-zero vector
+constexpr int kMaxB = 960;               // lengths travel as one kernel argument
+constexpr int kMaxLen = 1024;
+
+inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+struct Layout {
+  int N, P, Np, Pp, B, n_max;
+  int64_t S1, S2, Sall;  // leaf rows, rows of width >= 2, all rows
+  // byte offsets into the workspace
+  size_t lens, rowbase, row_b, row_i, rootmask, rootrow, eexp, mexp, qexp, fscale, gsc, xs, ztil, rmax;
+  size_t leafE, T, HZ, UV, BH, Wn, Wp, Wtn, Wtp;
+  size_t total;
+};
+
+struct Ptrs {  // device pointers resolved from a Layout
+  int32_t *lens, *rowbase, *row_b, *row_i, *rootmask, *rootrow, *eexp, *mexp, *qexp;
+  float *fscale, *gsc, *xs, *ztil, *rmax;
+  float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp;
+};
+
+struct LenArg {  // lengths passed by value: no host buffer has to outlive the call
+  int32_t v[kMaxB];
+};
+
+// ---- launchers (each only enqueues on `st`) -------------------------------------------------------
+void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_t st);
+void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const float* R, hipStream_t st);
+void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hipStream_t st);
+void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st);
+void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st);
+void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, const float* grad_logZ,
+                     float* grad_log_root, int accumulate, hipStream_t st);
+void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st);
+void launch_zero_pad_emit(const Layout& ly, const Ptrs& p, float* grad_log_emit, hipStream_t st);
+
+// C[r][c] = sum_k A[r][k] * Bm[c][k]   (both operands K-contiguous), r < rows, c < cols, K % 32 == 0.
+enum NtEpilogue { NT_EPI_ROWSCALE = 0, NT_EPI_MASKROWS = 1, NT_EPI_LEAF_EMIT = 2 };
+struct NtArgs {
+  const float* A; int64_t lda;
+  const float* Bm; int64_t ldb;
+  float* C; int64_t ldc;
+  int rows, cols, K;
+  int epilogue;
+  const float* rowscale;    // ROWSCALE: C = rowscale[r] * acc
+  const int32_t* rowmask;   // MASKROWS: rows with rowmask[r] != 0 are left untouched
+  // LEAF_EMIT: C[dst[r] * ldc + c] = acc * E[r][c] * 2^qexp[r], c < cols
+  const float* E; int64_t lde;
+  const int32_t* qexp;
+  const int32_t* row_b; const int32_t* row_i; int n_max;
+};
+void launch_gemm_nt(const NtArgs& a, hipStream_t st);
+
+// C[a][b] (+)= sum_s sc[s] * A[s][a] * Bm[s][b]   (both operands reduction-major), written into grad_L / grad_R.
+struct TnArgs {
+  const float* A; int64_t lda;     // UV rows [S x 2Np]
+  const float* Bm; int64_t ldb;    // T rows [S x Np] or leafE rows [S x Pp]
+  const float* sc;                 // [S]
+  int64_t S;
+  int Np;                          // rows a in [0,Np) -> grad_L, [Np, 2Np) -> grad_R
+  int N;                           // valid rows per half
+  int cols;                        // valid output columns
+  float* gL; float* gR; int64_t ldg; int col0;  // destination column offset (0 or N)
+  int accumulate;
+};
+void launch_gemm_tn(const TnArgs& a, hipStream_t st);
+
+}  // namespace spcfg
