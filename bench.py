@@ -1,0 +1,131 @@
+#!/usr/bin/env python3
+"""Benchmark of the simple-PCFG inside forward+backward pass on one MI355X.
+
+A step is one spcfg_inside_forward_backward call (every kernel of the hot path) on one synthetic
+PTB-shaped batch (N = P = 2048, B = 64, lengths <= 40) whose inputs are already resident in HBM.
+Prints ONE JSON line: sentences/s, plus `roofline` for the dominant kernel (the fp32 MFMA projection GEMM,
+timed with HIP events inside the library on the launch stream) and `cpu_baseline` (the CPU oracle timed on
+a bounded sample of the same batch on this machine's host cores).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(d, max_sentences, budget_s=30.0):
+    """Time the oracle (as it stands, fp64 numpy) on the first sentences of the batch; bounded by budget_s."""
+    from oracle import spcfg_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    done, t0 = 0, time.perf_counter()
+    for b in range(min(max_sentences, d["B"])):
+        n = int(d["lengths"][b])
+        O.inside_backward_sentence(d["log_root"], d["L"], d["R"], d["log_emit"][b, :n])
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return dict(value=done / dt, unit="sentences/s", cores=int(cores), kind="oracle",
+                sample=f"first {done} sentences of the batch (lengths {d['lengths'][:done].tolist()}), "
+                       f"fp64 numpy oracle forward+backward, {dt:.1f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="ptb", choices=["tiny", "small", "ptb", "long"])
+    ap.add_argument("--profile-steps", type=int, default=3)
+    ap.add_argument("--cpu-sentences", type=int, default=12)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (data-parallel sharding over sentences is described in "
+              "DESIGN.md but not built); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2310_14997_amd import binding as bd
+    from paper_2310_14997_amd import synth
+
+    d = synth.make_inputs(args.workload)
+    wl = bd.Workload(d)
+    wc = synth.work_counts(d["lengths"], d["N"], d["P"])
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        wl.forward_backward()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        wl.forward_backward()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    sent_per_s = d["B"] / (dt / args.steps)
+    logz = wl.logZ.cpu().numpy()
+    assert np.all(np.isfinite(logz)), "non-finite log Z in the benchmark batch"
+
+    # per-kernel-class device time: same launches, bracketed by HIP events on the launch stream
+    bd.spcfg_profile_enable(True)
+    for _ in range(max(args.profile_steps, 0)):
+        wl.forward_backward()
+    torch.cuda.synchronize()
+    prof = bd.spcfg_profile_read()
+    bd.spcfg_profile_enable(False)
+    classes = {k: dict(ms_per_step=v["ms"] / args.profile_steps, launches_per_step=v["launches"] / args.profile_steps,
+                       work_per_step=v["work"] / args.profile_steps) for k, v in prof.items()}
+    proj_ms = classes["gemm_fwd"]["ms_per_step"] + classes["gemm_bwd"]["ms_per_step"]
+    proj_flop = classes["gemm_fwd"]["work_per_step"] + classes["gemm_bwd"]["work_per_step"]
+    proj_launches = classes["gemm_fwd"]["launches_per_step"] + classes["gemm_bwd"]["launches_per_step"]
+    achieved_tflops = proj_flop / (proj_ms * 1e-3) / 1e12
+    split_ms = classes["split_fwd"]["ms_per_step"] + classes["split_bwd"]["ms_per_step"]
+    split_bytes = classes["split_fwd"]["work_per_step"] + classes["split_bwd"]["work_per_step"]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get(args.workload, {}).get("gemm_nt_bytes_per_launch")
+
+    out = {
+        "metric": "sentences/sec inside fwd+bwd at N=P=2048, n<=40",
+        "value": sent_per_s, "unit": "sentences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: B={d['B']}, N={d['N']}, P={d['P']}, n_max={d['n_max']}, "
+                               f"sum_n={wc['leaves']}, projected_spans={wc['proj_spans']}, "
+                               f"split_terms={wc['split_terms']}, seed={d['seed']}",
+                   "flop_fwd_bwd": wc["flop_fwd_bwd"], "tflops_fwd_bwd": wc["flop_fwd_bwd"] / (dt / args.steps) / 1e12},
+        "roofline": {"bound": "mfma", "kernel": "k_gemm_nt (fp32 MFMA stacked projection, forward + reverse)",
+                     "achieved": achieved_tflops, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved_tflops / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
+                     "launches_per_step": proj_launches, "avg_launch_us": proj_ms * 1e3 / max(proj_launches, 1),
+                     "flop_per_launch": proj_flop / max(proj_launches, 1)},
+        "split_reduction": {"bound": "hbm", "achieved": split_bytes / (split_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                            "unit": "GB/s", "frac": split_bytes / (split_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                            "ms_per_step": split_ms},
+        "kernel_classes": classes,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(d, args.cpu_sentences)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

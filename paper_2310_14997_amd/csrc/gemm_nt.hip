@@ -41,22 +41,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g) {
     gb[q] = g.Bm + (int64_t)rb * g.ldb + lc4 * 4;
   }
   float4 ra4[4], rb4[4];
-  auto load_global = [&](int kt) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      ra4[q] = *reinterpret_cast<const float4*>(ga[q] + kt * BK);
-      rb4[q] = *reinterpret_cast<const float4*>(gb[q] + kt * BK);
-    }
-  };
-  auto store_lds = [&](int buf) {
-    float* as = lds + buf * kStage;
-    float* bs = as + BM * LDT;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      *reinterpret_cast<float4*>(as + (lr + 32 * q) * LDT + lc4 * 4) = ra4[q];
-      *reinterpret_cast<float4*>(bs + (lr + 32 * q) * LDT + lc4 * 4) = rb4[q];
-    }
-  };
+  const int lds_st = lr * LDT + lc4 * 4;
 
   floatx16 acc[2][2];
 #pragma unroll
@@ -67,34 +52,55 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g) {
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
   const int KT = g.K / BK;
-  load_global(0);
-  store_lds(0);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    ra4[q] = *reinterpret_cast<const float4*>(ga[q]);
+    rb4[q] = *reinterpret_cast<const float4*>(gb[q]);
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    *reinterpret_cast<float4*>(lds + lds_st + 32 * q * LDT) = ra4[q];
+    *reinterpret_cast<float4*>(lds + BM * LDT + lds_st + 32 * q * LDT) = rb4[q];
+  }
   __syncthreads();
 
   const int frag_row = lane & 31, frag_k = (lane >> 5) * 4;
+  const int a_off = (wm * 64 + frag_row) * LDT + frag_k;
+  const int b_off = BM * LDT + (wn * 64 + frag_row) * LDT + frag_k;
   for (int kt = 0; kt < KT; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < KT) load_global(kt + 1);
-    const float* as = lds + buf * kStage + (wm * 64 + frag_row) * LDT + frag_k;
-    const float* bs = lds + buf * kStage + BM * LDT + (wn * 64 + frag_row) * LDT + frag_k;
+    // prefetch the next K-step into registers (the last iteration re-reads its own step; never stored out of range)
+    const int kn = min(kt + 1, KT - 1) * BK;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      ra4[q] = *reinterpret_cast<const float4*>(ga[q] + kn);
+      rb4[q] = *reinterpret_cast<const float4*>(gb[q] + kn);
+    }
+    const float* as = lds + buf * kStage + a_off;
+    const float* bs = lds + buf * kStage + b_off;
 #pragma unroll
     for (int kc = 0; kc < BK / 8; ++kc) {
-      float4 a[2], b[2];
-      a[0] = *reinterpret_cast<const float4*>(as + kc * 8);
-      a[1] = *reinterpret_cast<const float4*>(as + 32 * LDT + kc * 8);
-      b[0] = *reinterpret_cast<const float4*>(bs + kc * 8);
-      b[1] = *reinterpret_cast<const float4*>(bs + 32 * LDT + kc * 8);
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].x, b[ni].x, acc[mi][ni], 0, 0, 0);
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].y, b[ni].y, acc[mi][ni], 0, 0, 0);
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].z, b[ni].z, acc[mi][ni], 0, 0, 0);
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].w, b[ni].w, acc[mi][ni], 0, 0, 0);
-        }
+      const float4 a0 = *reinterpret_cast<const float4*>(as + kc * 8);
+      const float4 a1 = *reinterpret_cast<const float4*>(as + 32 * LDT + kc * 8);
+      const float4 b0 = *reinterpret_cast<const float4*>(bs + kc * 8);
+      const float4 b1 = *reinterpret_cast<const float4*>(bs + 32 * LDT + kc * 8);
+#define SPCFG_MFMA4(AX, BX)                                                                  \
+  acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.AX, b0.BX, acc[0][0], 0, 0, 0);       \
+  acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.AX, b1.BX, acc[0][1], 0, 0, 0);       \
+  acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.AX, b0.BX, acc[1][0], 0, 0, 0);       \
+  acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.AX, b1.BX, acc[1][1], 0, 0, 0);
+      SPCFG_MFMA4(x, x)
+      SPCFG_MFMA4(y, y)
+      SPCFG_MFMA4(z, z)
+      SPCFG_MFMA4(w, w)
+#undef SPCFG_MFMA4
     }
-    if (kt + 1 < KT) store_lds(buf ^ 1);
+    float* st = lds + (buf ^ 1) * kStage + lds_st;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      *reinterpret_cast<float4*>(st + 32 * q * LDT) = ra4[q];
+      *reinterpret_cast<float4*>(st + BM * LDT + 32 * q * LDT) = rb4[q];
+    }
     __syncthreads();
   }
 
