@@ -6,6 +6,13 @@
 // Each lane fetches its MFMA operands as one 16-byte LDS read covering four K values; the K order inside
 // an 8-wide chunk is permuted identically for both operands (lanes 0-31 take k0..k0+3, lanes 32-63
 // k0+4..k0+7), which leaves the sum over K unchanged.
+//
+// The number of span rows shrinks with the width (from thousands to a handful), so a tile-per-workgroup
+// launch would leave most of the 256 CUs idle for most widths.  Instead the (tile, K-step) iteration space is
+// cut into equal contiguous shares, one per workgroup.  A workgroup whose share covers only part of a
+// tile's K range writes its partial accumulators to a scratch slot and bumps the tile's arrival counter;
+// whichever workgroup arrives last sums the slots in fixed order (so the result does not depend on the
+// arrival order) and runs the epilogue.  Nobody waits on anybody: there is no spinning.
 #include "spcfg_internal.h"
 
 namespace spcfg {
@@ -14,97 +21,30 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
+// Partial tiles travel between workgroups (possibly on different XCDs, whose L2 caches are not coherent
+// with each other) as relaxed agent-scope atomic 8-byte accesses: stores write through, loads read the
+// coherent copy, and neither needs a cache write-back or invalidate.
+struct F2 { float a, b; };
+__device__ __forceinline__ void st_agent(float* p, float a, float b) {
+  const F2 v{a, b};
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), __builtin_bit_cast(unsigned long long, v),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ F2 ld_agent(const float* p) {
+  return __builtin_bit_cast(F2, __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT));
+}
+
 constexpr int BM = 128, BN = 128, BK = 32;
 constexpr int LDT = BK + 4;  // LDS row stride in floats: 16-byte aligned rows, conflict-free 16-byte reads
 constexpr int kStage = (BM + BN) * LDT;
 constexpr size_t kLdsBytes = 2 * kStage * sizeof(float);
+constexpr int kSlotFloats = BM * BN;
 
 template <int EPI>
-__global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g) {
-  extern __shared__ __align__(16) float lds[];
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave & 1, wn = wave >> 1;
-  const int tiles_m = (g.rows + BM - 1) / BM;
-  const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
-  const int row0 = tile_m * BM, col0 = tile_n * BN;
-
-  // global -> register staging: each thread moves 4 float4 of A and 4 of Bm per K-step
-  const int lc4 = tid & 7, lr = tid >> 3;  // 8 float4 per tile row, 32 rows per pass
-  const float* ga[4];
-  const float* gb[4];
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int ra = min(row0 + lr + 32 * q, g.rows - 1);
-    const int rb = min(col0 + lr + 32 * q, g.cols - 1);
-    ga[q] = g.A + (int64_t)ra * g.lda + lc4 * 4;
-    gb[q] = g.Bm + (int64_t)rb * g.ldb + lc4 * 4;
-  }
-  float4 ra4[4], rb4[4];
-  const int lds_st = lr * LDT + lc4 * 4;
-
-  floatx16 acc[2][2];
-#pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
-
-  const int KT = g.K / BK;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    ra4[q] = *reinterpret_cast<const float4*>(ga[q]);
-    rb4[q] = *reinterpret_cast<const float4*>(gb[q]);
-  }
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    *reinterpret_cast<float4*>(lds + lds_st + 32 * q * LDT) = ra4[q];
-    *reinterpret_cast<float4*>(lds + BM * LDT + lds_st + 32 * q * LDT) = rb4[q];
-  }
-  __syncthreads();
-
-  const int frag_row = lane & 31, frag_k = (lane >> 5) * 4;
-  const int a_off = (wm * 64 + frag_row) * LDT + frag_k;
-  const int b_off = BM * LDT + (wn * 64 + frag_row) * LDT + frag_k;
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    // prefetch the next K-step into registers (the last iteration re-reads its own step; never stored out of range)
-    const int kn = min(kt + 1, KT - 1) * BK;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      ra4[q] = *reinterpret_cast<const float4*>(ga[q] + kn);
-      rb4[q] = *reinterpret_cast<const float4*>(gb[q] + kn);
-    }
-    const float* as = lds + buf * kStage + a_off;
-    const float* bs = lds + buf * kStage + b_off;
-#pragma unroll
-    for (int kc = 0; kc < BK / 8; ++kc) {
-      const float4 a0 = *reinterpret_cast<const float4*>(as + kc * 8);
-      const float4 a1 = *reinterpret_cast<const float4*>(as + 32 * LDT + kc * 8);
-      const float4 b0 = *reinterpret_cast<const float4*>(bs + kc * 8);
-      const float4 b1 = *reinterpret_cast<const float4*>(bs + 32 * LDT + kc * 8);
-#define SPCFG_MFMA4(AX, BX)                                                                  \
-  acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.AX, b0.BX, acc[0][0], 0, 0, 0);       \
-  acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.AX, b1.BX, acc[0][1], 0, 0, 0);       \
-  acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.AX, b0.BX, acc[1][0], 0, 0, 0);       \
-  acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.AX, b1.BX, acc[1][1], 0, 0, 0);
-      SPCFG_MFMA4(x, x)
-      SPCFG_MFMA4(y, y)
-      SPCFG_MFMA4(z, z)
-      SPCFG_MFMA4(w, w)
-#undef SPCFG_MFMA4
-    }
-    float* st = lds + (buf ^ 1) * kStage + lds_st;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      *reinterpret_cast<float4*>(st + 32 * q * LDT) = ra4[q];
-      *reinterpret_cast<float4*>(st + BM * LDT + 32 * q * LDT) = rb4[q];
-    }
-    __syncthreads();
-  }
-
-  // epilogue.  Accumulator layout of the 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4.
+__device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[2][2], int row0, int col0, int wm, int wn,
+                                         int lane) {
+  // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
 #pragma unroll
   for (int mi = 0; mi < 2; ++mi) {
 #pragma unroll
@@ -135,6 +75,150 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g) {
 }
 
 template <int EPI>
+__global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total_iters) {
+  extern __shared__ __align__(16) float lds[];
+  __shared__ int s_last;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int tiles_m = (g.rows + BM - 1) / BM;
+  const int KT = g.K / BK;
+  const int lc4 = tid & 7, lr = tid >> 3;  // staging: 8 float4 per tile row, 32 rows per pass
+  const int lds_st = lr * LDT + lc4 * 4;
+  const int frag_row = lane & 31, frag_k = (lane >> 5) * 4;
+  const int a_off = (wm * 64 + frag_row) * LDT + frag_k;
+  const int b_off = BM * LDT + (wn * 64 + frag_row) * LDT + frag_k;
+
+  const int wg_begin = blockIdx.x * ipw;
+  const int wg_end = min(wg_begin + ipw, total_iters);
+  int it = wg_begin;
+  while (it < wg_end) {
+    const int tile = it / KT;
+    const int k0 = it - tile * KT;
+    const int k1 = min(KT, k0 + (wg_end - it));
+    const int tile_m = tile % tiles_m, tile_n = tile / tiles_m;
+    const int row0 = tile_m * BM, col0 = tile_n * BN;
+
+    const float* ga[4];
+    const float* gb[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int ra = min(row0 + lr + 32 * q, g.rows - 1);
+      const int rb = min(col0 + lr + 32 * q, g.cols - 1);
+      ga[q] = g.A + (int64_t)ra * g.lda + lc4 * 4;
+      gb[q] = g.Bm + (int64_t)rb * g.ldb + lc4 * 4;
+    }
+    float4 ra4[4], rb4[4];
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      ra4[q] = *reinterpret_cast<const float4*>(ga[q] + k0 * BK);
+      rb4[q] = *reinterpret_cast<const float4*>(gb[q] + k0 * BK);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      *reinterpret_cast<float4*>(lds + lds_st + 32 * q * LDT) = ra4[q];
+      *reinterpret_cast<float4*>(lds + BM * LDT + lds_st + 32 * q * LDT) = rb4[q];
+    }
+    __syncthreads();
+
+    for (int kt = k0; kt < k1; ++kt) {
+      const int buf = (kt - k0) & 1;
+      // prefetch the next K-step into registers (the last iteration re-reads its own step)
+      const int kn = min(kt + 1, k1 - 1) * BK;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        ra4[q] = *reinterpret_cast<const float4*>(ga[q] + kn);
+        rb4[q] = *reinterpret_cast<const float4*>(gb[q] + kn);
+      }
+      const float* as = lds + buf * kStage + a_off;
+      const float* bs = lds + buf * kStage + b_off;
+#pragma unroll
+      for (int kc = 0; kc < BK / 8; ++kc) {
+        const float4 a0 = *reinterpret_cast<const float4*>(as + kc * 8);
+        const float4 a1 = *reinterpret_cast<const float4*>(as + 32 * LDT + kc * 8);
+        const float4 b0 = *reinterpret_cast<const float4*>(bs + kc * 8);
+        const float4 b1 = *reinterpret_cast<const float4*>(bs + 32 * LDT + kc * 8);
+#define SPCFG_MFMA4(AX, BX)                                                                  \
+  acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.AX, b0.BX, acc[0][0], 0, 0, 0);       \
+  acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.AX, b1.BX, acc[0][1], 0, 0, 0);       \
+  acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.AX, b0.BX, acc[1][0], 0, 0, 0);       \
+  acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.AX, b1.BX, acc[1][1], 0, 0, 0);
+        SPCFG_MFMA4(x, x)
+        SPCFG_MFMA4(y, y)
+        SPCFG_MFMA4(z, z)
+        SPCFG_MFMA4(w, w)
+#undef SPCFG_MFMA4
+      }
+      float* st = lds + (buf ^ 1) * kStage + lds_st;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        *reinterpret_cast<float4*>(st + 32 * q * LDT) = ra4[q];
+        *reinterpret_cast<float4*>(st + BM * LDT + 32 * q * LDT) = rb4[q];
+      }
+      __syncthreads();
+    }
+
+    if (k0 == 0 && k1 == KT) {
+      epilogue<EPI>(g, acc, row0, col0, wm, wn, lane);
+    } else {
+      // partial tile: publish, count arrivals, last arriver reduces in fixed order
+      const int first_g = (tile * KT) / ipw;
+      const int last_g = (tile * KT + KT - 1) / ipw;
+      const int parts = last_g - first_g + 1;
+      float* slot = g.partial + (size_t)(2 * blockIdx.x + (it != wg_begin ? 1 : 0)) * kSlotFloats;
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            st_agent(slot + (((mi * 2 + ni) * 8 + j) * 256 + tid) * 2, acc[mi][ni][2 * j], acc[mi][ni][2 * j + 1]);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my stores have landed before the arrival is counted
+      __syncthreads();
+      if (tid == 0)
+        s_last = (__hip_atomic_fetch_add(&g.counters[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                  parts - 1) ? 1 : 0;
+      __syncthreads();
+      if (s_last) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+        for (int p = 0; p < parts; ++p) {
+          const int gp = first_g + p;
+          const int odd = (p == 0 && tile * KT != gp * ipw) ? 1 : 0;
+          const float* src = g.partial + (size_t)(2 * gp + odd) * kSlotFloats;
+#pragma unroll
+          for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+              for (int j = 0; j < 8; ++j) {
+                const F2 x = ld_agent(src + (((mi * 2 + ni) * 8 + j) * 256 + tid) * 2);
+                acc[mi][ni][2 * j] += x.a;
+                acc[mi][ni][2 * j + 1] += x.b;
+              }
+        }
+        epilogue<EPI>(g, acc, row0, col0, wm, wn, lane);
+        if (tid == 0)  // ready for the next launch on this stream
+          __hip_atomic_store(&g.counters[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    it += k1 - k0;
+  }
+}
+
+template <int EPI>
 void launch(const NtArgs& a, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
@@ -143,10 +227,22 @@ void launch(const NtArgs& a, hipStream_t st) {
     attr_set = true;
   }
   const int tiles = ((a.rows + BM - 1) / BM) * ((a.cols + BN - 1) / BN);
-  hipLaunchKernelGGL(k_gemm_nt<EPI>, dim3(tiles), dim3(256), kLdsBytes, st, a);
+  const int KT = a.K / BK;
+  const int total = tiles * KT;
+  // two workgroups per CU hide latency once there is enough work; with few tiles the extra partial-tile
+  // traffic of a finer cut costs more than it gains
+  int G = tiles >= 200 ? 512 : 256;
+  if (G > a.max_wgs) G = a.max_wgs;
+  if (G > total) G = total;
+  int ipw = (total + G - 1) / G;
+  G = (total + ipw - 1) / ipw;
+  hipLaunchKernelGGL(k_gemm_nt<EPI>, dim3(G), dim3(256), kLdsBytes, st, a, ipw, total);
 }
 
 }  // namespace
+
+int gemm_nt_tiles(int rows, int cols) { return ((rows + BM - 1) / BM) * ((cols + BN - 1) / BN); }
+size_t gemm_nt_partial_bytes(int max_wgs) { return (size_t)2 * max_wgs * kSlotFloats * sizeof(float); }
 
 void launch_gemm_nt(const NtArgs& a, hipStream_t st) {
   if (a.rows <= 0 || a.cols <= 0) return;

@@ -64,8 +64,10 @@ __device__ __forceinline__ int add_exp(int a, int b) { return (a == kExpZero || 
 // ------------------------------------------------------------------------------------------ span plan
 // Width-synchronous schedule (Sec. 3.2, span-level parallelism): rows are ordered by width, sentence, start.
 __global__ void k_plan_rowbase(LenArg la, int B, int n_max, int32_t* __restrict__ lens,
-                               int32_t* __restrict__ rowbase, int32_t* __restrict__ rootrow) {
+                               int32_t* __restrict__ rowbase, int32_t* __restrict__ rootrow,
+                               int32_t* __restrict__ counters, int n_counters) {
   __shared__ int s_w[kMaxLen + 2];
+  for (int t = threadIdx.x; t < n_counters; t += blockDim.x) counters[t] = 0;  // GEMM arrival counters
   for (int b = threadIdx.x; b < B; b += blockDim.x) lens[b] = la.v[b];
   for (int w = 1 + threadIdx.x; w <= n_max; w += blockDim.x) {
     int s = 0;
@@ -437,7 +439,8 @@ int pick_threads(int Np) {
 }  // namespace
 
 void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_t st) {
-  hipLaunchKernelGGL(k_plan_rowbase, dim3(1), dim3(256), 0, st, lens, ly.B, ly.n_max, p.lens, p.rowbase, p.rootrow);
+  hipLaunchKernelGGL(k_plan_rowbase, dim3(1), dim3(256), 0, st, lens, ly.B, ly.n_max, p.lens, p.rowbase, p.rootrow,
+                     p.counters, ly.n_counters);
   hipLaunchKernelGGL(k_plan_rows, dim3(ly.n_max, ly.B), dim3(64), 0, st, ly.B, p.lens, p.rowbase, p.row_b, p.row_i,
                      p.rootmask);
 }

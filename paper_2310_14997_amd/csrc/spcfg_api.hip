@@ -54,6 +54,10 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2) {
   ly.fscale = take(f4 * ly.Sall);
   ly.gsc = take(f4 * ly.Sall);
   ly.xs = take(f4 * S1);
+  // the widest launch has at most max(S1, S2) rows (one width) and 2Np columns
+  ly.n_counters = gemm_nt_tiles((int)(S1 > S2 ? S1 : S2), 2 * ly.Np);
+  ly.counters = take(i4 * (size_t)ly.n_counters);
+  ly.partial = take(gemm_nt_partial_bytes(kGemmWgs));
   ly.Wn = take(f4 * 2 * (size_t)ly.Np * ly.Np);
   ly.Wp = take(f4 * 2 * (size_t)ly.Np * ly.Pp);
   ly.Wtn = take(f4 * 2 * (size_t)ly.Np * ly.Np);
@@ -77,6 +81,7 @@ Ptrs resolve(const Layout& ly, void* ws) {
   p.ztil = (float*)(b + ly.ztil); p.rmax = (float*)(b + ly.rmax);
   p.leafE = (float*)(b + ly.leafE); p.T = (float*)(b + ly.T); p.HZ = (float*)(b + ly.HZ);
   p.UV = (float*)(b + ly.UV); p.BH = (float*)(b + ly.BH);
+  p.partial = (float*)(b + ly.partial); p.counters = (int32_t*)(b + ly.counters);
   p.Wn = (float*)(b + ly.Wn); p.Wp = (float*)(b + ly.Wp); p.Wtn = (float*)(b + ly.Wtn); p.Wtp = (float*)(b + ly.Wtp);
   return p;
 }
@@ -161,6 +166,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
   {  // width 1: [eta | zeta] = [L_P ; R_P] * emission vector
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.P * ly.S1);
     NtArgs a{};
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs;
     a.A = p.leafE; a.lda = Pp; a.Bm = p.Wp; a.ldb = Pp; a.C = p.HZ; a.ldc = 2 * Np;
     a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
     a.epilogue = NT_EPI_ROWSCALE; a.rowscale = p.fscale;
@@ -176,6 +182,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     if (w == n_max) break;  // every span of the largest width is a root span: never a child, not projected
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.N * rows);
     NtArgs a{};
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs;
     a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
     a.rows = (int)rows; a.cols = (int)(2 * Np); a.K = (int)Np;
@@ -215,6 +222,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       launch_split_bwd(ly, p, w, row0, rows, st);
     }
     NtArgs a{};
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs;
     a.A = p.UV + row0 * 2 * Np; a.lda = 2 * Np; a.K = (int)(2 * Np); a.rows = (int)rows;
     if (w >= 2) {
       Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.N * rows);

@@ -31,14 +31,16 @@ struct Layout {
   int64_t S1, S2, Sall;  // leaf rows, rows of width >= 2, all rows
   // byte offsets into the workspace
   size_t lens, rowbase, row_b, row_i, rootmask, rootrow, eexp, mexp, qexp, fscale, gsc, xs, ztil, rmax;
-  size_t leafE, T, HZ, UV, BH, Wn, Wp, Wtn, Wtp;
+  size_t leafE, T, HZ, UV, BH, Wn, Wp, Wtn, Wtp, partial, counters;
+  int n_counters;
   size_t total;
 };
 
 struct Ptrs {  // device pointers resolved from a Layout
   int32_t *lens, *rowbase, *row_b, *row_i, *rootmask, *rootrow, *eexp, *mexp, *qexp;
   float *fscale, *gsc, *xs, *ztil, *rmax;
-  float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp;
+  float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp, *partial;
+  int32_t* counters;
 };
 
 struct LenArg {  // lengths passed by value: no host buffer has to outlive the call
@@ -70,8 +72,13 @@ struct NtArgs {
   const float* E; int64_t lde;
   const int32_t* qexp;
   const int32_t* row_b; const int32_t* row_i; int n_max;
+  // work sharing across workgroups: scratch for partial tiles and per-tile arrival counters (zero between launches)
+  float* partial; int32_t* counters; int max_wgs;
 };
 void launch_gemm_nt(const NtArgs& a, hipStream_t st);
+int gemm_nt_tiles(int rows, int cols);           // number of output tiles (= arrival counters needed)
+size_t gemm_nt_partial_bytes(int max_wgs);       // scratch needed for partial tiles
+constexpr int kGemmWgs = 512;                    // workgroups per projection launch: 2 per CU on 256 CUs
 
 // C[a][b] (+)= sum_s sc[s] * A[s][a] * Bm[s][b]   (both operands reduction-major), written into grad_L / grad_R.
 struct TnArgs {
