@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=3)
     ap.add_argument("--cpu-sentences", type=int, default=12)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain device copy of known size (1 GiB read + 1 GiB written per launch, 5 "
+                         "launches): the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (data-parallel sharding over sentences is described in "
@@ -63,6 +66,16 @@ def main():
     import torch
     from paper_2310_14997_amd import binding as bd
     from paper_2310_14997_amd import synth
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "copy", "bytes_read_per_launch": src.numel() * 4,
+                          "bytes_written_per_launch": src.numel() * 4, "launches": 5}))
+        return
 
     d = synth.make_inputs(args.workload)
     wl = bd.Workload(d)
@@ -84,13 +97,14 @@ def main():
 
     # per-kernel-class device time: same launches, bracketed by HIP events on the launch stream
     bd.spcfg_profile_enable(True)
-    for _ in range(max(args.profile_steps, 0)):
+    psteps = max(args.profile_steps, 1)
+    for _ in range(psteps):
         wl.forward_backward()
     torch.cuda.synchronize()
     prof = bd.spcfg_profile_read()
     bd.spcfg_profile_enable(False)
-    classes = {k: dict(ms_per_step=v["ms"] / args.profile_steps, launches_per_step=v["launches"] / args.profile_steps,
-                       work_per_step=v["work"] / args.profile_steps) for k, v in prof.items()}
+    classes = {k: dict(ms_per_step=v["ms"] / psteps, launches_per_step=v["launches"] / psteps,
+                       work_per_step=v["work"] / psteps) for k, v in prof.items()}
     proj_ms = classes["gemm_fwd"]["ms_per_step"] + classes["gemm_bwd"]["ms_per_step"]
     proj_flop = classes["gemm_fwd"]["work_per_step"] + classes["gemm_bwd"]["work_per_step"]
     proj_launches = classes["gemm_fwd"]["launches_per_step"] + classes["gemm_bwd"]["launches_per_step"]

@@ -89,7 +89,12 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
   const int a_off = (wm * 64 + frag_row) * LDT + frag_k;
   const int b_off = BM * LDT + (wn * 64 + frag_row) * LDT + frag_k;
 
-  const int wg_begin = blockIdx.x * ipw;
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber them so that every XCD
+  // owns one contiguous run of shares, i.e. a contiguous run of tiles: the [L;R] panels it streams are then
+  // (nearly) disjoint from those of the other XCDs instead of every L2 fetching all of them.
+  const int nwg = gridDim.x, xcd = blockIdx.x & 7, qx = nwg >> 3, rx = nwg & 7;
+  const int wg = xcd * qx + min(xcd, rx) + (blockIdx.x >> 3);
+  const int wg_begin = wg * ipw;
   const int wg_end = min(wg_begin + ipw, total_iters);
   int it = wg_begin;
   while (it < wg_end) {
@@ -173,7 +178,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
       const int first_g = (tile * KT) / ipw;
       const int last_g = (tile * KT + KT - 1) / ipw;
       const int parts = last_g - first_g + 1;
-      float* slot = g.partial + (size_t)(2 * blockIdx.x + (it != wg_begin ? 1 : 0)) * kSlotFloats;
+      float* slot = g.partial + (size_t)(2 * wg + (it != wg_begin ? 1 : 0)) * kSlotFloats;
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -231,7 +236,7 @@ void launch(const NtArgs& a, hipStream_t st) {
   const int total = tiles * KT;
   // two workgroups per CU hide latency once there is enough work; with few tiles the extra partial-tile
   // traffic of a finer cut costs more than it gains
-  int G = tiles >= 200 ? 512 : 256;
+  int G = total >= 12288 ? 512 : 256;
   if (G > a.max_wgs) G = a.max_wgs;
   if (G > total) G = total;
   int ipw = (total + G - 1) / G;

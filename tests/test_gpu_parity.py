@@ -145,3 +145,49 @@ def test_runtime_errors_do_not_launch():
     with pytest.raises(bd.SpcfgError) as e:
         bd.spcfg_inside(wl.cfg, wl.log_root, wl.L, wl.R, wl.log_emit, wl.lengths, wl.logZ, wl.workspace[:1024])
     assert e.value.code == -4
+
+
+def test_long_sentences_scaled_down():
+    """Long-sentence shape (hundreds of widths, late widths with one or two spans) at a size the oracle finishes."""
+    d = synth.make_inputs("long", pad_value=np.nan, N=192, P=160, B=3, lengths=[131, 64, 97], V=2000)
+    print("case long-ish", flush=True)
+    got, _ = gpu_run(d, fused=True)
+    print(check_all(got, oracle_run(d)))
+
+
+def test_ptb_full_size_sampled_against_oracle_and_invariants():
+    """Headline configuration as bench.py launches it (B=64, N=P=2048, n<=40).  Per-sentence outputs of sampled
+    sentences are compared with the oracle one by one; batch-summed parameter gradients are checked through
+    the flow-conservation identities of expected rule counts, which hold at any size."""
+    d = synth.make_inputs("ptb", pad_value=np.nan)
+    print("case ptb full size", flush=True)
+    wl = bd.Workload(d)
+    wl.forward_backward()
+    got = wl.results()
+    wl.forward_backward()
+    again = wl.results()
+    for k in got:
+        assert np.array_equal(got[k], again[k], equal_nan=True), f"{k}: two runs differ bitwise"
+    lens = d["lengths"]
+    order = np.argsort(lens)
+    sample = sorted({int(order[0]), int(order[len(order) // 3]), int(order[len(order) // 2]), int(order[-1])})
+    for b in sample:
+        n = int(lens[b])
+        print("  oracle sentence", b, "length", n, flush=True)
+        lz, gL, gR, gr, ge = O.inside_backward_sentence(d["log_root"], d["L"], d["R"], d["log_emit"][b, :n])
+        check_logZ(got["logZ"][b:b + 1], np.array([lz]))
+        check_grad(f"grad_log_emit[{b}]", got["grad_log_emit"][b, :n], ge)
+        assert np.all(got["grad_log_emit"][b, n:] == 0.0)
+    nm1 = float((lens.astype(np.float64) - 1).sum())
+    L64, R64 = d["L"].astype(np.float64), d["R"].astype(np.float64)
+    EL, ER = L64 * got["grad_L"], R64 * got["grad_R"]
+    N = d["N"]
+    assert EL.sum() == pytest.approx(nm1, rel=1e-4) and ER.sum() == pytest.approx(nm1, rel=1e-4)
+    check_grad("parent counts L vs R", EL.sum(axis=1), ER.sum(axis=1))
+    tok = np.zeros(d["P"])
+    for b in range(d["B"]):
+        tok += got["grad_log_emit"][b, : int(lens[b])].sum(axis=0)
+    check_grad("preterminal child counts vs emission posteriors", (EL + ER)[:, N:].sum(axis=0), tok)
+    assert got["grad_log_root"].sum() == pytest.approx(d["B"], rel=1e-4)
+    # nonterminal occurrences: as a parent = as the root + as somebody's child
+    check_grad("nonterminal flow", EL.sum(axis=1), got["grad_log_root"] + (EL + ER)[:, :N].sum(axis=0), 2e-4)
