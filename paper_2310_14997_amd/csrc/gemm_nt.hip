@@ -35,21 +35,32 @@ __device__ __forceinline__ F2 ld_agent(const float* p) {
                                                   __HIP_MEMORY_SCOPE_AGENT));
 }
 
-constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int BN = 128, BK = 32;
 constexpr int LDT = BK + 4;  // LDS row stride in floats: 16-byte aligned rows, conflict-free 16-byte reads
-constexpr int kStage = (BM + BN) * LDT;
-constexpr size_t kLdsBytes = 2 * kStage * sizeof(float);
-constexpr int kSlotFloats = BM * BN;
 
-template <int EPI>
-__device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[2][2], int row0, int col0, int wm, int wn,
-                                         int lane) {
+// Tile geometry for a row-tile height BM (spans per tile).  Widths with few spans use shorter tiles so that
+// the matrix cores do not multiply padding rows.
+template <int BM> struct Geo {
+  static constexpr int WM = BM == 32 ? 1 : 2;            // wavefronts along rows
+  static constexpr int WN = 4 / WM;                      // wavefronts along columns
+  static constexpr int MI = BM / (32 * WM);              // 32x32 MFMA tiles per wavefront along rows
+  static constexpr int NI = BN / (32 * WN);              // ... along columns
+  static constexpr int QA = BM / 32;                     // float4 of A staged per thread and K-step
+  static constexpr int kStage = (BM + BN) * LDT;
+  static constexpr size_t kLdsBytes = 2 * kStage * sizeof(float);
+  static constexpr int kSlotFloats = BM * BN;
+};
+
+template <int EPI, int BM>
+__device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[Geo<BM>::MI][Geo<BM>::NI], int row0, int col0,
+                                         int wm, int wn, int lane) {
+  using G = Geo<BM>;
   // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi) {
+  for (int mi = 0; mi < G::MI; ++mi) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int r = row0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      const int r = row0 + (wm * G::MI + mi) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
       if (r >= g.rows) continue;
       float scale = 1.0f;
       int64_t drow = r;
@@ -63,8 +74,8 @@ __device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[2][2],
         drow = (int64_t)g.row_b[r] * g.n_max + g.row_i[r];
       }
 #pragma unroll
-      for (int ni = 0; ni < 2; ++ni) {
-        const int c = col0 + wn * 64 + ni * 32 + (lane & 31);
+      for (int ni = 0; ni < G::NI; ++ni) {
+        const int c = col0 + (wn * G::NI + ni) * 32 + (lane & 31);
         if (c >= g.cols) continue;
         float val = acc[mi][ni][v] * scale;
         if (EPI == NT_EPI_LEAF_EMIT) val *= g.E[(int64_t)r * g.lde + c];
@@ -74,20 +85,21 @@ __device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[2][2],
   }
 }
 
-template <int EPI>
+template <int EPI, int BM>
 __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total_iters) {
+  using G = Geo<BM>;
   extern __shared__ __align__(16) float lds[];
   __shared__ int s_last;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave & 1, wn = wave >> 1;
+  const int wm = wave % G::WM, wn = wave / G::WM;
   const int tiles_m = (g.rows + BM - 1) / BM;
   const int KT = g.K / BK;
   const int lc4 = tid & 7, lr = tid >> 3;  // staging: 8 float4 per tile row, 32 rows per pass
   const int lds_st = lr * LDT + lc4 * 4;
   const int frag_row = lane & 31, frag_k = (lane >> 5) * 4;
-  const int a_off = (wm * 64 + frag_row) * LDT + frag_k;
-  const int b_off = BM * LDT + (wn * 64 + frag_row) * LDT + frag_k;
+  const int a_off = (wm * G::MI * 32 + frag_row) * LDT + frag_k;
+  const int b_off = BM * LDT + (wn * G::NI * 32 + frag_row) * LDT + frag_k;
 
   // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber them so that every XCD
   // owns one contiguous run of shares, i.e. a contiguous run of tiles: the [L;R] panels it streams are then
@@ -104,34 +116,31 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
     const int tile_m = tile % tiles_m, tile_n = tile / tiles_m;
     const int row0 = tile_m * BM, col0 = tile_n * BN;
 
-    const float* ga[4];
+    const float* ga[G::QA];
     const float* gb[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int ra = min(row0 + lr + 32 * q, g.rows - 1);
-      const int rb = min(col0 + lr + 32 * q, g.cols - 1);
-      ga[q] = g.A + (int64_t)ra * g.lda + lc4 * 4;
-      gb[q] = g.Bm + (int64_t)rb * g.ldb + lc4 * 4;
-    }
-    float4 ra4[4], rb4[4];
-    floatx16 acc[2][2];
+    for (int q = 0; q < G::QA; ++q)
+      ga[q] = g.A + (int64_t)min(row0 + lr + 32 * q, g.rows - 1) * g.lda + lc4 * 4;
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int q = 0; q < 4; ++q)
+      gb[q] = g.Bm + (int64_t)min(col0 + lr + 32 * q, g.cols - 1) * g.ldb + lc4 * 4;
+    float4 ra4[G::QA], rb4[4];
+    floatx16 acc[G::MI][G::NI];
 #pragma unroll
-      for (int ni = 0; ni < 2; ++ni)
+    for (int mi = 0; mi < G::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < G::NI; ++ni)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      ra4[q] = *reinterpret_cast<const float4*>(ga[q] + k0 * BK);
-      rb4[q] = *reinterpret_cast<const float4*>(gb[q] + k0 * BK);
-    }
+    for (int q = 0; q < G::QA; ++q) ra4[q] = *reinterpret_cast<const float4*>(ga[q] + k0 * BK);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      *reinterpret_cast<float4*>(lds + lds_st + 32 * q * LDT) = ra4[q];
-      *reinterpret_cast<float4*>(lds + BM * LDT + lds_st + 32 * q * LDT) = rb4[q];
-    }
+    for (int q = 0; q < 4; ++q) rb4[q] = *reinterpret_cast<const float4*>(gb[q] + k0 * BK);
+#pragma unroll
+    for (int q = 0; q < G::QA; ++q) *reinterpret_cast<float4*>(lds + lds_st + 32 * q * LDT) = ra4[q];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) *reinterpret_cast<float4*>(lds + BM * LDT + lds_st + 32 * q * LDT) = rb4[q];
     __syncthreads();
 
     for (int kt = k0; kt < k1; ++kt) {
@@ -139,53 +148,50 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
       // prefetch the next K-step into registers (the last iteration re-reads its own step)
       const int kn = min(kt + 1, k1 - 1) * BK;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        ra4[q] = *reinterpret_cast<const float4*>(ga[q] + kn);
-        rb4[q] = *reinterpret_cast<const float4*>(gb[q] + kn);
-      }
-      const float* as = lds + buf * kStage + a_off;
-      const float* bs = lds + buf * kStage + b_off;
+      for (int q = 0; q < G::QA; ++q) ra4[q] = *reinterpret_cast<const float4*>(ga[q] + kn);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) rb4[q] = *reinterpret_cast<const float4*>(gb[q] + kn);
+      const float* as = lds + buf * G::kStage + a_off;
+      const float* bs = lds + buf * G::kStage + b_off;
 #pragma unroll
       for (int kc = 0; kc < BK / 8; ++kc) {
-        const float4 a0 = *reinterpret_cast<const float4*>(as + kc * 8);
-        const float4 a1 = *reinterpret_cast<const float4*>(as + 32 * LDT + kc * 8);
-        const float4 b0 = *reinterpret_cast<const float4*>(bs + kc * 8);
-        const float4 b1 = *reinterpret_cast<const float4*>(bs + 32 * LDT + kc * 8);
-#define SPCFG_MFMA4(AX, BX)                                                                  \
-  acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.AX, b0.BX, acc[0][0], 0, 0, 0);       \
-  acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.AX, b1.BX, acc[0][1], 0, 0, 0);       \
-  acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.AX, b0.BX, acc[1][0], 0, 0, 0);       \
-  acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.AX, b1.BX, acc[1][1], 0, 0, 0);
-        SPCFG_MFMA4(x, x)
-        SPCFG_MFMA4(y, y)
-        SPCFG_MFMA4(z, z)
-        SPCFG_MFMA4(w, w)
-#undef SPCFG_MFMA4
-      }
-      float* st = lds + (buf ^ 1) * kStage + lds_st;
+        float4 a[G::MI], b[G::NI];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        *reinterpret_cast<float4*>(st + 32 * q * LDT) = ra4[q];
-        *reinterpret_cast<float4*>(st + BM * LDT + 32 * q * LDT) = rb4[q];
+        for (int mi = 0; mi < G::MI; ++mi) a[mi] = *reinterpret_cast<const float4*>(as + mi * 32 * LDT + kc * 8);
+#pragma unroll
+        for (int ni = 0; ni < G::NI; ++ni) b[ni] = *reinterpret_cast<const float4*>(bs + ni * 32 * LDT + kc * 8);
+#define SPCFG_MFMA_STEP(C)                                                                             \
+  _Pragma("unroll") for (int mi = 0; mi < G::MI; ++mi) _Pragma("unroll") for (int ni = 0; ni < G::NI; ++ni) \
+      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].C, b[ni].C, acc[mi][ni], 0, 0, 0);
+        SPCFG_MFMA_STEP(x)
+        SPCFG_MFMA_STEP(y)
+        SPCFG_MFMA_STEP(z)
+        SPCFG_MFMA_STEP(w)
+#undef SPCFG_MFMA_STEP
       }
+      float* st = lds + (buf ^ 1) * G::kStage + lds_st;
+#pragma unroll
+      for (int q = 0; q < G::QA; ++q) *reinterpret_cast<float4*>(st + 32 * q * LDT) = ra4[q];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) *reinterpret_cast<float4*>(st + BM * LDT + 32 * q * LDT) = rb4[q];
       __syncthreads();
     }
 
     if (k0 == 0 && k1 == KT) {
-      epilogue<EPI>(g, acc, row0, col0, wm, wn, lane);
+      epilogue<EPI, BM>(g, acc, row0, col0, wm, wn, lane);
     } else {
       // partial tile: publish, count arrivals, last arriver reduces in fixed order
       const int first_g = (tile * KT) / ipw;
       const int last_g = (tile * KT + KT - 1) / ipw;
       const int parts = last_g - first_g + 1;
-      float* slot = g.partial + (size_t)(2 * wg + (it != wg_begin ? 1 : 0)) * kSlotFloats;
+      float* slot = g.partial + (size_t)(2 * wg + (it != wg_begin ? 1 : 0)) * G::kSlotFloats;
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
+      for (int mi = 0; mi < G::MI; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < G::NI; ++ni)
 #pragma unroll
           for (int j = 0; j < 8; ++j)
-            st_agent(slot + (((mi * 2 + ni) * 8 + j) * 256 + tid) * 2, acc[mi][ni][2 * j], acc[mi][ni][2 * j + 1]);
+            st_agent(slot + (((mi * G::NI + ni) * 8 + j) * 256 + tid) * 2, acc[mi][ni][2 * j], acc[mi][ni][2 * j + 1]);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my stores have landed before the arrival is counted
       __syncthreads();
       if (tid == 0)
@@ -194,27 +200,27 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
       __syncthreads();
       if (s_last) {
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
+        for (int mi = 0; mi < G::MI; ++mi)
 #pragma unroll
-          for (int ni = 0; ni < 2; ++ni)
+          for (int ni = 0; ni < G::NI; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
         for (int p = 0; p < parts; ++p) {
           const int gp = first_g + p;
           const int odd = (p == 0 && tile * KT != gp * ipw) ? 1 : 0;
-          const float* src = g.partial + (size_t)(2 * gp + odd) * kSlotFloats;
+          const float* src = g.partial + (size_t)(2 * gp + odd) * G::kSlotFloats;
 #pragma unroll
-          for (int mi = 0; mi < 2; ++mi)
+          for (int mi = 0; mi < G::MI; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
+            for (int ni = 0; ni < G::NI; ++ni)
 #pragma unroll
               for (int j = 0; j < 8; ++j) {
-                const F2 x = ld_agent(src + (((mi * 2 + ni) * 8 + j) * 256 + tid) * 2);
+                const F2 x = ld_agent(src + (((mi * G::NI + ni) * 8 + j) * 256 + tid) * 2);
                 acc[mi][ni][2 * j] += x.a;
                 acc[mi][ni][2 * j + 1] += x.b;
               }
         }
-        epilogue<EPI>(g, acc, row0, col0, wm, wn, lane);
+        epilogue<EPI, BM>(g, acc, row0, col0, wm, wn, lane);
         if (tid == 0)  // ready for the next launch on this stream
           __hip_atomic_store(&g.counters[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
@@ -223,38 +229,59 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
   }
 }
 
-template <int EPI>
+int pick_bm(int rows) {
+  if (rows <= 32) return 32;
+  if (rows <= 64) return 64;
+  // padded row count with 128-row and 64-row tiles: shorter tiles only when they save a lot of padding
+  const int p128 = (rows + 127) / 128 * 128, p64 = (rows + 63) / 64 * 64;
+  return (p128 > p64 && rows <= 320) ? 64 : 128;
+}
+
+template <int EPI, int BM>
 void launch(const NtArgs& a, hipStream_t st) {
+  using G = Geo<BM>;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI, BM>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::kLdsBytes);
     attr_set = true;
   }
   const int tiles = ((a.rows + BM - 1) / BM) * ((a.cols + BN - 1) / BN);
   const int KT = a.K / BK;
   const int total = tiles * KT;
-  // two workgroups per CU hide latency once there is enough work; with few tiles the extra partial-tile
-  // traffic of a finer cut costs more than it gains
-  int G = total >= 12288 ? 512 : 256;
-  if (G > a.max_wgs) G = a.max_wgs;
-  if (G > total) G = total;
-  int ipw = (total + G - 1) / G;
-  G = (total + ipw - 1) / ipw;
-  hipLaunchKernelGGL(k_gemm_nt<EPI>, dim3(G), dim3(256), kLdsBytes, st, a, ipw, total);
+  // Two workgroups per CU hide latency once there is enough work; with little work a finer cut only adds
+  // partial-tile traffic, so every workgroup keeps at least a handful of K-steps.
+  const int64_t weight = (int64_t)total * BM / 128;  // in units of 128-row K-steps
+  int Gn = weight >= 12288 ? 512 : 256;
+  if (Gn > a.max_wgs) Gn = a.max_wgs;
+  const int min_ipw = BM == 128 ? 4 : (BM == 64 ? 8 : 16);
+  if (Gn > total / min_ipw) Gn = total / min_ipw > 0 ? total / min_ipw : 1;
+  int ipw = (total + Gn - 1) / Gn;
+  Gn = (total + ipw - 1) / ipw;
+  hipLaunchKernelGGL((k_gemm_nt<EPI, BM>), dim3(Gn), dim3(256), G::kLdsBytes, st, a, ipw, total);
+}
+
+template <int EPI>
+void launch_bm(const NtArgs& a, hipStream_t st) {
+  switch (pick_bm(a.rows)) {
+    case 32: launch<EPI, 32>(a, st); break;
+    case 64: launch<EPI, 64>(a, st); break;
+    default: launch<EPI, 128>(a, st); break;
+  }
 }
 
 }  // namespace
 
-int gemm_nt_tiles(int rows, int cols) { return ((rows + BM - 1) / BM) * ((cols + BN - 1) / BN); }
-size_t gemm_nt_partial_bytes(int max_wgs) { return (size_t)2 * max_wgs * kSlotFloats * sizeof(float); }
+// number of arrival counters a launch can need (upper bound over the tile heights used)
+int gemm_nt_tiles(int rows, int cols) { return ((rows + 31) / 32) * ((cols + BN - 1) / BN); }
+size_t gemm_nt_partial_bytes(int max_wgs) { return (size_t)2 * max_wgs * Geo<128>::kSlotFloats * sizeof(float); }
 
 void launch_gemm_nt(const NtArgs& a, hipStream_t st) {
   if (a.rows <= 0 || a.cols <= 0) return;
   switch (a.epilogue) {
-    case NT_EPI_ROWSCALE: launch<NT_EPI_ROWSCALE>(a, st); break;
-    case NT_EPI_MASKROWS: launch<NT_EPI_MASKROWS>(a, st); break;
-    default: launch<NT_EPI_LEAF_EMIT>(a, st); break;
+    case NT_EPI_ROWSCALE: launch_bm<NT_EPI_ROWSCALE>(a, st); break;
+    case NT_EPI_MASKROWS: launch_bm<NT_EPI_MASKROWS>(a, st); break;
+    default: launch_bm<NT_EPI_LEAF_EMIT>(a, st); break;
   }
 }
 
