@@ -14,6 +14,9 @@
 // whichever workgroup arrives last sums the slots in fixed order (so the result does not depend on the
 // arrival order) and runs the epilogue.  Nobody waits on anybody: there is no spinning.
 #include "spcfg_internal.h"
+#ifdef SPCFG_TUNING
+#include <cstdlib>
+#endif
 
 namespace spcfg {
 
@@ -124,7 +127,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
 #pragma unroll
     for (int q = 0; q < 4; ++q)
       gb[q] = g.Bm + (int64_t)min(col0 + lr + 32 * q, g.cols - 1) * g.ldb + lc4 * 4;
-    float4 ra4[G::QA], rb4[4];
+    float4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;  // named scalars: arrays here end up in scratch memory
     floatx16 acc[G::MI][G::NI];
 #pragma unroll
     for (int mi = 0; mi < G::MI; ++mi)
@@ -133,47 +136,68 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
-#pragma unroll
-    for (int q = 0; q < G::QA; ++q) ra4[q] = *reinterpret_cast<const float4*>(ga[q] + k0 * BK);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) rb4[q] = *reinterpret_cast<const float4*>(gb[q] + k0 * BK);
-#pragma unroll
-    for (int q = 0; q < G::QA; ++q) *reinterpret_cast<float4*>(lds + lds_st + 32 * q * LDT) = ra4[q];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) *reinterpret_cast<float4*>(lds + BM * LDT + lds_st + 32 * q * LDT) = rb4[q];
+#define SPCFG_LOAD_TILE(KOFF)                                                    \
+  ra0 = *reinterpret_cast<const float4*>(ga[0] + (KOFF));                         \
+  if (G::QA > 1) ra1 = *reinterpret_cast<const float4*>(ga[G::QA > 1 ? 1 : 0] + (KOFF)); \
+  if (G::QA > 2) ra2 = *reinterpret_cast<const float4*>(ga[G::QA > 2 ? 2 : 0] + (KOFF)); \
+  if (G::QA > 2) ra3 = *reinterpret_cast<const float4*>(ga[G::QA > 2 ? 3 : 0] + (KOFF)); \
+  rb0 = *reinterpret_cast<const float4*>(gb[0] + (KOFF));                         \
+  rb1 = *reinterpret_cast<const float4*>(gb[1] + (KOFF));                         \
+  rb2 = *reinterpret_cast<const float4*>(gb[2] + (KOFF));                         \
+  rb3 = *reinterpret_cast<const float4*>(gb[3] + (KOFF));
+#define SPCFG_STORE_TILE(DST)                                                    \
+  *reinterpret_cast<float4*>((DST)) = ra0;                                        \
+  if (G::QA > 1) *reinterpret_cast<float4*>((DST) + 32 * LDT) = ra1;              \
+  if (G::QA > 2) *reinterpret_cast<float4*>((DST) + 64 * LDT) = ra2;              \
+  if (G::QA > 2) *reinterpret_cast<float4*>((DST) + 96 * LDT) = ra3;              \
+  *reinterpret_cast<float4*>((DST) + BM * LDT) = rb0;                             \
+  *reinterpret_cast<float4*>((DST) + BM * LDT + 32 * LDT) = rb1;                  \
+  *reinterpret_cast<float4*>((DST) + BM * LDT + 64 * LDT) = rb2;                  \
+  *reinterpret_cast<float4*>((DST) + BM * LDT + 96 * LDT) = rb3;
+    SPCFG_LOAD_TILE(k0 * BK)
+    SPCFG_STORE_TILE(lds + lds_st)
     __syncthreads();
 
     for (int kt = k0; kt < k1; ++kt) {
       const int buf = (kt - k0) & 1;
       // prefetch the next K-step into registers (the last iteration re-reads its own step)
       const int kn = min(kt + 1, k1 - 1) * BK;
-#pragma unroll
-      for (int q = 0; q < G::QA; ++q) ra4[q] = *reinterpret_cast<const float4*>(ga[q] + kn);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) rb4[q] = *reinterpret_cast<const float4*>(gb[q] + kn);
+      SPCFG_LOAD_TILE(kn)
+      // Pin the schedule: the compiler otherwise sinks the prefetch loads down to their LDS stores and exposes
+      // the full memory latency in every K-step.  Order: loads first, three quarters of the MFMA work, then the
+      // LDS stores of the prefetched tile (by then the loads have landed), then the last quarter, then the barrier.
+      __builtin_amdgcn_sched_barrier(0);
       const float* as = lds + buf * G::kStage + a_off;
       const float* bs = lds + buf * G::kStage + b_off;
-#pragma unroll
-      for (int kc = 0; kc < BK / 8; ++kc) {
-        float4 a[G::MI], b[G::NI];
-#pragma unroll
-        for (int mi = 0; mi < G::MI; ++mi) a[mi] = *reinterpret_cast<const float4*>(as + mi * 32 * LDT + kc * 8);
-#pragma unroll
-        for (int ni = 0; ni < G::NI; ++ni) b[ni] = *reinterpret_cast<const float4*>(bs + ni * 32 * LDT + kc * 8);
 #define SPCFG_MFMA_STEP(C)                                                                             \
   _Pragma("unroll") for (int mi = 0; mi < G::MI; ++mi) _Pragma("unroll") for (int ni = 0; ni < G::NI; ++ni) \
       acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].C, b[ni].C, acc[mi][ni], 0, 0, 0);
-        SPCFG_MFMA_STEP(x)
-        SPCFG_MFMA_STEP(y)
-        SPCFG_MFMA_STEP(z)
-        SPCFG_MFMA_STEP(w)
-#undef SPCFG_MFMA_STEP
+#define SPCFG_FRAGS(KC)                                                                                     \
+  _Pragma("unroll") for (int mi = 0; mi < G::MI; ++mi) a[mi] =                                              \
+      *reinterpret_cast<const float4*>(as + mi * 32 * LDT + (KC)*8);                                        \
+  _Pragma("unroll") for (int ni = 0; ni < G::NI; ++ni) b[ni] =                                              \
+      *reinterpret_cast<const float4*>(bs + ni * 32 * LDT + (KC)*8);
+#define SPCFG_KCHUNK(KC)                                                                                    \
+  {                                                                                                         \
+    float4 a[G::MI], b[G::NI];                                                                              \
+    SPCFG_FRAGS(KC)                                                                                         \
+    SPCFG_MFMA_STEP(x) SPCFG_MFMA_STEP(y) SPCFG_MFMA_STEP(z) SPCFG_MFMA_STEP(w)                             \
+  }
+      SPCFG_KCHUNK(0)
+      SPCFG_KCHUNK(1)
+      SPCFG_KCHUNK(2)
+      {
+        float4 a[G::MI], b[G::NI];
+        SPCFG_FRAGS(3)  // fetched before the LDS stores below so that their latency hides behind chunk 2
+        __builtin_amdgcn_sched_barrier(0);
+        SPCFG_STORE_TILE(lds + (buf ^ 1) * G::kStage + lds_st)
+        __builtin_amdgcn_sched_barrier(0);
+        SPCFG_MFMA_STEP(x) SPCFG_MFMA_STEP(y) SPCFG_MFMA_STEP(z) SPCFG_MFMA_STEP(w)
       }
-      float* st = lds + (buf ^ 1) * G::kStage + lds_st;
-#pragma unroll
-      for (int q = 0; q < G::QA; ++q) *reinterpret_cast<float4*>(st + 32 * q * LDT) = ra4[q];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) *reinterpret_cast<float4*>(st + BM * LDT + 32 * q * LDT) = rb4[q];
+#undef SPCFG_FRAGS
+#undef SPCFG_KCHUNK
+#undef SPCFG_MFMA_STEP
+      __builtin_amdgcn_sched_barrier(0);
       __syncthreads();
     }
 
@@ -199,27 +223,37 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
                   parts - 1) ? 1 : 0;
       __syncthreads();
       if (s_last) {
+        // one 32x32 accumulator tile at a time (8 loads in flight per lane), parts in ascending order
+        const int odd0 = (tile * KT != first_g * ipw) ? 1 : 0;
 #pragma unroll
         for (int mi = 0; mi < G::MI; ++mi)
 #pragma unroll
-          for (int ni = 0; ni < G::NI; ++ni)
+          for (int ni = 0; ni < G::NI; ++ni) {
+            floatx16 sum;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
-        for (int p = 0; p < parts; ++p) {
-          const int gp = first_g + p;
-          const int odd = (p == 0 && tile * KT != gp * ipw) ? 1 : 0;
-          const float* src = g.partial + (size_t)(2 * gp + odd) * G::kSlotFloats;
+            for (int v = 0; v < 16; ++v) sum[v] = 0.0f;
+            const size_t off = (size_t)((mi * G::NI + ni) * 8 * 256 + tid) * 2;
+            for (int p0 = 0; p0 < parts; p0 += 4) {  // four parts (32 loads per lane) in flight
+              F2 x[4][8];
 #pragma unroll
-          for (int mi = 0; mi < G::MI; ++mi)
+              for (int u = 0; u < 4; ++u) {
+                const int p = min(p0 + u, parts - 1);
+                const float* src = g.partial + (size_t)(2 * (first_g + p) + (p == 0 ? odd0 : 0)) * G::kSlotFloats + off;
 #pragma unroll
-            for (int ni = 0; ni < G::NI; ++ni)
-#pragma unroll
-              for (int j = 0; j < 8; ++j) {
-                const F2 x = ld_agent(src + (((mi * G::NI + ni) * 8 + j) * 256 + tid) * 2);
-                acc[mi][ni][2 * j] += x.a;
-                acc[mi][ni][2 * j + 1] += x.b;
+                for (int j = 0; j < 8; ++j) x[u][j] = ld_agent(src + j * 512);
               }
-        }
+#pragma unroll
+              for (int u = 0; u < 4; ++u) {
+                const float keep = (p0 + u < parts) ? 1.0f : 0.0f;  // the clamped duplicate of the last part adds nothing
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                  sum[2 * j] += keep * x[u][j].a;
+                  sum[2 * j + 1] += keep * x[u][j].b;
+                }
+              }
+            }
+            acc[mi][ni] = sum;
+          }
         epilogue<EPI, BM>(g, acc, row0, col0, wm, wn, lane);
         if (tid == 0)  // ready for the next launch on this stream
           __hip_atomic_store(&g.counters[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -229,13 +263,17 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
   }
 }
 
-int pick_bm(int rows) {
-  if (rows <= 32) return 32;
-  if (rows <= 64) return 64;
-  // padded row count with 128-row and 64-row tiles: shorter tiles only when they save a lot of padding
-  const int p128 = (rows + 127) / 128 * 128, p64 = (rows + 63) / 64 * 64;
-  return (p128 > p64 && rows <= 320) ? 64 : 128;
+// Tile height and workgroup count per launch, from a sweep on MI355X (256 CUs): what matters is the amount
+// of work relative to the machine, so the thresholds are in multiply-accumulates (rows * cols * K).  Small
+// launches want short tiles (finer shares, less padding) and one workgroup per CU; large ones tall tiles
+// (less LDS and L2 traffic per flop) and two workgroups per CU.
+int pick_bm(int rows, int cols, int K) {
+  const double work = (double)rows * cols * K;
+  if (rows <= 32 || work <= 2.7e9) return 32;
+  if (rows <= 64 || work <= 7.6e9) return 64;
+  return 128;
 }
+int pick_wgs(int rows, int cols, int K) { return (double)rows * cols * K <= 1.25e9 ? 256 : 512; }
 
 template <int EPI, int BM>
 void launch(const NtArgs& a, hipStream_t st) {
@@ -249,13 +287,13 @@ void launch(const NtArgs& a, hipStream_t st) {
   const int tiles = ((a.rows + BM - 1) / BM) * ((a.cols + BN - 1) / BN);
   const int KT = a.K / BK;
   const int total = tiles * KT;
-  // Two workgroups per CU hide latency once there is enough work; with little work a finer cut only adds
-  // partial-tile traffic, so every workgroup keeps at least a handful of K-steps.
-  const int64_t weight = (int64_t)total * BM / 128;  // in units of 128-row K-steps
-  int Gn = weight >= 12288 ? 512 : 256;
+  int Gn = pick_wgs(a.rows, a.cols, a.K);
   if (Gn > a.max_wgs) Gn = a.max_wgs;
-  const int min_ipw = BM == 128 ? 4 : (BM == 64 ? 8 : 16);
-  if (Gn > total / min_ipw) Gn = total / min_ipw > 0 ? total / min_ipw : 1;
+  if (Gn > total / 2) Gn = total / 2 > 0 ? total / 2 : 1;  // at least two K-steps per share
+#ifdef SPCFG_TUNING
+  if (getenv("SPCFG_NT_G")) Gn = atoi(getenv("SPCFG_NT_G"));
+  if (Gn > total) Gn = total;
+#endif
   int ipw = (total + Gn - 1) / Gn;
   Gn = (total + ipw - 1) / ipw;
   hipLaunchKernelGGL((k_gemm_nt<EPI, BM>), dim3(Gn), dim3(256), G::kLdsBytes, st, a, ipw, total);
@@ -263,7 +301,11 @@ void launch(const NtArgs& a, hipStream_t st) {
 
 template <int EPI>
 void launch_bm(const NtArgs& a, hipStream_t st) {
-  switch (pick_bm(a.rows)) {
+  int bm = pick_bm(a.rows, a.cols, a.K);
+#ifdef SPCFG_TUNING
+  if (getenv("SPCFG_NT_BM")) bm = atoi(getenv("SPCFG_NT_BM"));
+#endif
+  switch (bm) {
     case 32: launch<EPI, 32>(a, st); break;
     case 64: launch<EPI, 64>(a, st); break;
     default: launch<EPI, 128>(a, st); break;
