@@ -67,12 +67,17 @@ __device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[Geo<BM
       if (r >= g.rows) continue;
       float scale = 1.0f;
       int64_t drow = r;
-      if (EPI == NT_EPI_ROWSCALE) scale = g.rowscale[r];
       if (EPI == NT_EPI_MASKROWS) {
         if (g.rowmask[r]) continue;
       }
+      if (EPI == NT_EPI_ROWSCALE || EPI == NT_EPI_MASKROWS) {
+        // normalising shift of the input row: brings its largest magnitude into [0.5, 1)
+        const uint32_t mb = g.rowmaxb[r];
+        const int f = max((int)((mb >> 23) & 0xffu) - 126, -126);
+        scale = mb == 0u ? 0.0f : ldexpf(1.0f, -f);
+      }
       if (EPI == NT_EPI_LEAF_EMIT) {
-        const int q = g.qexp[r];
+        const int q = g.rowexp[r];
         scale = (q == kExpZero || q < -160) ? 0.0f : ldexpf(1.0f, min(q, 127));
         drow = (int64_t)g.row_b[r] * g.n_max + g.row_i[r];
       }

@@ -11,6 +11,7 @@ namespace spcfg {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int TM = 128, TN = 128, TK = 32;
 constexpr int kStageT = (TM + TN) * TK + TK;  // A tile, B tile, scales
@@ -27,35 +28,42 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g) {
 
   const int lc4 = tid & 31, lr = tid >> 5;  // 32 float4 per tile row, 8 rows per pass
   const bool bcol_ok = (b0 + lc4 * 4) < (int)g.ldb;  // ldb is the padded column count of X
-  float4 ra4[4], rb4[4];
+  const float* gA = g.A + a0 + lc4 * 4;
+  const float* gB = g.Bm + (bcol_ok ? b0 + lc4 * 4 : 0);
+  // staging registers as named scalars (arrays end up in scratch memory next to the scheduling barriers)
+  floatx4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;
   float rsc = 0.0f;
-  auto load_global = [&](int64_t s0) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int64_t s = s0 + lr + 8 * q;
-      const bool ok = s < g.S;
-      const int64_t sc = ok ? s : g.S - 1;
-      ra4[q] = *reinterpret_cast<const float4*>(g.A + sc * g.lda + a0 + lc4 * 4);
-      rb4[q] = bcol_ok ? *reinterpret_cast<const float4*>(g.Bm + sc * g.ldb + b0 + lc4 * 4)
-                       : make_float4(0.f, 0.f, 0.f, 0.f);
-      if (!ok) {
-        ra4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        rb4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-      }
-    }
-    if (tid < TK) rsc = (s0 + tid < g.S) ? g.sc[s0 + tid] : 0.0f;
-  };
-  auto store_lds = [&](int buf) {
-    float* as = lds + buf * kStageT;
-    float* bs = as + TM * TK;
-    float* ss = bs + TN * TK;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      *reinterpret_cast<float4*>(as + (lr + 8 * q) * TM + lc4 * 4) = ra4[q];
-      *reinterpret_cast<float4*>(bs + (lr + 8 * q) * TN + lc4 * 4) = rb4[q];
-    }
-    if (tid < TK) ss[tid] = rsc;
-  };
+  const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  // rows past the end are read from the last valid row (always in bounds) and replaced by zeros when the
+  // registers are stored to LDS (not earlier: a select right after the load would wait for the load)
+#define SPCFG_TN_LOAD1(RA, RB, Q, S0)                                              \
+  {                                                                                \
+    const int64_t s = (S0) + lr + 8 * (Q);                                         \
+    const bool ok = s < g.S;                                                       \
+    const int64_t sc = ok ? s : g.S - 1;                                           \
+    RA = *reinterpret_cast<const floatx4*>(gA + sc * g.lda);                        \
+    RB = *reinterpret_cast<const floatx4*>(gB + sc * g.ldb);                        \
+  }
+#define SPCFG_TN_LOAD(S0)                                                          \
+  SPCFG_TN_LOAD1(ra0, rb0, 0, S0) SPCFG_TN_LOAD1(ra1, rb1, 1, S0)                  \
+  SPCFG_TN_LOAD1(ra2, rb2, 2, S0) SPCFG_TN_LOAD1(ra3, rb3, 3, S0)                  \
+  if (tid < TK) rsc = ((S0) + tid < g.S) ? g.sc[(S0) + tid] : 0.0f;
+#define SPCFG_TN_STORE(BUF, S0)                                                    \
+  {                                                                                \
+    float* as_ = lds + (BUF)*kStageT + lr * TM + lc4 * 4;                          \
+    float* bs_ = lds + (BUF)*kStageT + TM * TK + lr * TN + lc4 * 4;                \
+    const bool k0_ = (S0) + lr < g.S, k1_ = (S0) + lr + 8 < g.S;                   \
+    const bool k2_ = (S0) + lr + 16 < g.S, k3_ = (S0) + lr + 24 < g.S;             \
+    *reinterpret_cast<floatx4*>(as_) = k0_ ? ra0 : zero4;                           \
+    *reinterpret_cast<floatx4*>(as_ + 8 * TM) = k1_ ? ra1 : zero4;                  \
+    *reinterpret_cast<floatx4*>(as_ + 16 * TM) = k2_ ? ra2 : zero4;                 \
+    *reinterpret_cast<floatx4*>(as_ + 24 * TM) = k3_ ? ra3 : zero4;                 \
+    *reinterpret_cast<floatx4*>(bs_) = (k0_ && bcol_ok) ? rb0 : zero4;              \
+    *reinterpret_cast<floatx4*>(bs_ + 8 * TN) = (k1_ && bcol_ok) ? rb1 : zero4;     \
+    *reinterpret_cast<floatx4*>(bs_ + 16 * TN) = (k2_ && bcol_ok) ? rb2 : zero4;    \
+    *reinterpret_cast<floatx4*>(bs_ + 24 * TN) = (k3_ && bcol_ok) ? rb3 : zero4;    \
+    if (tid < TK) lds[(BUF)*kStageT + (TM + TN) * TK + tid] = rsc;                 \
+  }
 
   floatx16 acc[2][2];
 #pragma unroll
@@ -66,31 +74,44 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g) {
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
   const int64_t KT = (g.S + TK - 1) / TK;
-  load_global(0);
-  store_lds(0);
+  SPCFG_TN_LOAD(0)
+  SPCFG_TN_STORE(0, 0)
   __syncthreads();
 
   const int fcol = lane & 31, fk = lane >> 5;
   for (int64_t kt = 0; kt < KT; ++kt) {
     const int buf = (int)(kt & 1);
-    if (kt + 1 < KT) load_global((kt + 1) * TK);
+    const int64_t sn = (kt + 1 < KT ? kt + 1 : kt) * TK;  // the last step re-reads itself (never used)
+    SPCFG_TN_LOAD(sn)
+    __builtin_amdgcn_sched_barrier(0);  // keep the prefetch loads at the top of the step
     const float* as = lds + buf * kStageT + wm * 64 + fcol;
     const float* bs = lds + buf * kStageT + TM * TK + wn * 64 + fcol;
     const float* ss = lds + buf * kStageT + (TM + TN) * TK;
+#define SPCFG_TN_KSTEP(KK)                                                                   \
+  {                                                                                          \
+    const int k = (KK) + fk;                                                                 \
+    const float s = ss[k];                                                                   \
+    const float a0v = as[k * TM] * s, a1v = as[k * TM + 32] * s;                             \
+    const float b0v = bs[k * TN], b1v = bs[k * TN + 32];                                     \
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0v, b0v, acc[0][0], 0, 0, 0);          \
+    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0v, b1v, acc[0][1], 0, 0, 0);          \
+    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1v, b0v, acc[1][0], 0, 0, 0);          \
+    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1v, b1v, acc[1][1], 0, 0, 0);          \
+  }
 #pragma unroll
-    for (int kk = 0; kk < TK; kk += 2) {
-      const int k = kk + fk;
-      const float s = ss[k];
-      const float a0v = as[k * TM] * s, a1v = as[k * TM + 32] * s;
-      const float b0v = bs[k * TN], b1v = bs[k * TN + 32];
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0v, b0v, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0v, b1v, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1v, b0v, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1v, b1v, acc[1][1], 0, 0, 0);
-    }
-    if (kt + 1 < KT) store_lds(buf ^ 1);
+    for (int kk = 0; kk < 24; kk += 2) SPCFG_TN_KSTEP(kk)
+    __builtin_amdgcn_sched_barrier(0);
+    SPCFG_TN_STORE(buf ^ 1, sn)  // behind three quarters of the MFMA work: the loads have landed by now
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 24; kk < TK; kk += 2) SPCFG_TN_KSTEP(kk)
+#undef SPCFG_TN_KSTEP
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
   }
+#undef SPCFG_TN_LOAD
+#undef SPCFG_TN_LOAD1
+#undef SPCFG_TN_STORE
 
   // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
 #pragma unroll

@@ -6,7 +6,6 @@ namespace spcfg {
 
 namespace {
 
-constexpr int kThreads = 256;
 
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -61,6 +60,17 @@ __device__ __forceinline__ float pow2i(int d) { return d < -160 ? 0.0f : ldexpf(
 
 __device__ __forceinline__ int add_exp(int a, int b) { return (a == kExpZero || b == kExpZero) ? kExpZero : a + b; }
 
+// A stored vector has a raw exponent m and the bit pattern of its largest magnitude (kept by integer
+// atomicMax, which is exact and order-independent).  Its normalising shift f puts that maximum into
+// [0.5, 1): the vector's consumers use the exponent m + f and the scale 2^-f.
+__device__ __forceinline__ int norm_shift(uint32_t maxbits) { return max((int)((maxbits >> 23) & 0xffu) - 126, -126); }
+__device__ __forceinline__ int norm_exp(int m, uint32_t maxbits) {
+  return (maxbits == 0u || m == kExpZero) ? kExpZero : m + norm_shift(maxbits);
+}
+__device__ __forceinline__ float norm_scale(uint32_t maxbits) {
+  return maxbits == 0u ? 0.0f : ldexpf(1.0f, -norm_shift(maxbits));
+}
+
 // ------------------------------------------------------------------------------------------ span plan
 // Width-synchronous schedule (Sec. 3.2, span-level parallelism): rows are ordered by width, sentence, start.
 __global__ void k_plan_rowbase(LenArg la, int B, int n_max, int32_t* __restrict__ lens,
@@ -97,7 +107,8 @@ __global__ void k_plan_rowbase(LenArg la, int B, int n_max, int32_t* __restrict_
 
 __global__ void k_plan_rows(int B, const int32_t* __restrict__ lens, const int32_t* __restrict__ rowbase,
                             int32_t* __restrict__ row_b, int32_t* __restrict__ row_i,
-                            int32_t* __restrict__ rootmask) {
+                            int32_t* __restrict__ rootmask, uint32_t* __restrict__ tmaxb,
+                            uint32_t* __restrict__ umaxb) {
   const int w = blockIdx.x + 1, b = blockIdx.y;
   const int n = lens[b];
   if (w > n) return;
@@ -106,6 +117,8 @@ __global__ void k_plan_rows(int B, const int32_t* __restrict__ lens, const int32
     row_b[base + i] = b;
     row_i[base + i] = i;
     rootmask[base + i] = (w == n) ? 1 : 0;
+    tmaxb[base + i] = 0u;
+    umaxb[base + i] = 0u;
   }
 }
 
@@ -147,8 +160,8 @@ __global__ void k_pack_weights(const float* __restrict__ L, const float* __restr
 // exp(e - max e) with the maximum kept aside (it re-enters only in log Z).
 __global__ void k_leaf_prep(const float* __restrict__ log_emit, int P, int Pp, int n_max,
                             const int32_t* __restrict__ row_b, const int32_t* __restrict__ row_i,
-                            float* __restrict__ leafE, float* __restrict__ xs, int32_t* __restrict__ eexp,
-                            int32_t* __restrict__ mexp, float* __restrict__ fscale) {
+                            float* __restrict__ leafE, float* __restrict__ xs, int32_t* __restrict__ mexp,
+                            uint32_t* __restrict__ tmaxb) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   const float* e = log_emit + ((int64_t)row_b[r] * n_max + row_i[r]) * P;
@@ -161,74 +174,98 @@ __global__ void k_leaf_prep(const float* __restrict__ log_emit, int P, int Pp, i
   for (int t = threadIdx.x; t < Pp; t += blockDim.x) out[t] = (t < P && !dead) ? expf(e[t] - x) : 0.0f;
   if (threadIdx.x == 0) {
     xs[r] = x;
-    mexp[r] = 0;
-    eexp[r] = dead ? kExpZero : 1;  // max entry is exactly 1 = 0.5 * 2^1
-    fscale[r] = dead ? 0.0f : 0.5f;
+    mexp[r] = dead ? kExpZero : 0;
+    tmaxb[r] = dead ? 0u : __float_as_uint(1.0f);  // the largest entry is exactly 1
   }
 }
 
 // ------------------------------------------------------------------------------------------ forward split
 // beta_ij = sum_k eta_ik * zeta_kj (Sec. 3.1 vector form) for every span of one width, in the scaled
 // representation: T = sum_k 2^(d_k - m) etat_ik * zetat_kj with d_k = e_ik + e_kj, m = max_k d_k.
-// One block per span; split-point coefficients are staged in LDS, the per-span maximum (the rescaling of
-// Sec. 3.2) is a wavefront reduction, and nothing per split point goes to HBM.
-__global__ void __launch_bounds__(kThreads)
+// One wavefront per (span, block of 256 nonterminals): split-point rows and coefficients are staged in
+// LDS, eight split points (16 row loads) are in flight per lane, the per-span maximum that drives the
+// rescaling of Sec. 3.2 is a wavefront reduction followed by one integer atomicMax, and nothing per split
+// point goes to HBM.  The normalisation itself is applied by the projection GEMM's epilogue.
+constexpr int kChunk = 256;  // nonterminals per wavefront (4 per lane)
+
+__global__ void __launch_bounds__(64)
 k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __restrict__ rowbase,
             const int32_t* __restrict__ row_b, const int32_t* __restrict__ row_i, const float* __restrict__ HZ,
-            float* __restrict__ T, int32_t* __restrict__ eexp, int32_t* __restrict__ mexp,
-            float* __restrict__ fscale) {
+            float* __restrict__ T, int32_t* __restrict__ mexp, uint32_t* __restrict__ tmaxb) {
   extern __shared__ __align__(16) unsigned char smem[];
   float* s_c = reinterpret_cast<float*>(smem);                 // [w-1]
   int32_t* s_l = reinterpret_cast<int32_t*>(s_c + (w - 1));    // [w-1] row of the left child
   int32_t* s_r = s_l + (w - 1);                                // [w-1] row of the right child
-  __shared__ float redf[16];
-  __shared__ int redi[16];
-
+  const int lane = threadIdx.x;
   const int64_t r = row0 + blockIdx.x;
   const int b = row_b[r], i = row_i[r];
   int dmax = kExpZero;
-  for (int k = 1 + threadIdx.x; k < w; k += blockDim.x) {
+  for (int k = 1 + lane; k < w; k += 64) {
     const int lr = rowbase[k * B + b] + i;            // span (i, i+k)
     const int rr = rowbase[(w - k) * B + b] + i + k;  // span (i+k, i+w)
     s_l[k - 1] = lr;
     s_r[k - 1] = rr;
-    const int d = add_exp(eexp[lr], eexp[rr]);
+    const int d = add_exp(norm_exp(mexp[lr], tmaxb[lr]), norm_exp(mexp[rr], tmaxb[rr]));
     s_c[k - 1] = __int_as_float(d);
     dmax = max(dmax, d);
   }
-  const int m = block_max_i(dmax, redi);  // (contains the barrier that publishes s_l, s_r, s_c)
-  for (int k = threadIdx.x; k < w - 1; k += blockDim.x) {
+  const int m = wave_max_i(dmax);
+  __syncthreads();
+  for (int k = lane; k < w - 1; k += 64) {
     const int d = __float_as_int(s_c[k]);
     s_c[k] = (d == kExpZero) ? 0.0f : pow2i(d - m);
   }
   __syncthreads();
 
   const int64_t ld = 2 * (int64_t)Np;
-  float* out = T + (r - S1) * Np;
+  const int a = blockIdx.y * kChunk + lane * 4;
   float tmax = 0.0f;
-  for (int a = threadIdx.x * 4; a < Np; a += blockDim.x * 4) {
+  if (a < Np) {
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 4
-    for (int k = 0; k < w - 1; ++k) {
-      const float c = s_c[k];
-      const float4 h = *reinterpret_cast<const float4*>(HZ + s_l[k] * ld + a);
-      const float4 z = *reinterpret_cast<const float4*>(HZ + s_r[k] * ld + Np + a);
-      acc.x = fmaf(c * h.x, z.x, acc.x);
-      acc.y = fmaf(c * h.y, z.y, acc.y);
-      acc.z = fmaf(c * h.z, z.z, acc.z);
-      acc.w = fmaf(c * h.w, z.w, acc.w);
+    const float* hz_l = HZ + a;
+    const float* hz_r = HZ + Np + a;
+    int k = 0;
+    for (; k + 8 <= w - 1; k += 8) {
+      float4 h[8], z[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        h[u] = *reinterpret_cast<const float4*>(hz_l + s_l[k + u] * ld);
+        z[u] = *reinterpret_cast<const float4*>(hz_r + s_r[k + u] * ld);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float c = s_c[k + u];
+        acc.x = fmaf(c * h[u].x, z[u].x, acc.x);
+        acc.y = fmaf(c * h[u].y, z[u].y, acc.y);
+        acc.z = fmaf(c * h[u].z, z[u].z, acc.z);
+        acc.w = fmaf(c * h[u].w, z[u].w, acc.w);
+      }
     }
-    *reinterpret_cast<float4*>(out + a) = acc;
-    tmax = fmaxf(tmax, fmaxf(fmaxf(acc.x, acc.y), fmaxf(acc.z, acc.w)));
+    for (; k < w - 1; k += 4) {  // remainder in masked groups of four: no serial chain of dependent loads
+      float4 h[4], z[4];
+      float c[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int kk = min(k + u, w - 2);
+        c[u] = (k + u < w - 1) ? s_c[kk] : 0.0f;
+        h[u] = *reinterpret_cast<const float4*>(hz_l + s_l[kk] * ld);
+        z[u] = *reinterpret_cast<const float4*>(hz_r + s_r[kk] * ld);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        acc.x = fmaf(c[u] * h[u].x, z[u].x, acc.x);
+        acc.y = fmaf(c[u] * h[u].y, z[u].y, acc.y);
+        acc.z = fmaf(c[u] * h[u].z, z[u].z, acc.z);
+        acc.w = fmaf(c[u] * h[u].w, z[u].w, acc.w);
+      }
+    }
+    *reinterpret_cast<float4*>(T + (r - S1) * Np + a) = acc;
+    tmax = fmaxf(fmaxf(acc.x, acc.y), fmaxf(acc.z, acc.w));
   }
-  tmax = block_max(tmax, redf);
-  if (threadIdx.x == 0) {
-    int f = 0;
-    const bool dead = !(tmax > 0.0f) || m == kExpZero;
-    if (!dead) { (void)frexpf(tmax, &f); f = max(f, -126); }
-    mexp[r] = dead ? kExpZero : m;
-    eexp[r] = dead ? kExpZero : m + f;
-    fscale[r] = dead ? 0.0f : pow2i(-f);
+  tmax = wave_max(tmax);
+  if (lane == 0) {
+    if (tmax > 0.0f && m != kExpZero) atomicMax(&tmaxb[r], __float_as_uint(tmax));
+    if (blockIdx.y == 0) mexp[r] = m;
   }
 }
 
@@ -237,7 +274,7 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __res
 __global__ void k_root_fwd(int B, int N, int Np, int64_t S1, const int32_t* __restrict__ lens,
                            const int32_t* __restrict__ rowbase, const int32_t* __restrict__ rootrow,
                            const float* __restrict__ log_root, const float* __restrict__ T,
-                           const int32_t* __restrict__ eexp, const float* __restrict__ fscale,
+                           const int32_t* __restrict__ mexp, const uint32_t* __restrict__ tmaxb,
                            const float* __restrict__ xs, float* __restrict__ logZ, float* __restrict__ ztil,
                            float* __restrict__ rmaxs) {
   __shared__ float redf[16];
@@ -250,7 +287,7 @@ __global__ void k_root_fwd(int B, int N, int Np, int64_t S1, const int32_t* __re
   const bool deadroot = !(rm > -INFINITY);
   const float rmx = deadroot ? 0.0f : rm;
   const float* t = T + (r - S1) * Np;
-  const float fs = fscale[r];
+  const float fs = norm_scale(tmaxb[r]);
   double z = 0.0;
   for (int a = threadIdx.x; a < N; a += blockDim.x) z += (double)expf(log_root[a] - rmx) * (double)(t[a] * fs);
   z = block_sum_d(z, redd);
@@ -260,7 +297,7 @@ __global__ void k_root_fwd(int B, int N, int Np, int64_t S1, const int32_t* __re
   for (int i = threadIdx.x; i < n; i += blockDim.x) sx += (double)xs[leaf0 + i];
   sx = block_sum_d(sx, redd);
   if (threadIdx.x == 0) {
-    const int e = eexp[r];
+    const int e = norm_exp(mexp[r], tmaxb[r]);
     const bool dead = deadroot || e == kExpZero || !(z > 0.0);
     logZ[b] = dead ? -INFINITY : (float)((double)rmx + log(z) + (double)e * 0.6931471805599453094 + sx);
     ztil[b] = dead ? 0.0f : (float)z;
@@ -272,8 +309,9 @@ __global__ void k_root_fwd(int B, int N, int Np, int64_t S1, const int32_t* __re
 __global__ void k_root_bwd(int N, int Np, int64_t S1, const int32_t* __restrict__ rootrow,
                            const float* __restrict__ log_root, const float* __restrict__ grad_logZ,
                            const float* __restrict__ ztil, const float* __restrict__ rmaxs,
-                           const int32_t* __restrict__ eexp, float* __restrict__ BH, float* __restrict__ UV,
-                           int32_t* __restrict__ qexp, float* __restrict__ gsc) {
+                           const int32_t* __restrict__ mexp, const uint32_t* __restrict__ tmaxb,
+                           float* __restrict__ BH, float* __restrict__ UV, int32_t* __restrict__ uexp,
+                           uint32_t* __restrict__ umaxb, float* __restrict__ gsc) {
   const int b = blockIdx.x;
   const int64_t r = rootrow[b];
   const float g = grad_logZ ? grad_logZ[b] : 1.0f;
@@ -289,7 +327,9 @@ __global__ void k_root_bwd(int N, int Np, int64_t S1, const int32_t* __restrict_
     uv[Np + a] = 0.0f;
   }
   if (threadIdx.x == 0) {
-    qexp[r] = dead ? kExpZero : -eexp[r];
+    // consumers read the exponent of BH as uexp + norm_shift(umaxb); 0.5 has shift 0
+    uexp[r] = dead ? kExpZero : -norm_exp(mexp[r], tmaxb[r]);
+    umaxb[r] = dead ? 0u : __float_as_uint(0.5f);
     gsc[r] = 0.0f;
   }
 }
@@ -298,7 +338,7 @@ __global__ void k_root_bwd(int N, int Np, int64_t S1, const int32_t* __restrict_
 __global__ void k_grad_log_root(int B, int N, int Np, int64_t S1, const int32_t* __restrict__ rootrow,
                                 const float* __restrict__ log_root, const float* __restrict__ grad_logZ,
                                 const float* __restrict__ ztil, const float* __restrict__ rmaxs,
-                                const float* __restrict__ T, const float* __restrict__ fscale,
+                                const float* __restrict__ T, const uint32_t* __restrict__ tmaxb,
                                 float* __restrict__ grad_log_root, int accumulate) {
   const int a = blockIdx.x * blockDim.x + threadIdx.x;
   if (a >= N) return;
@@ -309,7 +349,7 @@ __global__ void k_grad_log_root(int B, int N, int Np, int64_t S1, const int32_t*
     if (!(zt > 0.0f)) continue;
     const int64_t r = rootrow[b];
     const float g = grad_logZ ? grad_logZ[b] : 1.0f;
-    acc += g * expf(lr - rmaxs[b]) * (T[(r - S1) * Np + a] * fscale[r]) / zt;
+    acc += g * expf(lr - rmaxs[b]) * (T[(r - S1) * Np + a] * norm_scale(tmaxb[r])) / zt;
   }
   grad_log_root[a] = accumulate ? grad_log_root[a] + acc : acc;
 }
@@ -319,17 +359,18 @@ __global__ void k_grad_log_root(int B, int N, int Np, int64_t S1, const int32_t*
 // recomputed from the stored projections, never saved).  For the span (i,j):
 //   adjoint of eta_ij  = sum_{j'>j} adj(beta_ij') * zeta_jj'     (as the left child of (i,j'))
 //   adjoint of zeta_ij = sum_{i'<i} adj(beta_i'j) * eta_i'i      (as the right child of (i',j))
-// Both are written with one common exponent so that they can be projected back through [L;R] together.
-__global__ void __launch_bounds__(kThreads)
+// Both are written with one common exponent so that they can be projected back through [L;R] together;
+// as in the forward pass one wavefront handles (span, 256 nonterminals) and the normalisation by the
+// largest magnitude is left to the GEMM epilogue.
+__global__ void __launch_bounds__(64)
 k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __restrict__ lens,
             const int32_t* __restrict__ rowbase, const int32_t* __restrict__ row_b,
             const int32_t* __restrict__ row_i, const int32_t* __restrict__ rootmask,
-            const float* __restrict__ HZ, const float* __restrict__ BH, const int32_t* __restrict__ eexp,
-            const int32_t* __restrict__ mexp, float* __restrict__ UV, int32_t* __restrict__ qexp,
-            float* __restrict__ gsc) {
+            const float* __restrict__ HZ, const float* __restrict__ BH, const int32_t* __restrict__ mexp,
+            const uint32_t* __restrict__ tmaxb, float* __restrict__ UV, int32_t* __restrict__ uexp,
+            uint32_t* __restrict__ umaxb, float* __restrict__ gsc) {
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ float redf[16];
-  __shared__ int redi[16];
+  const int lane = threadIdx.x;
   const int64_t r = row0 + blockIdx.x;
   if (rootmask[r]) return;  // the root span has no parent; its adjoint comes from k_root_bwd
   const int b = row_b[r], i = row_i[r];
@@ -343,7 +384,7 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __res
   int32_t* s_s = s_p + nt;                                 // [nt] sibling row
 
   int dmax = kExpZero;
-  for (int t = threadIdx.x; t < nt; t += blockDim.x) {
+  for (int t = lane; t < nt; t += 64) {
     int pr, sr;
     if (t < nl) {
       const int jp = j + 1 + t;
@@ -356,67 +397,77 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __res
     }
     s_p[t] = pr - (int)S1;
     s_s[t] = sr;
-    const int d = add_exp(qexp[pr], eexp[sr]);
+    const int d = add_exp(norm_exp(uexp[pr], umaxb[pr]), norm_exp(mexp[sr], tmaxb[sr]));
     s_c[t] = __int_as_float(d);
     dmax = max(dmax, d);
   }
-  const int m = block_max_i(dmax, redi);
-  for (int t = threadIdx.x; t < nt; t += blockDim.x) {
+  const int m = wave_max_i(dmax);
+  __syncthreads();
+  for (int t = lane; t < nt; t += 64) {
     const int d = __float_as_int(s_c[t]);
     s_c[t] = (d == kExpZero) ? 0.0f : pow2i(d - m);
   }
   __syncthreads();
 
   const int64_t ld = 2 * (int64_t)Np;
-  float* out = UV + r * ld;
+  const int a = blockIdx.y * kChunk + lane * 4;
   float amax = 0.0f;
-  for (int a = threadIdx.x * 4; a < Np; a += blockDim.x * 4) {
+  if (a < Np) {
     float4 u = make_float4(0.f, 0.f, 0.f, 0.f), v = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 4
-    for (int t = 0; t < nl; ++t) {
-      const float c = s_c[t];
-      const float4 g = *reinterpret_cast<const float4*>(BH + (int64_t)s_p[t] * Np + a);
-      const float4 z = *reinterpret_cast<const float4*>(HZ + s_s[t] * ld + Np + a);
-      u.x = fmaf(c * g.x, z.x, u.x);
-      u.y = fmaf(c * g.y, z.y, u.y);
-      u.z = fmaf(c * g.z, z.z, u.z);
-      u.w = fmaf(c * g.w, z.w, u.w);
-    }
-#pragma unroll 4
-    for (int t = nl; t < nt; ++t) {
-      const float c = s_c[t];
-      const float4 g = *reinterpret_cast<const float4*>(BH + (int64_t)s_p[t] * Np + a);
-      const float4 h = *reinterpret_cast<const float4*>(HZ + s_s[t] * ld + a);
-      v.x = fmaf(c * g.x, h.x, v.x);
-      v.y = fmaf(c * g.y, h.y, v.y);
-      v.z = fmaf(c * g.z, h.z, v.z);
-      v.w = fmaf(c * g.w, h.w, v.w);
-    }
-    // keep the unscaled sums in the output row; they are rescaled below once the block maximum is known
+    const float* bh = BH + a;
+    // left-child role: sibling zeta (second half of HZ); right-child role: sibling eta (first half)
+#define SPCFG_GATHER(ACC, T0, T1, HZOFF)                                                        \
+  {                                                                                             \
+    int t = (T0);                                                                               \
+    for (; t + 8 <= (T1); t += 8) {                                                             \
+      float4 gq[8], sq[8];                                                                      \
+      _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                           \
+        gq[q] = *reinterpret_cast<const float4*>(bh + (int64_t)s_p[t + q] * Np);                \
+        sq[q] = *reinterpret_cast<const float4*>(HZ + s_s[t + q] * ld + (HZOFF) + a);           \
+      }                                                                                         \
+      _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                           \
+        const float c = s_c[t + q];                                                             \
+        ACC.x = fmaf(c * gq[q].x, sq[q].x, ACC.x);                                              \
+        ACC.y = fmaf(c * gq[q].y, sq[q].y, ACC.y);                                              \
+        ACC.z = fmaf(c * gq[q].z, sq[q].z, ACC.z);                                              \
+        ACC.w = fmaf(c * gq[q].w, sq[q].w, ACC.w);                                              \
+      }                                                                                         \
+    }                                                                                           \
+    for (; t < (T1); t += 4) {                                                                  \
+      float4 gq[4], sq[4];                                                                      \
+      float cq[4];                                                                              \
+      _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                           \
+        const int tt = min(t + q, (T1)-1);                                                      \
+        cq[q] = (t + q < (T1)) ? s_c[tt] : 0.0f;                                                \
+        gq[q] = *reinterpret_cast<const float4*>(bh + (int64_t)s_p[tt] * Np);                   \
+        sq[q] = *reinterpret_cast<const float4*>(HZ + s_s[tt] * ld + (HZOFF) + a);              \
+      }                                                                                         \
+      _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                           \
+        ACC.x = fmaf(cq[q] * gq[q].x, sq[q].x, ACC.x);                                          \
+        ACC.y = fmaf(cq[q] * gq[q].y, sq[q].y, ACC.y);                                          \
+        ACC.z = fmaf(cq[q] * gq[q].z, sq[q].z, ACC.z);                                          \
+        ACC.w = fmaf(cq[q] * gq[q].w, sq[q].w, ACC.w);                                          \
+      }                                                                                         \
+    }                                                                                           \
+  }
+    SPCFG_GATHER(u, 0, nl, Np)
+    SPCFG_GATHER(v, nl, nt, 0)
+#undef SPCFG_GATHER
+    float* out = UV + r * ld;
     *reinterpret_cast<float4*>(out + a) = u;
     *reinterpret_cast<float4*>(out + Np + a) = v;
-    amax = fmaxf(amax, fmaxf(fmaxf(fabsf(u.x), fabsf(u.y)), fmaxf(fabsf(u.z), fabsf(u.w))));
-    amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+    amax = fmaxf(fmaxf(fmaxf(fabsf(u.x), fabsf(u.y)), fmaxf(fabsf(u.z), fabsf(u.w))),
+                 fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
   }
-  amax = block_max(amax, redf);  // barrier inside: every thread's stores above are its own, re-read below
-  const bool dead = !(amax > 0.0f) || m == kExpZero;
-  int f = 0;
-  if (!dead) { (void)frexpf(amax, &f); f = max(f, -126); }
-  const float sc = dead ? 0.0f : pow2i(-f);
-  for (int a = threadIdx.x * 4; a < Np; a += blockDim.x * 4) {
-    float4 u = *reinterpret_cast<float4*>(out + a);
-    float4 v = *reinterpret_cast<float4*>(out + Np + a);
-    u.x *= sc; u.y *= sc; u.z *= sc; u.w *= sc;
-    v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
-    *reinterpret_cast<float4*>(out + a) = u;
-    *reinterpret_cast<float4*>(out + Np + a) = v;
-  }
-  if (threadIdx.x == 0) {
-    const int q = dead ? kExpZero : m + f;
-    qexp[r] = q;
-    // scale that turns UV[r] (x) (stored inside vector of the row) into its contribution to dZ/d[L;R]
-    const int me = (r < S1) ? 0 : mexp[r];
-    gsc[r] = (dead || me == kExpZero) ? 0.0f : pow2i(max(q + me, -160));
+  amax = wave_max(amax);
+  if (lane == 0) {
+    if (amax > 0.0f && m != kExpZero) atomicMax(&umaxb[r], __float_as_uint(amax));
+    if (blockIdx.y == 0) {
+      uexp[r] = m;
+      // scale that turns UV[r] (x) (stored inside vector of the row) into its contribution to dZ/d[L;R]
+      const int me = mexp[r];
+      gsc[r] = (m == kExpZero || me == kExpZero) ? 0.0f : pow2i(max(m + me, -160));
+    }
   }
 }
 
@@ -429,20 +480,13 @@ __global__ void k_zero_pad_emit(int P, int n_max, const int32_t* __restrict__ le
   for (int64_t t = threadIdx.x; t < cnt; t += blockDim.x) base[t] = 0.0f;
 }
 
-int pick_threads(int Np) {
-  int t = Np / 4;
-  if (t > kThreads) t = kThreads;
-  if (t < 64) t = 64;
-  return (t + 63) / 64 * 64;
-}
-
 }  // namespace
 
 void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_t st) {
   hipLaunchKernelGGL(k_plan_rowbase, dim3(1), dim3(256), 0, st, lens, ly.B, ly.n_max, p.lens, p.rowbase, p.rootrow,
                      p.counters, ly.n_counters);
   hipLaunchKernelGGL(k_plan_rows, dim3(ly.n_max, ly.B), dim3(64), 0, st, ly.B, p.lens, p.rowbase, p.row_b, p.row_i,
-                     p.rootmask);
+                     p.rootmask, p.tmaxb, p.umaxb);
 }
 
 void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const float* R, hipStream_t st) {
@@ -453,33 +497,34 @@ void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const 
 
 void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hipStream_t st) {
   hipLaunchKernelGGL(k_leaf_prep, dim3((unsigned)ly.S1), dim3(256), 0, st, log_emit, ly.P, ly.Pp, ly.n_max, p.row_b,
-                     p.row_i, p.leafE, p.xs, p.eexp, p.mexp, p.fscale);
+                     p.row_i, p.leafE, p.xs, p.mexp, p.tmaxb);
 }
 
 void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
   const size_t sh = (size_t)(w - 1) * 12;
-  hipLaunchKernelGGL(k_split_fwd, dim3((unsigned)rows), dim3(pick_threads(ly.Np)), sh, st, w, row0, ly.B, ly.Np,
-                     ly.S1, p.rowbase, p.row_b, p.row_i, p.HZ, p.T, p.eexp, p.mexp, p.fscale);
+  const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
+  hipLaunchKernelGGL(k_split_fwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.rowbase, p.row_b, p.row_i,
+                     p.HZ, p.T, p.mexp, p.tmaxb);
 }
 
 void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st) {
   hipLaunchKernelGGL(k_root_fwd, dim3(ly.B), dim3(256), 0, st, ly.B, ly.N, ly.Np, ly.S1, p.lens, p.rowbase,
-                     p.rootrow, log_root, p.T, p.eexp, p.fscale, p.xs, logZ, p.ztil, p.rmax);
+                     p.rootrow, log_root, p.T, p.mexp, p.tmaxb, p.xs, logZ, p.ztil, p.rmax);
 }
 
 void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, const float* grad_logZ,
                      float* grad_log_root, int accumulate, hipStream_t st) {
   hipLaunchKernelGGL(k_root_bwd, dim3(ly.B), dim3(256), 0, st, ly.N, ly.Np, ly.S1, p.rootrow, log_root, grad_logZ,
-                     p.ztil, p.rmax, p.eexp, p.BH, p.UV, p.qexp, p.gsc);
+                     p.ztil, p.rmax, p.mexp, p.tmaxb, p.BH, p.UV, p.uexp, p.umaxb, p.gsc);
   hipLaunchKernelGGL(k_grad_log_root, dim3((ly.N + 255) / 256), dim3(256), 0, st, ly.B, ly.N, ly.Np, ly.S1,
-                     p.rootrow, log_root, grad_logZ, p.ztil, p.rmax, p.T, p.fscale, grad_log_root, accumulate);
+                     p.rootrow, log_root, grad_logZ, p.ztil, p.rmax, p.T, p.tmaxb, grad_log_root, accumulate);
 }
 
 void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
   const size_t sh = (size_t)ly.n_max * 12;
-  hipLaunchKernelGGL(k_split_bwd, dim3((unsigned)rows), dim3(pick_threads(ly.Np)), sh, st, w, row0, ly.B, ly.Np,
-                     ly.S1, p.lens, p.rowbase, p.row_b, p.row_i, p.rootmask, p.HZ, p.BH, p.eexp, p.mexp, p.UV,
-                     p.qexp, p.gsc);
+  const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
+  hipLaunchKernelGGL(k_split_bwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.lens, p.rowbase, p.row_b,
+                     p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc);
 }
 
 void launch_zero_pad_emit(const Layout& ly, const Ptrs& p, float* grad_log_emit, hipStream_t st) {

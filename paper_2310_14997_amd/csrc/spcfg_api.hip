@@ -48,10 +48,10 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2) {
   ly.row_b = take(i4 * ly.Sall);
   ly.row_i = take(i4 * ly.Sall);
   ly.rootmask = take(i4 * ly.Sall);
-  ly.eexp = take(i4 * ly.Sall);
   ly.mexp = take(i4 * ly.Sall);
-  ly.qexp = take(i4 * ly.Sall);
-  ly.fscale = take(f4 * ly.Sall);
+  ly.uexp = take(i4 * ly.Sall);
+  ly.tmaxb = take(i4 * ly.Sall);
+  ly.umaxb = take(i4 * ly.Sall);
   ly.gsc = take(f4 * ly.Sall);
   ly.xs = take(f4 * S1);
   // the widest launch has at most max(S1, S2) rows (one width) and 2Np columns
@@ -76,8 +76,9 @@ Ptrs resolve(const Layout& ly, void* ws) {
   Ptrs p;
   p.lens = (int32_t*)(b + ly.lens); p.rowbase = (int32_t*)(b + ly.rowbase); p.rootrow = (int32_t*)(b + ly.rootrow);
   p.row_b = (int32_t*)(b + ly.row_b); p.row_i = (int32_t*)(b + ly.row_i); p.rootmask = (int32_t*)(b + ly.rootmask);
-  p.eexp = (int32_t*)(b + ly.eexp); p.mexp = (int32_t*)(b + ly.mexp); p.qexp = (int32_t*)(b + ly.qexp);
-  p.fscale = (float*)(b + ly.fscale); p.gsc = (float*)(b + ly.gsc); p.xs = (float*)(b + ly.xs);
+  p.mexp = (int32_t*)(b + ly.mexp); p.uexp = (int32_t*)(b + ly.uexp);
+  p.tmaxb = (uint32_t*)(b + ly.tmaxb); p.umaxb = (uint32_t*)(b + ly.umaxb);
+  p.gsc = (float*)(b + ly.gsc); p.xs = (float*)(b + ly.xs);
   p.ztil = (float*)(b + ly.ztil); p.rmax = (float*)(b + ly.rmax);
   p.leafE = (float*)(b + ly.leafE); p.T = (float*)(b + ly.T); p.HZ = (float*)(b + ly.HZ);
   p.UV = (float*)(b + ly.UV); p.BH = (float*)(b + ly.BH);
@@ -169,7 +170,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs;
     a.A = p.leafE; a.lda = Pp; a.Bm = p.Wp; a.ldb = Pp; a.C = p.HZ; a.ldc = 2 * Np;
     a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
-    a.epilogue = NT_EPI_ROWSCALE; a.rowscale = p.fscale;
+    a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb;
     launch_gemm_nt(a, st);
   }
   for (int w = 2; w <= n_max; ++w) {
@@ -186,7 +187,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
     a.rows = (int)rows; a.cols = (int)(2 * Np); a.K = (int)Np;
-    a.epilogue = NT_EPI_ROWSCALE; a.rowscale = p.fscale + row0;
+    a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb + row0;
     launch_gemm_nt(a, st);
   }
   {
@@ -218,7 +219,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
         const int n = plan.lens.v[b];
         if (n > w) terms += (double)(n - w + 1) * (n - w);
       }
-      Scope s(st, SPCFG_PROF_SPLIT_BWD, 4.0 * ly.N * (2.0 * terms + 2.0 * rows));
+      Scope s(st, SPCFG_PROF_SPLIT_BWD, 4.0 * ly.N * (2.0 * terms + 2.0 * rows));  // reads + the two output vectors
       launch_split_bwd(ly, p, w, row0, rows, st);
     }
     NtArgs a{};
@@ -227,12 +228,12 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
     if (w >= 2) {
       Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.N * rows);
       a.Bm = p.Wtn; a.ldb = 2 * Np; a.C = p.BH + (row0 - ly.S1) * Np; a.ldc = Np; a.cols = (int)Np;
-      a.epilogue = NT_EPI_MASKROWS; a.rowmask = p.rootmask + row0;
+      a.epilogue = NT_EPI_MASKROWS; a.rowmask = p.rootmask + row0; a.rowmaxb = p.umaxb + row0;
       launch_gemm_nt(a, st);
     } else {
       Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.P * rows);
       a.Bm = p.Wtp; a.ldb = 2 * Np; a.C = grad_log_emit; a.ldc = ly.P; a.cols = ly.P;
-      a.epilogue = NT_EPI_LEAF_EMIT; a.E = p.leafE; a.lde = Pp; a.qexp = p.qexp;
+      a.epilogue = NT_EPI_LEAF_EMIT; a.E = p.leafE; a.lde = Pp; a.rowexp = p.uexp;
       a.row_b = p.row_b; a.row_i = p.row_i; a.n_max = n_max;
       launch_gemm_nt(a, st);
     }

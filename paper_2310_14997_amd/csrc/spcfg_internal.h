@@ -6,9 +6,12 @@
 // fp32, so the only rounding is that of the probability-space products and sums themselves.
 //   leaf row r:        leafE[r] = exp(e_i - max e_i)          (exponent 0; the max is added back into logZ)
 //   span row r (w>=2): T[r]     = sum_k 2^(d_k - m) * eta_ik * zeta_kj,  m = max_k d_k   (exponent mexp[r] = m)
-//   every non-root row: HZ[r]   = [eta | zeta] = fscale[r] * [L;R] * (leafE[r] or T[r])   (exponent eexp[r])
-//   reverse pass:      UV[r]    = scaled adjoints of [eta | zeta]                         (exponent qexp[r])
-//                      BH[r]    = UV[r] * [L;R]  = scaled adjoint of beta                 (exponent qexp[r])
+//   every non-root row: HZ[r]   = [eta | zeta] = 2^-f * [L;R] * (leafE[r] or T[r])        (exponent mexp[r] + f)
+//   reverse pass:      UV[r]    = unnormalised adjoints of [eta | zeta]                   (exponent uexp[r])
+//                      BH[r]    = 2^-f' * UV[r] * [L;R]  = scaled adjoint of beta         (exponent uexp[r] + f')
+// f (f') is the shift that brings the largest magnitude of T[r] (UV[r]) into [0.5, 1).  The split kernels
+// record that magnitude's bit pattern in tmaxb[r] (umaxb[r]) with an integer atomicMax; the GEMM epilogue
+// applies 2^-f, and every consumer derives the exponent from (mexp, tmaxb) or (uexp, umaxb).
 // Rows are ordered by width, then sentence, then start position, so each width is one contiguous block.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -30,15 +33,16 @@ struct Layout {
   int N, P, Np, Pp, B, n_max;
   int64_t S1, S2, Sall;  // leaf rows, rows of width >= 2, all rows
   // byte offsets into the workspace
-  size_t lens, rowbase, row_b, row_i, rootmask, rootrow, eexp, mexp, qexp, fscale, gsc, xs, ztil, rmax;
+  size_t lens, rowbase, row_b, row_i, rootmask, rootrow, mexp, uexp, tmaxb, umaxb, gsc, xs, ztil, rmax;
   size_t leafE, T, HZ, UV, BH, Wn, Wp, Wtn, Wtp, partial, counters;
   int n_counters;
   size_t total;
 };
 
 struct Ptrs {  // device pointers resolved from a Layout
-  int32_t *lens, *rowbase, *row_b, *row_i, *rootmask, *rootrow, *eexp, *mexp, *qexp;
-  float *fscale, *gsc, *xs, *ztil, *rmax;
+  int32_t *lens, *rowbase, *row_b, *row_i, *rootmask, *rootrow, *mexp, *uexp;
+  uint32_t *tmaxb, *umaxb;
+  float *gsc, *xs, *ztil, *rmax;
   float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp, *partial;
   int32_t* counters;
 };
@@ -66,11 +70,11 @@ struct NtArgs {
   float* C; int64_t ldc;
   int rows, cols, K;
   int epilogue;
-  const float* rowscale;    // ROWSCALE: C = rowscale[r] * acc
+  const uint32_t* rowmaxb;  // ROWSCALE, MASKROWS: C = 2^-f(rowmaxb[r]) * acc (normalising shift of the A row)
   const int32_t* rowmask;   // MASKROWS: rows with rowmask[r] != 0 are left untouched
-  // LEAF_EMIT: C[dst[r] * ldc + c] = acc * E[r][c] * 2^qexp[r], c < cols
+  // LEAF_EMIT: C[dst[r] * ldc + c] = acc * E[r][c] * 2^rowexp[r], c < cols
   const float* E; int64_t lde;
-  const int32_t* qexp;
+  const int32_t* rowexp;
   const int32_t* row_b; const int32_t* row_i; int n_max;
   // work sharing across workgroups: scratch for partial tiles and per-tile arrival counters (zero between launches)
   float* partial; int32_t* counters; int max_wgs;
