@@ -21,6 +21,7 @@ sys.path.insert(0, ROOT)
 import numpy as np  # noqa: E402
 
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
+PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 
 
@@ -50,7 +51,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="ptb", choices=["tiny", "small", "ptb", "long"])
+    ap.add_argument("--workload", default="ptb", choices=["tiny", "small", "ptb", "scaled", "long"])
+    ap.add_argument("--precision", default=None, choices=["fp32", "bf16"],
+                    help="operand type of the projection GEMMs (default: the workload's own: bf16 for scaled)")
     ap.add_argument("--profile-steps", type=int, default=3)
     ap.add_argument("--cpu-sentences", type=int, default=12)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -78,7 +81,10 @@ def main():
         return
 
     d = synth.make_inputs(args.workload)
-    wl = bd.Workload(d)
+    precision = args.precision or d["precision"]
+    bf16 = precision == "bf16"
+    wl = bd.Workload(d, precision=bd.PRECISION_BF16 if bf16 else bd.PRECISION_FP32)
+    peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_FP32_MFMA_TFLOPS
     wc = synth.work_counts(d["lengths"], d["N"], d["P"])
     stream = torch.cuda.current_stream()
 
@@ -115,20 +121,23 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get(args.workload, {}).get("gemm_nt_bytes_per_launch")
+            traffic = json.load(f).get(args.workload + ("_bf16" if bf16 and args.workload != "scaled" else ""),
+                                       {}).get("gemm_nt_bytes_per_launch")
 
     out = {
-        "metric": "sentences/sec inside fwd+bwd at N=P=2048, n<=40",
+        "metric": f"sentences/sec inside fwd+bwd at N=P={d['N']}, n<={d['n_max']}",
         "value": sent_per_s, "unit": "sentences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: B={d['B']}, N={d['N']}, P={d['P']}, n_max={d['n_max']}, "
                                f"sum_n={wc['leaves']}, projected_spans={wc['proj_spans']}, "
                                f"split_terms={wc['split_terms']}, seed={d['seed']}",
                    "flop_fwd_bwd": wc["flop_fwd_bwd"], "tflops_fwd_bwd": wc["flop_fwd_bwd"] / (dt / args.steps) / 1e12},
-        "roofline": {"bound": "mfma", "kernel": "k_gemm_nt (fp32 MFMA stacked projection, forward + reverse)",
-                     "achieved": achieved_tflops, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved_tflops / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
+        "roofline": {"bound": "mfma",
+                     "kernel": ("k_gemm_nt16 (bf16 MFMA" if bf16 else "k_gemm_nt (fp32 MFMA")
+                               + " stacked projection, forward + reverse)",
+                     "achieved": achieved_tflops, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved_tflops / peak, "traffic": traffic,
                      "launches_per_step": proj_launches, "avg_launch_us": proj_ms * 1e3 / max(proj_launches, 1),
                      "flop_per_launch": proj_flop / max(proj_launches, 1)},
         "split_reduction": {"bound": "hbm", "achieved": split_bytes / (split_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,

@@ -2,96 +2,19 @@
 // width at once) and for their reverse:  C[r][c] = sum_k A[r][k] * Bm[c][k], both operands K-contiguous.
 //
 // gfx950 mapping: 128x128x32 tile per 256-thread workgroup (4 wavefronts, 2x2, 64x64 each = 2x2 tiles of
-// v_mfma_f32_32x32x2_f32).  Global -> registers -> LDS with two LDS stages and one barrier per K-step.
-// Each lane fetches its MFMA operands as one 16-byte LDS read covering four K values; the K order inside
-// an 8-wide chunk is permuted identically for both operands (lanes 0-31 take k0..k0+3, lanes 32-63
-// k0+4..k0+7), which leaves the sum over K unchanged.
-//
-// The number of span rows shrinks with the width (from thousands to a handful), so a tile-per-workgroup
-// launch would leave most of the 256 CUs idle for most widths.  Instead the (tile, K-step) iteration space is
-// cut into equal contiguous shares, one per workgroup.  A workgroup whose share covers only part of a
-// tile's K range writes its partial accumulators to a scratch slot and bumps the tile's arrival counter;
-// whichever workgroup arrives last sums the slots in fixed order (so the result does not depend on the
-// arrival order) and runs the epilogue.  Nobody waits on anybody: there is no spinning.
-#include "spcfg_internal.h"
-#ifdef SPCFG_TUNING
-#include <cstdlib>
-#endif
+// v_mfma_f32_32x32x2_f32; shorter tiles for widths with few spans).  Global -> registers -> LDS with two LDS
+// stages and one barrier per K-step.  Each lane fetches its MFMA operands as one 16-byte LDS read covering
+// four K values; the K order inside an 8-wide chunk is permuted identically for both operands (lanes 0-31
+// take k0..k0+3, lanes 32-63 k0+4..k0+7), which leaves the sum over K unchanged.  Work sharing across
+// workgroups and the epilogues are in gemm_nt_common.h.
+#include "gemm_nt_common.h"
 
 namespace spcfg {
 
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-// Partial tiles travel between workgroups (possibly on different XCDs, whose L2 caches are not coherent
-// with each other) as relaxed agent-scope atomic 8-byte accesses: stores write through, loads read the
-// coherent copy, and neither needs a cache write-back or invalidate.
-struct F2 { float a, b; };
-__device__ __forceinline__ void st_agent(float* p, float a, float b) {
-  const F2 v{a, b};
-  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), __builtin_bit_cast(unsigned long long, v),
-                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ F2 ld_agent(const float* p) {
-  return __builtin_bit_cast(F2, __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
-                                                  __HIP_MEMORY_SCOPE_AGENT));
-}
-
-constexpr int BN = 128, BK = 32;
-constexpr int LDT = BK + 4;  // LDS row stride in floats: 16-byte aligned rows, conflict-free 16-byte reads
-
-// Tile geometry for a row-tile height BM (spans per tile).  Widths with few spans use shorter tiles so that
-// the matrix cores do not multiply padding rows.
-template <int BM> struct Geo {
-  static constexpr int WM = BM == 32 ? 1 : 2;            // wavefronts along rows
-  static constexpr int WN = 4 / WM;                      // wavefronts along columns
-  static constexpr int MI = BM / (32 * WM);              // 32x32 MFMA tiles per wavefront along rows
-  static constexpr int NI = BN / (32 * WN);              // ... along columns
-  static constexpr int QA = BM / 32;                     // float4 of A staged per thread and K-step
-  static constexpr int kStage = (BM + BN) * LDT;
-  static constexpr size_t kLdsBytes = 2 * kStage * sizeof(float);
-  static constexpr int kSlotFloats = BM * BN;
-};
-
-template <int EPI, int BM>
-__device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[Geo<BM>::MI][Geo<BM>::NI], int row0, int col0,
-                                         int wm, int wn, int lane) {
-  using G = Geo<BM>;
-  // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
-#pragma unroll
-  for (int mi = 0; mi < G::MI; ++mi) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int r = row0 + (wm * G::MI + mi) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-      if (r >= g.rows) continue;
-      float scale = 1.0f;
-      int64_t drow = r;
-      if (EPI == NT_EPI_MASKROWS) {
-        if (g.rowmask[r]) continue;
-      }
-      if (EPI == NT_EPI_ROWSCALE || EPI == NT_EPI_MASKROWS) {
-        // normalising shift of the input row: brings its largest magnitude into [0.5, 1)
-        const uint32_t mb = g.rowmaxb[r];
-        const int f = max((int)((mb >> 23) & 0xffu) - 126, -126);
-        scale = mb == 0u ? 0.0f : ldexpf(1.0f, -f);
-      }
-      if (EPI == NT_EPI_LEAF_EMIT) {
-        const int q = g.rowexp[r];
-        scale = (q == kExpZero || q < -160) ? 0.0f : ldexpf(1.0f, min(q, 127));
-        drow = (int64_t)g.row_b[r] * g.n_max + g.row_i[r];
-      }
-#pragma unroll
-      for (int ni = 0; ni < G::NI; ++ni) {
-        const int c = col0 + (wn * G::NI + ni) * 32 + (lane & 31);
-        if (c >= g.cols) continue;
-        float val = acc[mi][ni][v] * scale;
-        if (EPI == NT_EPI_LEAF_EMIT) val *= g.E[(int64_t)r * g.lde + c];
-        g.C[drow * g.ldc + c] = val;
-      }
-    }
-  }
-}
+using namespace nt;
+constexpr int BK = 32;
 
 template <int EPI, int BM>
 __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total_iters) {
@@ -109,11 +32,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
   const int a_off = (wm * G::MI * 32 + frag_row) * LDT + frag_k;
   const int b_off = BM * LDT + (wn * G::NI * 32 + frag_row) * LDT + frag_k;
 
-  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber them so that every XCD
-  // owns one contiguous run of shares, i.e. a contiguous run of tiles: the [L;R] panels it streams are then
-  // (nearly) disjoint from those of the other XCDs instead of every L2 fetching all of them.
-  const int nwg = gridDim.x, xcd = blockIdx.x & 7, qx = nwg >> 3, rx = nwg & 7;
-  const int wg = xcd * qx + min(xcd, rx) + (blockIdx.x >> 3);
+  const int wg = renumbered_wg();
   const int wg_begin = wg * ipw;
   const int wg_end = min(wg_begin + ipw, total_iters);
   int it = wg_begin;
@@ -128,10 +47,10 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
     const float* gb[4];
 #pragma unroll
     for (int q = 0; q < G::QA; ++q)
-      ga[q] = g.A + (int64_t)min(row0 + lr + 32 * q, g.rows - 1) * g.lda + lc4 * 4;
+      ga[q] = static_cast<const float*>(g.A) + (int64_t)min(row0 + lr + 32 * q, g.rows - 1) * g.lda + lc4 * 4;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      gb[q] = g.Bm + (int64_t)min(col0 + lr + 32 * q, g.cols - 1) * g.ldb + lc4 * 4;
+      gb[q] = static_cast<const float*>(g.Bm) + (int64_t)min(col0 + lr + 32 * q, g.cols - 1) * g.ldb + lc4 * 4;
     float4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;  // named scalars: arrays here end up in scratch memory
     floatx16 acc[G::MI][G::NI];
 #pragma unroll
@@ -206,79 +125,10 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
       __syncthreads();
     }
 
-    if (k0 == 0 && k1 == KT) {
-      epilogue<EPI, BM>(g, acc, row0, col0, wm, wn, lane);
-    } else {
-      // partial tile: publish, count arrivals, last arriver reduces in fixed order
-      const int first_g = (tile * KT) / ipw;
-      const int last_g = (tile * KT + KT - 1) / ipw;
-      const int parts = last_g - first_g + 1;
-      float* slot = g.partial + (size_t)(2 * wg + (it != wg_begin ? 1 : 0)) * G::kSlotFloats;
-#pragma unroll
-      for (int mi = 0; mi < G::MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < G::NI; ++ni)
-#pragma unroll
-          for (int j = 0; j < 8; ++j)
-            st_agent(slot + (((mi * G::NI + ni) * 8 + j) * 256 + tid) * 2, acc[mi][ni][2 * j], acc[mi][ni][2 * j + 1]);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my stores have landed before the arrival is counted
-      __syncthreads();
-      if (tid == 0)
-        s_last = (__hip_atomic_fetch_add(&g.counters[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                  parts - 1) ? 1 : 0;
-      __syncthreads();
-      if (s_last) {
-        // one 32x32 accumulator tile at a time (8 loads in flight per lane), parts in ascending order
-        const int odd0 = (tile * KT != first_g * ipw) ? 1 : 0;
-#pragma unroll
-        for (int mi = 0; mi < G::MI; ++mi)
-#pragma unroll
-          for (int ni = 0; ni < G::NI; ++ni) {
-            floatx16 sum;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sum[v] = 0.0f;
-            const size_t off = (size_t)((mi * G::NI + ni) * 8 * 256 + tid) * 2;
-            for (int p0 = 0; p0 < parts; p0 += 4) {  // four parts (32 loads per lane) in flight
-              F2 x[4][8];
-#pragma unroll
-              for (int u = 0; u < 4; ++u) {
-                const int p = min(p0 + u, parts - 1);
-                const float* src = g.partial + (size_t)(2 * (first_g + p) + (p == 0 ? odd0 : 0)) * G::kSlotFloats + off;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) x[u][j] = ld_agent(src + j * 512);
-              }
-#pragma unroll
-              for (int u = 0; u < 4; ++u) {
-                const float keep = (p0 + u < parts) ? 1.0f : 0.0f;  // the clamped duplicate of the last part adds nothing
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                  sum[2 * j] += keep * x[u][j].a;
-                  sum[2 * j + 1] += keep * x[u][j].b;
-                }
-              }
-            }
-            acc[mi][ni] = sum;
-          }
-        epilogue<EPI, BM>(g, acc, row0, col0, wm, wn, lane);
-        if (tid == 0)  // ready for the next launch on this stream
-          __hip_atomic_store(&g.counters[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-    }
+    finish_tile<EPI, BM>(g, acc, tile, k0, k1, KT, ipw, wg, it, wg_begin, row0, col0, wm, wn, lane, tid, &s_last);
     it += k1 - k0;
   }
 }
-
-// Tile height and workgroup count per launch, from a sweep on MI355X (256 CUs): what matters is the amount
-// of work relative to the machine, so the thresholds are in multiply-accumulates (rows * cols * K).  Small
-// launches want short tiles (finer shares, less padding) and one workgroup per CU; large ones tall tiles
-// (less LDS and L2 traffic per flop) and two workgroups per CU.
-int pick_bm(int rows, int cols, int K) {
-  const double work = (double)rows * cols * K;
-  if (rows <= 32 || work <= 2.7e9) return 32;
-  if (rows <= 64 || work <= 7.6e9) return 64;
-  return 128;
-}
-int pick_wgs(int rows, int cols, int K) { return (double)rows * cols * K <= 1.25e9 ? 256 : 512; }
 
 template <int EPI, int BM>
 void launch(const NtArgs& a, hipStream_t st) {
@@ -289,28 +139,12 @@ void launch(const NtArgs& a, hipStream_t st) {
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::kLdsBytes);
     attr_set = true;
   }
-  const int tiles = ((a.rows + BM - 1) / BM) * ((a.cols + BN - 1) / BN);
-  const int KT = a.K / BK;
-  const int total = tiles * KT;
-  int Gn = pick_wgs(a.rows, a.cols, a.K);
-  if (Gn > a.max_wgs) Gn = a.max_wgs;
-  if (Gn > total / 2) Gn = total / 2 > 0 ? total / 2 : 1;  // at least two K-steps per share
-#ifdef SPCFG_TUNING
-  if (getenv("SPCFG_NT_G")) Gn = atoi(getenv("SPCFG_NT_G"));
-  if (Gn > total) Gn = total;
-#endif
-  int ipw = (total + Gn - 1) / Gn;
-  Gn = (total + ipw - 1) / ipw;
-  hipLaunchKernelGGL((k_gemm_nt<EPI, BM>), dim3(Gn), dim3(256), G::kLdsBytes, st, a, ipw, total);
+  launch_shared(k_gemm_nt<EPI, BM>, a, BM, BK, G::kLdsBytes, st);
 }
 
 template <int EPI>
 void launch_bm(const NtArgs& a, hipStream_t st) {
-  int bm = pick_bm(a.rows, a.cols, a.K);
-#ifdef SPCFG_TUNING
-  if (getenv("SPCFG_NT_BM")) bm = atoi(getenv("SPCFG_NT_BM"));
-#endif
-  switch (bm) {
+  switch (chosen_bm(a)) {
     case 32: launch<EPI, 32>(a, st); break;
     case 64: launch<EPI, 64>(a, st); break;
     default: launch<EPI, 128>(a, st); break;
@@ -320,11 +154,12 @@ void launch_bm(const NtArgs& a, hipStream_t st) {
 }  // namespace
 
 // number of arrival counters a launch can need (upper bound over the tile heights used)
-int gemm_nt_tiles(int rows, int cols) { return ((rows + 31) / 32) * ((cols + BN - 1) / BN); }
-size_t gemm_nt_partial_bytes(int max_wgs) { return (size_t)2 * max_wgs * Geo<128>::kSlotFloats * sizeof(float); }
+int gemm_nt_tiles(int rows, int cols) { return ((rows + 31) / 32) * ((cols + nt::BN - 1) / nt::BN); }
+size_t gemm_nt_partial_bytes(int max_wgs) { return (size_t)2 * max_wgs * nt::Geo<128>::kSlotFloats * sizeof(float); }
 
 void launch_gemm_nt(const NtArgs& a, hipStream_t st) {
   if (a.rows <= 0 || a.cols <= 0) return;
+  if (a.b_bf16) { launch_gemm_nt16(a, st); return; }
   switch (a.epilogue) {
     case NT_EPI_ROWSCALE: launch_bm<NT_EPI_ROWSCALE>(a, st); break;
     case NT_EPI_MASKROWS: launch_bm<NT_EPI_MASKROWS>(a, st); break;

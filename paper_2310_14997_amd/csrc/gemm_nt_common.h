@@ -1,0 +1,223 @@
+// Shared pieces of the NT projection GEMMs (fp32 and bf16 operand variants): tile geometry, epilogues,
+// and the work sharing across workgroups.
+//
+// The number of span rows shrinks with the width (from thousands to a handful), so a tile-per-workgroup
+// launch would leave most of the 256 CUs idle for most widths.  Instead the (tile, K-step) iteration space is
+// cut into equal contiguous shares, one per workgroup.  A workgroup whose share covers only part of a
+// tile's K range writes its partial accumulators to a scratch slot and bumps the tile's arrival counter;
+// whichever workgroup arrives last sums the slots in fixed order (so the result does not depend on the
+// arrival order) and runs the epilogue.  Nobody waits on anybody: there is no spinning.
+#pragma once
+#include "spcfg_internal.h"
+#ifdef SPCFG_TUNING
+#include <cstdlib>
+#endif
+
+namespace spcfg {
+namespace nt {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// Partial tiles travel between workgroups (possibly on different XCDs, whose L2 caches are not coherent
+// with each other) as relaxed agent-scope atomic 8-byte accesses: stores write through, loads read the
+// coherent copy, and neither needs a cache write-back or invalidate.
+struct F2 { float a, b; };
+__device__ __forceinline__ void st_agent(float* p, float a, float b) {
+  const F2 v{a, b};
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), __builtin_bit_cast(unsigned long long, v),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ F2 ld_agent(const float* p) {
+  return __builtin_bit_cast(F2, __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT));
+}
+
+constexpr int BN = 128;
+// One K-step is 128 bytes of every tile row (32 fp32 or 64 bf16 values); LDS rows are 144 bytes apart
+// (16-byte aligned, and 16-byte reads of 8 consecutive rows touch all banks once).
+constexpr int LDT = 36;  // LDS row stride in 4-byte words
+
+// Tile geometry for a row-tile height BM (spans per tile).  Widths with few spans use shorter tiles so that
+// the matrix cores do not multiply padding rows.
+template <int BM> struct Geo {
+  static constexpr int WM = BM == 32 ? 1 : 2;            // wavefronts along rows
+  static constexpr int WN = 4 / WM;                      // wavefronts along columns
+  static constexpr int MI = BM / (32 * WM);              // 32x32 MFMA tiles per wavefront along rows
+  static constexpr int NI = BN / (32 * WN);              // ... along columns
+  static constexpr int QA = BM / 32;                     // 16-byte chunks of A staged per thread and K-step
+  static constexpr int kStage = (BM + BN) * LDT;         // words per LDS stage
+  static constexpr size_t kLdsBytes = 2 * kStage * sizeof(float);
+  static constexpr int kSlotFloats = BM * BN;
+};
+
+template <int EPI, int BM>
+__device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[Geo<BM>::MI][Geo<BM>::NI], int row0, int col0,
+                                         int wm, int wn, int lane) {
+  using G = Geo<BM>;
+  // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
+#pragma unroll
+  for (int mi = 0; mi < G::MI; ++mi) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int r = row0 + (wm * G::MI + mi) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      if (r >= g.rows) continue;
+      float scale = 1.0f;
+      int64_t drow = r;
+      if (EPI == NT_EPI_MASKROWS) {
+        if (g.rowmask[r]) continue;
+      }
+      if (EPI == NT_EPI_ROWSCALE || EPI == NT_EPI_MASKROWS) {
+        // normalising shift of the input row: brings its largest magnitude into [0.5, 1)
+        const uint32_t mb = g.rowmaxb[r];
+        const int f = max((int)((mb >> 23) & 0xffu) - 126, -126);
+        scale = mb == 0u ? 0.0f : ldexpf(1.0f, -f);
+      }
+      if (EPI == NT_EPI_GRAD) {  // rows are the stacked parents [L;R]: scatter into grad_L / grad_R
+        const int half = r >= g.Np ? 1 : 0;
+        const int arow = r - half * g.Np;
+        if (arow >= g.Nvalid) continue;
+        float* dst = (half ? g.gR : g.gL) + (int64_t)arow * g.ldg + g.col0;
+#pragma unroll
+        for (int ni = 0; ni < G::NI; ++ni) {
+          const int c = col0 + (wn * G::NI + ni) * 32 + (lane & 31);
+          if (c >= g.cols) continue;
+          dst[c] = g.accumulate ? dst[c] + acc[mi][ni][v] : acc[mi][ni][v];
+        }
+        continue;
+      }
+      if (EPI == NT_EPI_LEAF_EMIT) {
+        const int q = g.rowexp[r];
+        scale = (q == kExpZero || q < -160) ? 0.0f : ldexpf(1.0f, min(q, 127));
+        drow = (int64_t)g.row_b[r] * g.n_max + g.row_i[r];
+      }
+#pragma unroll
+      for (int ni = 0; ni < G::NI; ++ni) {
+        const int c = col0 + (wn * G::NI + ni) * 32 + (lane & 31);
+        if (c >= g.cols) continue;
+        float val = acc[mi][ni][v] * scale;
+        if (EPI == NT_EPI_LEAF_EMIT) val *= g.E[(int64_t)r * g.lde + c];
+        g.C[drow * g.ldc + c] = val;
+      }
+    }
+  }
+}
+
+// Share of the (tile, K-step) space of this workgroup.  Workgroups are dealt round-robin to the 8 XCDs (each
+// with its own L2); they are renumbered so that every XCD owns one contiguous run of shares, i.e. a
+// contiguous run of tiles: the [L;R] panels it streams are then (nearly) disjoint from those of the other
+// XCDs instead of every L2 fetching all of them.
+__device__ __forceinline__ int renumbered_wg() {
+  const int nwg = gridDim.x, xcd = blockIdx.x & 7, qx = nwg >> 3, rx = nwg & 7;
+  return xcd * qx + min(xcd, rx) + (blockIdx.x >> 3);
+}
+
+// After the K loop of one tile segment [k0, k1): run the epilogue if the segment is the whole tile, else
+// publish the partial tile, count the arrival, and let the last arriver reduce in fixed order.
+template <int EPI, int BM>
+__device__ __forceinline__ void finish_tile(const NtArgs& g, floatx16 (&acc)[Geo<BM>::MI][Geo<BM>::NI], int tile, int k0,
+                                            int k1, int KT, int ipw, int wg, int it, int wg_begin, int row0, int col0,
+                                            int wm, int wn, int lane, int tid, int* s_last_ptr) {
+  using G = Geo<BM>;
+  int& s_last = *s_last_ptr;
+  if (k0 == 0 && k1 == KT) {
+    epilogue<EPI, BM>(g, acc, row0, col0, wm, wn, lane);
+  } else {
+    // partial tile: publish, count arrivals, last arriver reduces in fixed order
+    const int first_g = (tile * KT) / ipw;
+    const int last_g = (tile * KT + KT - 1) / ipw;
+    const int parts = last_g - first_g + 1;
+    float* slot = g.partial + (size_t)(2 * wg + (it != wg_begin ? 1 : 0)) * G::kSlotFloats;
+#pragma unroll
+    for (int mi = 0; mi < G::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < G::NI; ++ni)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          st_agent(slot + (((mi * G::NI + ni) * 8 + j) * 256 + tid) * 2, acc[mi][ni][2 * j], acc[mi][ni][2 * j + 1]);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my stores have landed before the arrival is counted
+    __syncthreads();
+    if (tid == 0)
+      s_last = (__hip_atomic_fetch_add(&g.counters[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                parts - 1) ? 1 : 0;
+    __syncthreads();
+    if (s_last) {
+      // one 32x32 accumulator tile at a time (8 loads in flight per lane), parts in ascending order
+      const int odd0 = (tile * KT != first_g * ipw) ? 1 : 0;
+#pragma unroll
+      for (int mi = 0; mi < G::MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < G::NI; ++ni) {
+          floatx16 sum;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sum[v] = 0.0f;
+          const size_t off = (size_t)((mi * G::NI + ni) * 8 * 256 + tid) * 2;
+          for (int p0 = 0; p0 < parts; p0 += 4) {  // four parts (32 loads per lane) in flight
+            F2 x[4][8];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const int p = min(p0 + u, parts - 1);
+              const float* src = g.partial + (size_t)(2 * (first_g + p) + (p == 0 ? odd0 : 0)) * G::kSlotFloats + off;
+#pragma unroll
+              for (int j = 0; j < 8; ++j) x[u][j] = ld_agent(src + j * 512);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const float keep = (p0 + u < parts) ? 1.0f : 0.0f;  // the clamped duplicate of the last part adds nothing
+#pragma unroll
+              for (int j = 0; j < 8; ++j) {
+                sum[2 * j] += keep * x[u][j].a;
+                sum[2 * j + 1] += keep * x[u][j].b;
+              }
+            }
+          }
+          acc[mi][ni] = sum;
+        }
+      epilogue<EPI, BM>(g, acc, row0, col0, wm, wn, lane);
+      if (tid == 0)  // ready for the next launch on this stream
+        __hip_atomic_store(&g.counters[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
+// Tile height and workgroup count per launch, from a sweep on MI355X (256 CUs): what matters is the amount
+// of work relative to the machine, so the thresholds are in multiply-accumulates (rows * cols * K).  Small
+// launches want short tiles (finer shares, less padding) and one workgroup per CU; large ones tall tiles
+// (less LDS and L2 traffic per flop) and two workgroups per CU.
+inline int pick_bm(int rows, int cols, int K) {
+  const double work = (double)rows * cols * K;
+  if (rows <= 32 || work <= 2.7e9) return 32;
+  if (rows <= 64 || work <= 7.6e9) return 64;
+  return 128;
+}
+inline int pick_wgs(int rows, int cols, int K) { return (double)rows * cols * K <= 1.25e9 ? 256 : 512; }
+
+
+// Launch helper: splits total = tiles * KT K-steps into equal shares.
+template <typename Kernel>
+void launch_shared(Kernel kernel, const NtArgs& a, int BM, int BKelems, size_t lds_bytes, hipStream_t st) {
+  const int tiles = ((a.rows + BM - 1) / BM) * ((a.cols + BN - 1) / BN);
+  const int KT = a.K / BKelems;
+  const int total = tiles * KT;
+  int Gn = pick_wgs(a.rows, a.cols, a.K);
+  if (Gn > a.max_wgs) Gn = a.max_wgs;
+  if (Gn > total / 2) Gn = total / 2 > 0 ? total / 2 : 1;  // at least two K-steps per share
+#ifdef SPCFG_TUNING
+  if (getenv("SPCFG_NT_G")) Gn = atoi(getenv("SPCFG_NT_G"));
+  if (Gn > total) Gn = total;
+#endif
+  int ipw = (total + Gn - 1) / Gn;
+  Gn = (total + ipw - 1) / ipw;
+  hipLaunchKernelGGL(kernel, dim3(Gn), dim3(256), lds_bytes, st, a, ipw, total);
+}
+
+inline int chosen_bm(const NtArgs& a) {
+  int bm = pick_bm(a.rows, a.cols, a.K);
+#ifdef SPCFG_TUNING
+  if (getenv("SPCFG_NT_BM")) bm = atoi(getenv("SPCFG_NT_BM"));
+#endif
+  return bm;
+}
+
+}  // namespace nt
+}  // namespace spcfg

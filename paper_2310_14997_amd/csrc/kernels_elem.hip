@@ -126,9 +126,10 @@ __global__ void k_plan_rows(int B, const int32_t* __restrict__ lens, const int32
 // Stacks [L;R] (Sec. 3.2, kernel fusion: one matrix product for both projections) into zero-padded,
 // K-contiguous operands: Wn [2Np x Np] / Wp [2Np x Pp] for the forward products and their transposes
 // Wtn [Np x 2Np] / Wtp [Pp x 2Np] for the reverse products.
+template <typename OutT>
 __global__ void k_pack_weights(const float* __restrict__ L, const float* __restrict__ R, int N, int P, int Np,
-                               int Pp, float* __restrict__ Wn, float* __restrict__ Wp, float* __restrict__ Wtn,
-                               float* __restrict__ Wtp) {
+                               int Pp, OutT* __restrict__ Wn, OutT* __restrict__ Wp, OutT* __restrict__ Wtn,
+                               OutT* __restrict__ Wtp) {
   __shared__ float tile[32][33];
   const float* src = blockIdx.z ? R : L;
   const int M = N + P;
@@ -144,15 +145,37 @@ __global__ void k_pack_weights(const float* __restrict__ L, const float* __restr
     float v = 0.0f;
     if (a < N && c < (ppart ? P : N)) v = src[(int64_t)a * M + (ppart ? N + c : c)];
     tile[ty + 8 * q][tx] = v;
-    if (ppart) Wp[(int64_t)(half + a) * Pp + c] = v; else Wn[(int64_t)(half + a) * Np + c] = v;
+    if (ppart) Wp[(int64_t)(half + a) * Pp + c] = (OutT)v; else Wn[(int64_t)(half + a) * Np + c] = (OutT)v;
   }
   __syncthreads();
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int c = cc0 + ty + 8 * q, a = a0 + tx;
     const float v = tile[tx][ty + 8 * q];
-    if (ppart) Wtp[(int64_t)c * (2 * Np) + half + a] = v; else Wtn[(int64_t)c * (2 * Np) + half + a] = v;
+    if (ppart) Wtp[(int64_t)c * (2 * Np) + half + a] = (OutT)v; else Wtn[(int64_t)c * (2 * Np) + half + a] = (OutT)v;
   }
+}
+
+// Xt[c][s] = bf16(sc[s] * X[s][c]) for s < S, 0 for S <= s < Spad: the reduction-major operands of the
+// rule-gradient product, transposed so that the bf16 GEMM reads both K-contiguously.
+__global__ void k_transpose_bf16(const float* __restrict__ X, int64_t ldx, const float* __restrict__ sc, int64_t S,
+                                 int64_t Spad, __bf16* __restrict__ Xt) {
+  __shared__ float tile[64][65];
+  const int64_t s0 = (int64_t)blockIdx.x * 64;
+  const int c0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;  // 64 x 4
+#pragma unroll 4
+  for (int q = 0; q < 16; ++q) {
+    const int64_t s = s0 + ty + 4 * q;
+    float v = 0.0f;
+    if (s < S) v = X[s * ldx + c0 + tx] * (sc ? sc[s] : 1.0f);
+    tile[ty + 4 * q][tx] = v;
+  }
+  __syncthreads();
+  const int c = threadIdx.x >> 2, sq = (threadIdx.x & 3) * 16;
+  __bf16* out = Xt + (int64_t)(c0 + c) * Spad + s0 + sq;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) out[j] = (__bf16)tile[sq + j][c];
 }
 
 // ------------------------------------------------------------------------------------------ leaves
@@ -491,8 +514,18 @@ void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_
 
 void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const float* R, hipStream_t st) {
   dim3 grid((ly.Np + ly.Pp) / 32, ly.Np / 32, 2);
-  hipLaunchKernelGGL(k_pack_weights, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp, p.Wn, p.Wp, p.Wtn,
-                     p.Wtp);
+  if (ly.bf16)
+    hipLaunchKernelGGL(k_pack_weights<__bf16>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
+                       (__bf16*)p.Wn, (__bf16*)p.Wp, (__bf16*)p.Wtn, (__bf16*)p.Wtp);
+  else
+    hipLaunchKernelGGL(k_pack_weights<float>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp, p.Wn, p.Wp,
+                       p.Wtn, p.Wtp);
+}
+
+void launch_transpose_bf16(const float* X, int64_t ldx, int cols, const float* sc, int64_t S, int64_t Spad, void* Xt,
+                           hipStream_t st) {
+  dim3 grid((unsigned)(Spad / 64), (unsigned)(cols / 64));
+  hipLaunchKernelGGL(k_transpose_bf16, grid, dim3(256), 0, st, X, ldx, sc, S, Spad, (__bf16*)Xt);
 }
 
 void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hipStream_t st) {

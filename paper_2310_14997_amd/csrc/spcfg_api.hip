@@ -25,15 +25,16 @@ int check_cfg(const spcfg_config* c) {
   if (!c || c->struct_size != sizeof(spcfg_config)) return SPCFG_ERR_ARG;
   if (c->N < 1 || c->P < 1 || c->N > (1 << 16) || c->P > (1 << 16)) return SPCFG_ERR_SHAPE;
   if (c->max_B < 1 || c->max_B > kMaxB || c->max_n < 2 || c->max_n > kMaxLen) return SPCFG_ERR_SHAPE;
-  if (c->precision != SPCFG_PRECISION_FP32) return SPCFG_ERR_UNSUPPORTED;
+  if (c->precision != SPCFG_PRECISION_FP32 && c->precision != SPCFG_PRECISION_BF16) return SPCFG_ERR_UNSUPPORTED;
   if (c->flags & ~(uint32_t)SPCFG_FLAG_ACCUMULATE_GRADS) return SPCFG_ERR_UNSUPPORTED;
   return SPCFG_OK;
 }
 
 // Byte layout of the workspace for a batch with S1 leaf rows and S2 rows of width >= 2.
-Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2) {
+Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int bf16) {
   Layout ly{};
-  ly.N = N; ly.P = P; ly.B = B; ly.n_max = n_max;
+  ly.N = N; ly.P = P; ly.B = B; ly.n_max = n_max; ly.bf16 = bf16;
+  ly.S1pad = (S1 + 63) / 64 * 64; ly.S2pad = (S2 + 63) / 64 * 64;
   ly.Np = round_up(N, kPad);
   ly.Pp = round_up(P, kPad);
   ly.S1 = S1; ly.S2 = S2; ly.Sall = S1 + S2;
@@ -56,12 +57,23 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2) {
   ly.xs = take(f4 * S1);
   // the widest launch has at most max(S1, S2) rows (one width) and 2Np columns
   ly.n_counters = gemm_nt_tiles((int)(S1 > S2 ? S1 : S2), 2 * ly.Np);
+  {  // the bf16 rule-gradient product has 2Np rows and up to max(Np, Pp) columns
+    const int g = (2 * ly.Np / 128 + 1) * ((ly.Np > ly.Pp ? ly.Np : ly.Pp) / 128 + 1);
+    if (g > ly.n_counters) ly.n_counters = g;
+  }
   ly.counters = take(i4 * (size_t)ly.n_counters);
   ly.partial = take(gemm_nt_partial_bytes(kGemmWgs));
-  ly.Wn = take(f4 * 2 * (size_t)ly.Np * ly.Np);
-  ly.Wp = take(f4 * 2 * (size_t)ly.Np * ly.Pp);
-  ly.Wtn = take(f4 * 2 * (size_t)ly.Np * ly.Np);
-  ly.Wtp = take(f4 * 2 * (size_t)ly.Np * ly.Pp);
+  const size_t w4 = bf16 ? 2 : 4;  // bytes per packed weight
+  ly.Wn = take(w4 * 2 * (size_t)ly.Np * ly.Np);
+  ly.Wp = take(w4 * 2 * (size_t)ly.Np * ly.Pp);
+  ly.Wtn = take(w4 * 2 * (size_t)ly.Np * ly.Np);
+  ly.Wtp = take(w4 * 2 * (size_t)ly.Np * ly.Pp);
+  if (bf16) {
+    ly.UVt_n = take(2 * 2 * (size_t)ly.Np * ly.S2pad);
+    ly.Tt = take(2 * (size_t)ly.Np * ly.S2pad);
+    ly.UVt_p = take(2 * 2 * (size_t)ly.Np * ly.S1pad);
+    ly.Et = take(2 * (size_t)ly.Pp * ly.S1pad);
+  }
   ly.leafE = take(f4 * (size_t)S1 * ly.Pp);
   ly.T = take(f4 * (size_t)S2 * ly.Np);
   ly.BH = take(f4 * (size_t)S2 * ly.Np);
@@ -83,6 +95,7 @@ Ptrs resolve(const Layout& ly, void* ws) {
   p.leafE = (float*)(b + ly.leafE); p.T = (float*)(b + ly.T); p.HZ = (float*)(b + ly.HZ);
   p.UV = (float*)(b + ly.UV); p.BH = (float*)(b + ly.BH);
   p.partial = (float*)(b + ly.partial); p.counters = (int32_t*)(b + ly.counters);
+  p.UVt_n = b + ly.UVt_n; p.Tt = b + ly.Tt; p.UVt_p = b + ly.UVt_p; p.Et = b + ly.Et;
   p.Wn = (float*)(b + ly.Wn); p.Wp = (float*)(b + ly.Wp); p.Wtn = (float*)(b + ly.Wtn); p.Wtp = (float*)(b + ly.Wtp);
   return p;
 }
@@ -105,7 +118,7 @@ int make_plan(const spcfg_config* cfg, const int32_t* lengths, int B, int n_max,
   }
   const int64_t S1 = plan->cnt[1], Sall = run;
   if (Sall >= (int64_t)1 << 30) return SPCFG_ERR_SHAPE;
-  *ly = make_layout(cfg->N, cfg->P, B, n_max, S1, Sall - S1);
+  *ly = make_layout(cfg->N, cfg->P, B, n_max, S1, Sall - S1, cfg->precision == SPCFG_PRECISION_BF16);
   return SPCFG_OK;
 }
 
@@ -167,7 +180,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
   {  // width 1: [eta | zeta] = [L_P ; R_P] * emission vector
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.P * ly.S1);
     NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.b_bf16 = ly.bf16;
     a.A = p.leafE; a.lda = Pp; a.Bm = p.Wp; a.ldb = Pp; a.C = p.HZ; a.ldc = 2 * Np;
     a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
     a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb;
@@ -183,7 +196,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     if (w == n_max) break;  // every span of the largest width is a root span: never a child, not projected
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.N * rows);
     NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.b_bf16 = ly.bf16;
     a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
     a.rows = (int)rows; a.cols = (int)(2 * Np); a.K = (int)Np;
@@ -223,7 +236,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       launch_split_bwd(ly, p, w, row0, rows, st);
     }
     NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.b_bf16 = ly.bf16;
     a.A = p.UV + row0 * 2 * Np; a.lda = 2 * Np; a.K = (int)(2 * Np); a.rows = (int)rows;
     if (w >= 2) {
       Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.N * rows);
@@ -240,13 +253,29 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
   }
   {
     Scope s(st, SPCFG_PROF_GEMM_GRAD, 4.0 * ly.N * ((double)ly.N * ly.S2 + (double)ly.P * ly.S1), 2);
-    TnArgs t{};
-    t.Np = (int)Np; t.N = ly.N; t.gL = grad_L; t.gR = grad_R; t.ldg = ly.N + ly.P; t.accumulate = acc;
-    t.A = p.UV + ly.S1 * 2 * Np; t.lda = 2 * Np; t.Bm = p.T; t.ldb = Np; t.sc = p.gsc + ly.S1; t.S = ly.S2;
-    t.cols = ly.N; t.col0 = 0;
-    launch_gemm_tn(t, st);
-    t.A = p.UV; t.Bm = p.leafE; t.ldb = Pp; t.sc = p.gsc; t.S = ly.S1; t.cols = ly.P; t.col0 = ly.N;
-    launch_gemm_tn(t, st);
+    if (!ly.bf16) {
+      TnArgs t{};
+      t.Np = (int)Np; t.N = ly.N; t.gL = grad_L; t.gR = grad_R; t.ldg = ly.N + ly.P; t.accumulate = acc;
+      t.A = p.UV + ly.S1 * 2 * Np; t.lda = 2 * Np; t.Bm = p.T; t.ldb = Np; t.sc = p.gsc + ly.S1; t.S = ly.S2;
+      t.cols = ly.N; t.col0 = 0;
+      launch_gemm_tn(t, st);
+      t.A = p.UV; t.Bm = p.leafE; t.ldb = Pp; t.sc = p.gsc; t.S = ly.S1; t.cols = ly.P; t.col0 = ly.N;
+      launch_gemm_tn(t, st);
+    } else {
+      // both operands transposed to bf16 (span scale folded into the adjoint rows), then the NT kernel
+      launch_transpose_bf16(p.UV + ly.S1 * 2 * Np, 2 * Np, (int)(2 * Np), p.gsc + ly.S1, ly.S2, ly.S2pad, p.UVt_n, st);
+      launch_transpose_bf16(p.T, Np, (int)Np, nullptr, ly.S2, ly.S2pad, p.Tt, st);
+      launch_transpose_bf16(p.UV, 2 * Np, (int)(2 * Np), p.gsc, ly.S1, ly.S1pad, p.UVt_p, st);
+      launch_transpose_bf16(p.leafE, Pp, (int)Pp, nullptr, ly.S1, ly.S1pad, p.Et, st);
+      NtArgs a{};
+      a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.a_bf16 = 1; a.b_bf16 = 1;
+      a.epilogue = NT_EPI_GRAD; a.gL = grad_L; a.gR = grad_R; a.ldg = ly.N + ly.P; a.Np = (int)Np; a.Nvalid = ly.N;
+      a.accumulate = acc; a.rows = (int)(2 * Np);
+      a.A = p.UVt_n; a.lda = ly.S2pad; a.Bm = p.Tt; a.ldb = ly.S2pad; a.K = (int)ly.S2pad; a.cols = ly.N; a.col0 = 0;
+      launch_gemm_nt(a, st);
+      a.A = p.UVt_p; a.lda = ly.S1pad; a.Bm = p.Et; a.ldb = ly.S1pad; a.K = (int)ly.S1pad; a.cols = ly.P; a.col0 = ly.N;
+      launch_gemm_nt(a, st);
+    }
   }
   return hip_status();
 }
@@ -265,7 +294,8 @@ int spcfg_workspace_bytes(const spcfg_config* cfg, size_t* out_bytes) {
   const int64_t S1 = (int64_t)cfg->max_B * cfg->max_n;
   const int64_t Sall = (int64_t)cfg->max_B * cfg->max_n * (cfg->max_n + 1) / 2;
   if (Sall >= (int64_t)1 << 30) return SPCFG_ERR_SHAPE;
-  *out_bytes = make_layout(cfg->N, cfg->P, cfg->max_B, cfg->max_n, S1, Sall - S1).total;
+  *out_bytes = make_layout(cfg->N, cfg->P, cfg->max_B, cfg->max_n, S1, Sall - S1,
+                           cfg->precision == SPCFG_PRECISION_BF16).total;
   return SPCFG_OK;
 }
 

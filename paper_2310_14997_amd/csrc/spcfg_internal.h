@@ -31,10 +31,13 @@ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 struct Layout {
   int N, P, Np, Pp, B, n_max;
+  int bf16;              // projections with bf16 operands: packed weights are bf16, transposed bf16 copies for the rule gradients
+  int64_t S1pad, S2pad;  // row counts rounded up to 64 (K of the bf16 rule-gradient product)
   int64_t S1, S2, Sall;  // leaf rows, rows of width >= 2, all rows
   // byte offsets into the workspace
   size_t lens, rowbase, row_b, row_i, rootmask, rootrow, mexp, uexp, tmaxb, umaxb, gsc, xs, ztil, rmax;
   size_t leafE, T, HZ, UV, BH, Wn, Wp, Wtn, Wtp, partial, counters;
+  size_t UVt_n, Tt, UVt_p, Et;  // bf16 mode only
   int n_counters;
   size_t total;
 };
@@ -43,7 +46,8 @@ struct Ptrs {  // device pointers resolved from a Layout
   int32_t *lens, *rowbase, *row_b, *row_i, *rootmask, *rootrow, *mexp, *uexp;
   uint32_t *tmaxb, *umaxb;
   float *gsc, *xs, *ztil, *rmax;
-  float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp, *partial;
+  float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp, *partial;  // W* hold bf16 data in bf16 mode
+  void *UVt_n, *Tt, *UVt_p, *Et;
   int32_t* counters;
 };
 
@@ -54,6 +58,8 @@ struct LenArg {  // lengths passed by value: no host buffer has to outlive the c
 // ---- launchers (each only enqueues on `st`) -------------------------------------------------------
 void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_t st);
 void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const float* R, hipStream_t st);
+void launch_transpose_bf16(const float* X, int64_t ldx, int cols, const float* sc, int64_t S, int64_t Spad, void* Xt,
+                           hipStream_t st);
 void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hipStream_t st);
 void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st);
 void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st);
@@ -63,10 +69,13 @@ void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int6
 void launch_zero_pad_emit(const Layout& ly, const Ptrs& p, float* grad_log_emit, hipStream_t st);
 
 // C[r][c] = sum_k A[r][k] * Bm[c][k]   (both operands K-contiguous), r < rows, c < cols, K % 32 == 0.
-enum NtEpilogue { NT_EPI_ROWSCALE = 0, NT_EPI_MASKROWS = 1, NT_EPI_LEAF_EMIT = 2 };
+enum NtEpilogue { NT_EPI_ROWSCALE = 0, NT_EPI_MASKROWS = 1, NT_EPI_LEAF_EMIT = 2, NT_EPI_GRAD = 3 };
 struct NtArgs {
-  const float* A; int64_t lda;
-  const float* Bm; int64_t ldb;
+  // fp32 mode: A, Bm are float.  bf16 mode (b_bf16): Bm points to bf16 data; A is float and rounded to bf16
+  // while it is staged (a_bf16 = 0) or already bf16 (a_bf16 = 1).  lda/ldb count elements; K % 64 == 0 then.
+  const void* A; int64_t lda;
+  const void* Bm; int64_t ldb;
+  int a_bf16, b_bf16;
   float* C; int64_t ldc;
   int rows, cols, K;
   int epilogue;
@@ -76,10 +85,13 @@ struct NtArgs {
   const float* E; int64_t lde;
   const int32_t* rowexp;
   const int32_t* row_b; const int32_t* row_i; int n_max;
+  // GRAD: rows are stacked parents; row r -> (r < Np ? gL : gR)[(r mod Np) * ldg + col0 + c], rows >= Nvalid per half dropped
+  float* gL; float* gR; int64_t ldg; int col0, Np, Nvalid, accumulate;
   // work sharing across workgroups: scratch for partial tiles and per-tile arrival counters (zero between launches)
   float* partial; int32_t* counters; int max_wgs;
 };
 void launch_gemm_nt(const NtArgs& a, hipStream_t st);
+void launch_gemm_nt16(const NtArgs& a, hipStream_t st);  // bf16-operand variant (called through launch_gemm_nt)
 int gemm_nt_tiles(int rows, int cols);           // number of output tiles (= arrival counters needed)
 size_t gemm_nt_partial_bytes(int max_wgs);       // scratch needed for partial tiles
 constexpr int kGemmWgs = 512;                    // workgroups per projection launch: 2 per CU on 256 CUs

@@ -191,3 +191,75 @@ def test_ptb_full_size_sampled_against_oracle_and_invariants():
     assert got["grad_log_root"].sum() == pytest.approx(d["B"], rel=1e-4)
     # nonterminal occurrences: as a parent = as the root + as somebody's child
     check_grad("nonterminal flow", EL.sum(axis=1), got["grad_log_root"] + (EL + ER)[:, :N].sum(axis=0), 2e-4)
+
+
+# ---------------------------------------------------------------------------------------------- bf16 operands
+# Tolerances of the bf16 path: log Z within 2e-3 absolute per sentence (stated by the benchmark spec).  No gradient
+# tolerance is stated for bf16; operands carry a unit roundoff of 2^-9 = 2e-3 and every gradient entry is a
+# sum of products of rounded quantities, so the bound used here is a relative L2 error of 1e-2 per tensor.
+BF16_LOGZ_ATOL = 2e-3
+BF16_GRAD_L2 = 1e-2
+
+
+def check_bf16(got, ref):
+    fin = np.isfinite(ref["logZ"])
+    assert np.array_equal(np.isfinite(got["logZ"]), fin)
+    err = np.abs(got["logZ"][fin] - ref["logZ"][fin])
+    assert np.all(err <= BF16_LOGZ_ATOL), f"bf16 logZ abs err {err.max():.3e} > {BF16_LOGZ_ATOL}"
+    stats = {"logZ_abs": float(err.max())}
+    for k in ("grad_log_root", "grad_log_emit", "grad_L", "grad_R"):
+        assert np.all(np.isfinite(got[k])), k
+        l2 = np.linalg.norm(got[k] - ref[k]) / np.linalg.norm(ref[k])
+        assert l2 <= BF16_GRAD_L2, f"{k}: bf16 relative L2 error {l2:.3e} > {BF16_GRAD_L2}"
+        stats[k] = float(l2)
+    return stats
+
+
+def gpu_run_bf16(d, fused=True):
+    wl = bd.Workload(d, precision=bd.PRECISION_BF16)
+    if fused:
+        wl.forward_backward()
+    else:
+        wl.forward()
+        wl.backward()
+    return wl.results()
+
+
+def test_bf16_tiny_and_ragged():
+    for kw in (dict(), dict(N=70, P=45, B=5, lengths=[2, 9, 17, 5, 12], V=300), dict(N=257, P=129, B=2, lengths=[14, 9])):
+        d = synth.make_inputs("tiny", seed=4242, pad_value=np.nan, **kw)
+        print("case bf16", kw, flush=True)
+        print(check_bf16(gpu_run_bf16(d, fused=False), oracle_run(d)))
+
+
+def test_bf16_small_config():
+    d = synth.make_inputs("small", pad_value=np.nan)
+    print("case bf16 small", flush=True)
+    print(check_bf16(gpu_run_bf16(d), oracle_run(d)))
+
+
+def test_bf16_scaled_shape_reduced():
+    """The Scaled workload's shape (every sentence 40 words, N(0,1) logits) at N=P=1024, B=4."""
+    d = synth.make_inputs("scaled", pad_value=np.nan, N=1024, P=1024, B=4, lengths=[40, 40, 40, 40])
+    print("case bf16 scaled/4", flush=True)
+    print(check_bf16(gpu_run_bf16(d), oracle_run(d)))
+
+
+def test_bf16_scaled_full_size_sampled():
+    """Scaled configuration at full size (B=32, n=40, N=P=4096, bf16 projections) as bench.py launches it; two
+    sampled sentences are compared with the oracle one by one, the rest through count invariants."""
+    d = synth.make_inputs("scaled", pad_value=np.nan)
+    print("case bf16 scaled full size", flush=True)
+    got = gpu_run_bf16(d)
+    for b in (0, 17):
+        n = int(d["lengths"][b])
+        print("  oracle sentence", b, flush=True)
+        lz, gL, gR, gr, ge = O.inside_backward_sentence(d["log_root"], d["L"], d["R"], d["log_emit"][b, :n])
+        assert abs(got["logZ"][b] - lz) <= BF16_LOGZ_ATOL, (got["logZ"][b], lz)
+        l2 = np.linalg.norm(got["grad_log_emit"][b, :n] - ge) / np.linalg.norm(ge)
+        assert l2 <= BF16_GRAD_L2, l2
+    n = d["lengths"].astype(np.float64)
+    assert np.allclose(got["grad_log_emit"].sum(axis=2), 1.0, rtol=5e-3)
+    assert (d["L"].astype(np.float64) * got["grad_L"]).sum() == pytest.approx((n - 1).sum(), rel=5e-3)
+    assert (d["R"].astype(np.float64) * got["grad_R"]).sum() == pytest.approx((n - 1).sum(), rel=5e-3)
+    assert got["grad_log_root"].sum() == pytest.approx(len(n), rel=5e-3)
