@@ -125,7 +125,8 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
       __syncthreads();
     }
 
-    finish_tile<EPI, BM>(g, acc, tile, k0, k1, KT, ipw, wg, it, wg_begin, row0, col0, wm, wn, lane, tid, &s_last);
+    finish_tile<BM>(g.partial, g.counters, acc, tile, k0, k1, KT, ipw, wg, it, wg_begin, tid, &s_last,
+                    [&](floatx16(&t)[G::MI][G::NI]) { epilogue<EPI, BM>(g, t, row0, col0, wm, wn, lane); });
     it += k1 - k0;
   }
 }

@@ -114,20 +114,20 @@ __device__ __forceinline__ int renumbered_wg() {
 
 // After the K loop of one tile segment [k0, k1): run the epilogue if the segment is the whole tile, else
 // publish the partial tile, count the arrival, and let the last arriver reduce in fixed order.
-template <int EPI, int BM>
-__device__ __forceinline__ void finish_tile(const NtArgs& g, floatx16 (&acc)[Geo<BM>::MI][Geo<BM>::NI], int tile, int k0,
-                                            int k1, int KT, int ipw, int wg, int it, int wg_begin, int row0, int col0,
-                                            int wm, int wn, int lane, int tid, int* s_last_ptr) {
+template <int BM, typename Epi>
+__device__ __forceinline__ void finish_tile(float* partial, int32_t* counters, floatx16 (&acc)[Geo<BM>::MI][Geo<BM>::NI],
+                                            int tile, int k0, int k1, int KT, int ipw, int wg, int it, int wg_begin,
+                                            int tid, int* s_last_ptr, Epi&& run_epilogue) {
   using G = Geo<BM>;
   int& s_last = *s_last_ptr;
   if (k0 == 0 && k1 == KT) {
-    epilogue<EPI, BM>(g, acc, row0, col0, wm, wn, lane);
+    run_epilogue(acc);
   } else {
     // partial tile: publish, count arrivals, last arriver reduces in fixed order
     const int first_g = (tile * KT) / ipw;
     const int last_g = (tile * KT + KT - 1) / ipw;
     const int parts = last_g - first_g + 1;
-    float* slot = g.partial + (size_t)(2 * wg + (it != wg_begin ? 1 : 0)) * G::kSlotFloats;
+    float* slot = partial + (size_t)(2 * wg + (it != wg_begin ? 1 : 0)) * G::kSlotFloats;
 #pragma unroll
     for (int mi = 0; mi < G::MI; ++mi)
 #pragma unroll
@@ -138,7 +138,7 @@ __device__ __forceinline__ void finish_tile(const NtArgs& g, floatx16 (&acc)[Geo
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my stores have landed before the arrival is counted
     __syncthreads();
     if (tid == 0)
-      s_last = (__hip_atomic_fetch_add(&g.counters[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+      s_last = (__hip_atomic_fetch_add(&counters[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                 parts - 1) ? 1 : 0;
     __syncthreads();
     if (s_last) {
@@ -157,7 +157,7 @@ __device__ __forceinline__ void finish_tile(const NtArgs& g, floatx16 (&acc)[Geo
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
               const int p = min(p0 + u, parts - 1);
-              const float* src = g.partial + (size_t)(2 * (first_g + p) + (p == 0 ? odd0 : 0)) * G::kSlotFloats + off;
+              const float* src = partial + (size_t)(2 * (first_g + p) + (p == 0 ? odd0 : 0)) * G::kSlotFloats + off;
 #pragma unroll
               for (int j = 0; j < 8; ++j) x[u][j] = ld_agent(src + j * 512);
             }
@@ -173,9 +173,9 @@ __device__ __forceinline__ void finish_tile(const NtArgs& g, floatx16 (&acc)[Geo
           }
           acc[mi][ni] = sum;
         }
-      epilogue<EPI, BM>(g, acc, row0, col0, wm, wn, lane);
+      run_epilogue(acc);
       if (tid == 0)  // ready for the next launch on this stream
-        __hip_atomic_store(&g.counters[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&counters[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }

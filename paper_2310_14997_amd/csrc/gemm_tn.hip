@@ -3,27 +3,38 @@
 // through the stacked projection of Sec. 3.2).  Both operands are reduction-major, so tiles go to LDS as
 // they lie in memory ([s][a], [s][b]) and every MFMA operand is a conflict-free 4-byte LDS read.
 // 128x128 output tile, 32 span rows per step, 4 wavefronts (2x2) of 2x2 v_mfma_f32_32x32x2_f32 tiles.
-// The per-row power-of-two scale is applied to the A fragments in registers.
-#include "spcfg_internal.h"
+// The per-row power-of-two scale is applied to the A fragments in registers.  The (tile, K-step) space is
+// shared among workgroups as in the projection GEMMs, so grammars with few output tiles still fill the chip.
+#include "gemm_nt_common.h"
 
 namespace spcfg {
 
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
+using nt::floatx16;
+using nt::floatx4;
 
 constexpr int TM = 128, TN = 128, TK = 32;
 constexpr int kStageT = (TM + TN) * TK + TK;  // A tile, B tile, scales
 constexpr size_t kLdsBytesT = 2 * kStageT * sizeof(float);
 
-__global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g) {
+__global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total_iters) {
   extern __shared__ __align__(16) float lds[];
+  __shared__ int s_last;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
   const int tiles_a = (2 * g.Np) / TM;
-  const int tile_a = blockIdx.x % tiles_a, tile_b = blockIdx.x / tiles_a;
+  const int KT = (int)((g.S + TK - 1) / TK);
+  const int wg = nt::renumbered_wg();
+  const int wg_begin = wg * ipw;
+  const int wg_end = min(wg_begin + ipw, total_iters);
+  int it = wg_begin;
+  while (it < wg_end) {
+  const int tile = it / KT;
+  const int k0 = it - tile * KT;
+  const int k1 = min(KT, k0 + (wg_end - it));
+  const int tile_a = tile % tiles_a, tile_b = tile / tiles_a;
   const int a0 = tile_a * TM, b0 = tile_b * TN;
 
   const int lc4 = tid & 31, lr = tid >> 5;  // 32 float4 per tile row, 8 rows per pass
@@ -73,15 +84,14 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
-  const int64_t KT = (g.S + TK - 1) / TK;
-  SPCFG_TN_LOAD(0)
-  SPCFG_TN_STORE(0, 0)
+  SPCFG_TN_LOAD((int64_t)k0 * TK)
+  SPCFG_TN_STORE(0, (int64_t)k0 * TK)
   __syncthreads();
 
   const int fcol = lane & 31, fk = lane >> 5;
-  for (int64_t kt = 0; kt < KT; ++kt) {
-    const int buf = (int)(kt & 1);
-    const int64_t sn = (kt + 1 < KT ? kt + 1 : kt) * TK;  // the last step re-reads itself (never used)
+  for (int kt = k0; kt < k1; ++kt) {
+    const int buf = (kt - k0) & 1;
+    const int64_t sn = (int64_t)(kt + 1 < k1 ? kt + 1 : kt) * TK;  // the last step re-reads itself (never used)
     SPCFG_TN_LOAD(sn)
     __builtin_amdgcn_sched_barrier(0);  // keep the prefetch loads at the top of the step
     const float* as = lds + buf * kStageT + wm * 64 + fcol;
@@ -113,25 +123,30 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g) {
 #undef SPCFG_TN_LOAD1
 #undef SPCFG_TN_STORE
 
-  // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
+  nt::finish_tile<128>(g.partial, g.counters, acc, tile, k0, k1, KT, ipw, wg, it, wg_begin, tid, &s_last,
+                       [&](floatx16(&t)[2][2]) {
+    // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi) {
+    for (int mi = 0; mi < 2; ++mi) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int ar = a0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-      const int half = ar >= g.Np;
-      const int arow = ar - half * g.Np;
-      if (arow >= g.N) continue;
-      float* dst = (half ? g.gR : g.gL) + (int64_t)arow * g.ldg + g.col0;
+      for (int v = 0; v < 16; ++v) {
+        const int ar = a0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int half = ar >= g.Np;
+        const int arow = ar - half * g.Np;
+        if (arow >= g.N) continue;
+        float* dst = (half ? g.gR : g.gL) + (int64_t)arow * g.ldg + g.col0;
 #pragma unroll
-      for (int ni = 0; ni < 2; ++ni) {
-        const int c = b0 + wn * 64 + ni * 32 + (lane & 31);
-        if (c >= g.cols) continue;
-        const float val = acc[mi][ni][v];
-        dst[c] = g.accumulate ? dst[c] + val : val;
+        for (int ni = 0; ni < 2; ++ni) {
+          const int c = b0 + wn * 64 + ni * 32 + (lane & 31);
+          if (c >= g.cols) continue;
+          const float val = t[mi][ni][v];
+          dst[c] = g.accumulate ? dst[c] + val : val;
+        }
       }
     }
-  }
+  });
+  it += k1 - k0;
+  }  // share loop
 }
 
 }  // namespace
@@ -143,8 +158,17 @@ void launch_gemm_tn(const TnArgs& a, hipStream_t st) {
                               (int)kLdsBytesT);
     attr_set = true;
   }
+  if (a.S <= 0) return;
   const int tiles = ((2 * a.Np) / TM) * ((a.cols + TN - 1) / TN);
-  hipLaunchKernelGGL(k_gemm_tn, dim3(tiles), dim3(256), kLdsBytesT, st, a);
+  const int KT = (int)((a.S + TK - 1) / TK);
+  const int64_t total64 = (int64_t)tiles * KT;
+  if (total64 >= ((int64_t)1 << 31)) return;  // guarded by the row-count limit of the layout
+  const int total = (int)total64;
+  int Gn = a.max_wgs < 512 ? a.max_wgs : 512;
+  if (Gn > total / 2) Gn = total / 2 > 0 ? total / 2 : 1;
+  int ipw = (total + Gn - 1) / Gn;
+  Gn = (total + ipw - 1) / ipw;
+  hipLaunchKernelGGL(k_gemm_tn, dim3(Gn), dim3(256), kLdsBytesT, st, a, ipw, total);
 }
 
 }  // namespace spcfg

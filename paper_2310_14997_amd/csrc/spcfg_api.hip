@@ -255,6 +255,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
     Scope s(st, SPCFG_PROF_GEMM_GRAD, 4.0 * ly.N * ((double)ly.N * ly.S2 + (double)ly.P * ly.S1), 2);
     if (!ly.bf16) {
       TnArgs t{};
+      t.partial = p.partial; t.counters = p.counters; t.max_wgs = kGemmWgs;
       t.Np = (int)Np; t.N = ly.N; t.gL = grad_L; t.gR = grad_R; t.ldg = ly.N + ly.P; t.accumulate = acc;
       t.A = p.UV + ly.S1 * 2 * Np; t.lda = 2 * Np; t.Bm = p.T; t.ldb = Np; t.sc = p.gsc + ly.S1; t.S = ly.S2;
       t.cols = ly.N; t.col0 = 0;

@@ -107,6 +107,7 @@ struct TnArgs {
   int cols;                        // valid output columns
   float* gL; float* gR; int64_t ldg; int col0;  // destination column offset (0 or N)
   int accumulate;
+  float* partial; int32_t* counters; int max_wgs;  // work sharing scratch, as in NtArgs
 };
 void launch_gemm_tn(const TnArgs& a, hipStream_t st);
 
