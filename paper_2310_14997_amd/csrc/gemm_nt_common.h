@@ -190,7 +190,10 @@ inline int pick_bm(int rows, int cols, int K) {
   if (rows <= 64 || work <= 7.6e9) return 64;
   return 128;
 }
-inline int pick_wgs(int rows, int cols, int K) { return (double)rows * cols * K <= 1.25e9 ? 256 : 512; }
+inline int pick_wgs(int rows, int cols, int K) {
+  const double work = (double)rows * cols * K;
+  return work <= 8e7 ? 128 : (work <= 1.25e9 ? 256 : 512);
+}
 
 
 // Launch helper: splits total = tiles * KT K-steps into equal shares.
@@ -200,10 +203,12 @@ void launch_shared(Kernel kernel, const NtArgs& a, int BM, int BKelems, size_t l
   const int KT = a.K / BKelems;
   const int total = tiles * KT;
   int Gn = pick_wgs(a.rows, a.cols, a.K);
-  if (Gn > a.max_wgs) Gn = a.max_wgs;
+  const int cap = a.max_wgs * (128 / BM);  // the partial-tile scratch holds 2 * max_wgs slots of 128 x 128
+  if (Gn > cap) Gn = cap;
   if (Gn > total / 2) Gn = total / 2 > 0 ? total / 2 : 1;  // at least two K-steps per share
 #ifdef SPCFG_TUNING
   if (getenv("SPCFG_NT_G")) Gn = atoi(getenv("SPCFG_NT_G"));
+  if (Gn > cap) Gn = cap;
   if (Gn > total) Gn = total;
 #endif
   int ipw = (total + Gn - 1) / Gn;
