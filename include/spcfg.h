@@ -57,7 +57,9 @@ typedef struct {
   int32_t max_B;     /* capacity: largest batch the workspace is sized for                        */
   int32_t max_n;     /* capacity: largest sentence length the workspace is sized for              */
   int32_t precision; /* SPCFG_PRECISION_FP32: fp32 operands on the matrix cores, fp32 accumulate;
-                        SPCFG_PRECISION_BF16: bf16 operands, fp32 accumulate (projections only)   */
+                        SPCFG_PRECISION_BF16: the operands of the projection and rule-gradient
+                        products are rounded to bf16, fp32 accumulate; everything else stays fp32.
+                        log Z then agrees with exact arithmetic to about 1e-3 absolute at n = 40 */
   uint32_t flags;    /* SPCFG_FLAG_*                                                              */
 } spcfg_config;
 
