@@ -82,48 +82,56 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
     SPCFG_STORE_TILE(lds + lds_st)
     __syncthreads();
 
+    // MFMA operands of one 8-wide K chunk: named scalars (arrays next to scheduling barriers go to scratch)
+#define SPCFG_FRAGS(A0, A1, B0, B1, AS, BS, KC)                                         \
+  A0 = *reinterpret_cast<const float4*>((AS) + (KC)*8);                                  \
+  if (G::MI > 1) A1 = *reinterpret_cast<const float4*>((AS) + 32 * LDT + (KC)*8);        \
+  B0 = *reinterpret_cast<const float4*>((BS) + (KC)*8);                                  \
+  if (G::NI > 1) B1 = *reinterpret_cast<const float4*>((BS) + 32 * LDT + (KC)*8);
+#define SPCFG_MFMA1(A0, A1, B0, B1, C)                                                                      \
+  acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(A0.C, B0.C, acc[0][0], 0, 0, 0);                          \
+  if (G::NI > 1) acc[0][G::NI - 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(A0.C, B1.C, acc[0][G::NI - 1], 0, 0, 0); \
+  if (G::MI > 1) acc[G::MI - 1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(A1.C, B0.C, acc[G::MI - 1][0], 0, 0, 0); \
+  if (G::MI > 1 && G::NI > 1)                                                                                \
+    acc[G::MI - 1][G::NI - 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(A1.C, B1.C, acc[G::MI - 1][G::NI - 1], 0, 0, 0);
+#define SPCFG_MFMA4(A0, A1, B0, B1) \
+  SPCFG_MFMA1(A0, A1, B0, B1, x) SPCFG_MFMA1(A0, A1, B0, B1, y) SPCFG_MFMA1(A0, A1, B0, B1, z) SPCFG_MFMA1(A0, A1, B0, B1, w)
+
+    float4 pa0, pa1, pb0, pb1;  // chunk 0 of the current K-step, fetched one step ahead (behind the barrier)
+    float4 qa0, qa1, qb0, qb1;  // chunks 1..3
+    SPCFG_FRAGS(pa0, pa1, pb0, pb1, lds + a_off, lds + b_off, 0)
+
     for (int kt = k0; kt < k1; ++kt) {
       const int buf = (kt - k0) & 1;
       // prefetch the next K-step into registers (the last iteration re-reads its own step)
       const int kn = min(kt + 1, k1 - 1) * BK;
       SPCFG_LOAD_TILE(kn)
-      // Pin the schedule: the compiler otherwise sinks the prefetch loads down to their LDS stores and exposes
-      // the full memory latency in every K-step.  Order: loads first, three quarters of the MFMA work, then the
-      // LDS stores of the prefetched tile (by then the loads have landed), then the last quarter, then the barrier.
+      // Pinned schedule (left alone, the compiler sinks the prefetch loads down to their LDS stores and exposes
+      // the memory latency in every K-step): loads, chunks 0-2, LDS stores of the prefetched tile (the loads
+      // have landed by then), barrier, operands of the NEXT step's chunk 0, and only then the MFMAs of chunk 3,
+      // so that the LDS latency right after the barrier hides behind a quarter step of matrix work.
       __builtin_amdgcn_sched_barrier(0);
       const float* as = lds + buf * G::kStage + a_off;
       const float* bs = lds + buf * G::kStage + b_off;
-#define SPCFG_MFMA_STEP(C)                                                                             \
-  _Pragma("unroll") for (int mi = 0; mi < G::MI; ++mi) _Pragma("unroll") for (int ni = 0; ni < G::NI; ++ni) \
-      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].C, b[ni].C, acc[mi][ni], 0, 0, 0);
-#define SPCFG_FRAGS(KC)                                                                                     \
-  _Pragma("unroll") for (int mi = 0; mi < G::MI; ++mi) a[mi] =                                              \
-      *reinterpret_cast<const float4*>(as + mi * 32 * LDT + (KC)*8);                                        \
-  _Pragma("unroll") for (int ni = 0; ni < G::NI; ++ni) b[ni] =                                              \
-      *reinterpret_cast<const float4*>(bs + ni * 32 * LDT + (KC)*8);
-#define SPCFG_KCHUNK(KC)                                                                                    \
-  {                                                                                                         \
-    float4 a[G::MI], b[G::NI];                                                                              \
-    SPCFG_FRAGS(KC)                                                                                         \
-    SPCFG_MFMA_STEP(x) SPCFG_MFMA_STEP(y) SPCFG_MFMA_STEP(z) SPCFG_MFMA_STEP(w)                             \
-  }
-      SPCFG_KCHUNK(0)
-      SPCFG_KCHUNK(1)
-      SPCFG_KCHUNK(2)
-      {
-        float4 a[G::MI], b[G::NI];
-        SPCFG_FRAGS(3)  // fetched before the LDS stores below so that their latency hides behind chunk 2
-        __builtin_amdgcn_sched_barrier(0);
-        SPCFG_STORE_TILE(lds + (buf ^ 1) * G::kStage + lds_st)
-        __builtin_amdgcn_sched_barrier(0);
-        SPCFG_MFMA_STEP(x) SPCFG_MFMA_STEP(y) SPCFG_MFMA_STEP(z) SPCFG_MFMA_STEP(w)
-      }
-#undef SPCFG_FRAGS
-#undef SPCFG_KCHUNK
-#undef SPCFG_MFMA_STEP
+      SPCFG_MFMA4(pa0, pa1, pb0, pb1)
+      SPCFG_FRAGS(qa0, qa1, qb0, qb1, as, bs, 1)
+      SPCFG_MFMA4(qa0, qa1, qb0, qb1)
+      SPCFG_FRAGS(qa0, qa1, qb0, qb1, as, bs, 2)
+      SPCFG_MFMA4(qa0, qa1, qb0, qb1)
+      SPCFG_FRAGS(qa0, qa1, qb0, qb1, as, bs, 3)
+      __builtin_amdgcn_sched_barrier(0);
+      SPCFG_STORE_TILE(lds + (buf ^ 1) * G::kStage + lds_st)
       __builtin_amdgcn_sched_barrier(0);
       __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+      SPCFG_FRAGS(pa0, pa1, pb0, pb1, lds + (buf ^ 1) * G::kStage + a_off, lds + (buf ^ 1) * G::kStage + b_off, 0)
+      __builtin_amdgcn_sched_barrier(0);
+      SPCFG_MFMA4(qa0, qa1, qb0, qb1)
     }
+    __syncthreads();  // every wavefront has fetched its last operands before the LDS tiles are reused
+#undef SPCFG_FRAGS
+#undef SPCFG_MFMA1
+#undef SPCFG_MFMA4
 
     finish_tile<BM>(g.partial, g.counters, acc, tile, k0, k1, KT, ipw, wg, it, wg_begin, tid, &s_last,
                     [&](floatx16(&t)[G::MI][G::NI]) { epilogue<EPI, BM>(g, t, row0, col0, wm, wn, lane); });
