@@ -89,6 +89,34 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
   __syncthreads();
 
   const int fcol = lane & 31, fk = lane >> 5;
+  // operands of one K pair: named scalars, double-buffered by hand so that the LDS reads of pair kk+2 are in
+  // flight while the MFMAs of pair kk execute
+  // (the span scale is multiplied in when the pair is used, not when it is fetched: a use right behind
+  // the LDS read would wait for it)
+#define SPCFG_TN_FRAGS(P, AS, BS, SS, KK)                                  \
+  {                                                                        \
+    const int k_ = (KK) + fk;                                              \
+    P##s = (SS)[k_];                                                       \
+    P##a0 = (AS)[k_ * TM];                                                 \
+    P##a1 = (AS)[k_ * TM + 32];                                            \
+    P##b0 = (BS)[k_ * TN];                                                 \
+    P##b1 = (BS)[k_ * TN + 32];                                            \
+  }
+#define SPCFG_TN_MFMA(P)                                                                          \
+  {                                                                                               \
+    const float a0_ = P##a0 * P##s, a1_ = P##a1 * P##s;                                           \
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0_, P##b0, acc[0][0], 0, 0, 0);             \
+    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0_, P##b1, acc[0][1], 0, 0, 0);             \
+    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1_, P##b0, acc[1][0], 0, 0, 0);             \
+    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1_, P##b1, acc[1][1], 0, 0, 0);             \
+  }
+  float xa0, xa1, xb0, xb1, xs, ya0, ya1, yb0, yb1, ys;
+  {
+    const float* as = lds + wm * 64 + fcol;
+    const float* bs = lds + TM * TK + wn * 64 + fcol;
+    const float* ss = lds + (TM + TN) * TK;
+    SPCFG_TN_FRAGS(x, as, bs, ss, 0)
+  }
   for (int kt = k0; kt < k1; ++kt) {
     const int buf = (kt - k0) & 1;
     const int64_t sn = (int64_t)(kt + 1 < k1 ? kt + 1 : kt) * TK;  // the last step re-reads itself (never used)
@@ -97,28 +125,39 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
     const float* as = lds + buf * kStageT + wm * 64 + fcol;
     const float* bs = lds + buf * kStageT + TM * TK + wn * 64 + fcol;
     const float* ss = lds + buf * kStageT + (TM + TN) * TK;
-#define SPCFG_TN_KSTEP(KK)                                                                   \
-  {                                                                                          \
-    const int k = (KK) + fk;                                                                 \
-    const float s = ss[k];                                                                   \
-    const float a0v = as[k * TM] * s, a1v = as[k * TM + 32] * s;                             \
-    const float b0v = bs[k * TN], b1v = bs[k * TN + 32];                                     \
-    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0v, b0v, acc[0][0], 0, 0, 0);          \
-    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0v, b1v, acc[0][1], 0, 0, 0);          \
-    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1v, b0v, acc[1][0], 0, 0, 0);          \
-    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1v, b1v, acc[1][1], 0, 0, 0);          \
-  }
+    // pairs 0..29 in two-pair stages: x holds pair kk, y pair kk+2
 #pragma unroll
-    for (int kk = 0; kk < 24; kk += 2) SPCFG_TN_KSTEP(kk)
-    __builtin_amdgcn_sched_barrier(0);
-    SPCFG_TN_STORE(buf ^ 1, sn)  // behind three quarters of the MFMA work: the loads have landed by now
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int kk = 24; kk < TK; kk += 2) SPCFG_TN_KSTEP(kk)
-#undef SPCFG_TN_KSTEP
+    for (int kk = 0; kk < TK - 4; kk += 4) {
+      SPCFG_TN_FRAGS(y, as, bs, ss, kk + 2)
+      SPCFG_TN_MFMA(x)
+      __builtin_amdgcn_sched_barrier(0);
+      SPCFG_TN_FRAGS(x, as, bs, ss, kk + 4)
+      SPCFG_TN_MFMA(y)
+      __builtin_amdgcn_sched_barrier(0);
+      if (kk == 20) {  // LDS stores of the prefetched tile, behind three quarters of the MFMA work
+        SPCFG_TN_STORE(buf ^ 1, sn)
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // here x holds pair TK-4; fetch the last pair, then the barrier, then the next step's first pair, and only
+    // then the last MFMAs: the LDS latency behind the barrier hides under them
+    SPCFG_TN_FRAGS(y, as, bs, ss, TK - 2)
+    SPCFG_TN_MFMA(x)
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    {
+      const float* as2 = lds + (buf ^ 1) * kStageT + wm * 64 + fcol;
+      const float* bs2 = lds + (buf ^ 1) * kStageT + TM * TK + wn * 64 + fcol;
+      const float* ss2 = lds + (buf ^ 1) * kStageT + (TM + TN) * TK;
+      SPCFG_TN_FRAGS(x, as2, bs2, ss2, 0)
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    SPCFG_TN_MFMA(y)
   }
+  __syncthreads();  // all operands fetched before the LDS tiles are reused by the next tile segment
+#undef SPCFG_TN_FRAGS
+#undef SPCFG_TN_MFMA
 #undef SPCFG_TN_LOAD
 #undef SPCFG_TN_LOAD1
 #undef SPCFG_TN_STORE
