@@ -263,3 +263,58 @@ def test_bf16_scaled_full_size_sampled():
     assert (d["L"].astype(np.float64) * got["grad_L"]).sum() == pytest.approx((n - 1).sum(), rel=5e-3)
     assert (d["R"].astype(np.float64) * got["grad_R"]).sum() == pytest.approx((n - 1).sum(), rel=5e-3)
     assert got["grad_log_root"].sum() == pytest.approx(len(n), rel=5e-3)
+
+
+# ---------------------------------------------------------------------------------------------- edge cases
+@pytest.mark.parametrize("N,P,lens", [
+    (1, 1, [2]),                       # smallest legal problem
+    (1, 7, [2, 5, 3]),                 # a single nonterminal
+    (5, 1, [4, 2]),                    # a single preterminal
+    (33, 17, [2, 2, 2, 2]),            # every sentence has the minimum length: width 2 is all root spans
+    (40, 24, [3] * 37),                # many short sentences
+])
+def test_degenerate_sizes(N, P, lens):
+    d = synth.make_inputs("tiny", seed=900 + N + len(lens), pad_value=np.nan, N=N, P=P, B=len(lens), lengths=lens, V=50)
+    print("case degenerate", N, P, lens[:5], flush=True)
+    got, _ = gpu_run(d)
+    check_all(got, oracle_run(d))
+
+
+def test_long_single_sentence_many_widths():
+    """One sentence of 260 words (259 widths, late widths with a single span, LDS tables of 259 entries)."""
+    d = synth.make_inputs("long", seed=31, pad_value=np.nan, N=24, P=20, B=2, lengths=[260, 7], V=200)
+    print("case n=260", flush=True)
+    got, _ = gpu_run(d, fused=True)
+    print(check_all(got, oracle_run(d)))
+
+
+def test_workspace_reuse_across_different_batches():
+    """The same workspace buffer serves batches of different shapes one after the other."""
+    import torch
+    d1 = synth.make_inputs("tiny", seed=11, pad_value=np.nan, N=96, P=70, B=6, lengths=[12, 5, 9, 3, 20, 7])
+    d2 = synth.make_inputs("tiny", seed=12, pad_value=np.nan, N=96, P=70, B=3, lengths=[4, 30, 2])
+    w1, w2 = bd.Workload(d1), bd.Workload(d2)
+    big = w1.workspace if w1.workspace.numel() >= w2.workspace.numel() else w2.workspace
+    w1.workspace = big
+    w2.workspace = big
+    print("case workspace reuse", flush=True)
+    w1.forward_backward()
+    r1 = w1.results()
+    w2.forward_backward()
+    r2 = w2.results()
+    w1.forward_backward()
+    r1b = w1.results()
+    check_all(r1, oracle_run(d1))
+    check_all(r2, oracle_run(d2))
+    for k in r1:
+        assert np.array_equal(r1[k], r1b[k]), k
+
+
+def test_extreme_scales_of_emissions_and_root():
+    """Log-weights far outside the fp32 range of their exponentials: only differences matter."""
+    d = synth.make_inputs("tiny", seed=13, pad_value=np.nan, B=3, lengths=[6, 9, 4])
+    d["log_emit"] = (d["log_emit"] - 900.0).astype(np.float32)
+    d["log_root"] = (d["log_root"] + 300.0).astype(np.float32)
+    print("case extreme scales", flush=True)
+    got, _ = gpu_run(d)
+    check_all(got, oracle_run(d))
