@@ -54,7 +54,8 @@ def main():
     ap.add_argument("--workload", default="ptb", choices=["tiny", "small", "ptb", "scaled", "long"])
     ap.add_argument("--precision", default=None, choices=["fp32", "bf16"],
                     help="operand type of the projection GEMMs (default: the workload's own: bf16 for scaled)")
-    ap.add_argument("--profile-steps", type=int, default=3)
+    ap.add_argument("--profile-steps", type=int, default=None,
+                    help="steps repeated with HIP events around every kernel launch (default: as many as --steps)")
     ap.add_argument("--cpu-sentences", type=int, default=12)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -101,9 +102,10 @@ def main():
     logz = wl.logZ.cpu().numpy()
     assert np.all(np.isfinite(logz)), "non-finite log Z in the benchmark batch"
 
-    # per-kernel-class device time: same launches, bracketed by HIP events on the launch stream
+    # per-kernel-class device time: the same steps again, every launch bracketed by HIP events on the launch
+    # stream (kept out of the timed region above because the events perturb the whole-step time by a few %)
     bd.spcfg_profile_enable(True)
-    psteps = max(args.profile_steps, 1)
+    psteps = max(args.profile_steps if args.profile_steps is not None else args.steps, 1)
     for _ in range(psteps):
         wl.forward_backward()
     torch.cuda.synchronize()
