@@ -46,6 +46,48 @@ def cpu_baseline(d, max_sentences, budget_s=30.0):
                        f"fp64 numpy oracle forward+backward, {dt:.1f} s")
 
 
+def time_frontend(workload, wl, steps):
+    """Front-end forward and backward on the workload's shape (HBM-bound passes over the logit matrices and the
+    P x V emission table), timed with events on the launch stream; gradients fed from the inside pass's outputs."""
+    import torch
+    from paper_2310_14997_amd import binding as bd
+    from paper_2310_14997_amd import synth
+    d = synth.make_logits(workload)
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    N, P, V, B, n_max = d["N"], d["P"], d["V"], d["B"], d["n_max"]
+    M = N + P
+    f = dict(dtype=torch.float32, device=dev)
+    tin = {k: t(d[k]) for k in ("root_logits", "L_logits", "R_logits", "emis_logits", "tokens")}
+    o = dict(log_root=torch.empty(N, **f), L=torch.empty(N, M, **f), R=torch.empty(N, M, **f),
+             log_emit=torch.empty(B, n_max, P, **f), lse=torch.empty(P, **f))
+    g = dict(r=torch.empty(N, **f), l=torch.empty(N, M, **f), rr=torch.empty(N, M, **f), e=torch.empty(P, V, **f),
+             s=torch.empty(32, P, **f))
+
+    def fwd():
+        bd.spcfg_rules_forward(tin["root_logits"], tin["L_logits"], tin["R_logits"], tin["emis_logits"], tin["tokens"],
+                               d["lengths"], o["log_root"], o["L"], o["R"], o["log_emit"], o["lse"])
+
+    def bwd():
+        bd.spcfg_rules_backward(o["log_root"], o["L"], o["R"], tin["emis_logits"], o["lse"], tin["tokens"], d["lengths"],
+                                wl.grad_log_root, wl.grad_L, wl.grad_R, wl.grad_log_emit, g["r"], g["l"], g["rr"], g["e"],
+                                g["s"])
+
+    res = {}
+    for name, fn, byt in (("forward", fwd, 4.0 * (4 * N * M + P * V + 2 * B * n_max * P)),
+                          ("backward", bwd, 4.0 * (6 * N * M + 2 * P * V + 2 * B * n_max * P))):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        res[name] = {"ms": ms, "algorithmic_GBps": byt / (ms * 1e-3) / 1e9}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,6 +100,9 @@ def main():
                     help="steps repeated with HIP events around every kernel launch (default: as many as --steps)")
     ap.add_argument("--cpu-sentences", type=int, default=12)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--frontend", action="store_true",
+                    help="also time the rule-probability front-end (softmaxes + emission gather) and its backward "
+                         "at the workload's shape; reported under \"frontend\", not part of the step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of known size (1 GiB read + 1 GiB written per launch, 5 "
                          "launches): the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -147,6 +192,8 @@ def main():
                             "ms_per_step": split_ms},
         "kernel_classes": classes,
     }
+    if args.frontend:
+        out["frontend"] = time_frontend(args.workload, wl, args.steps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(d, args.cpu_sentences)
     print(json.dumps(out))

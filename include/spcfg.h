@@ -137,6 +137,39 @@ int spcfg_profile_enable(int on);
 int spcfg_profile_read(double* ms, int64_t* launches, double* work);
 const char* spcfg_profile_class_name(int cls);
 
+/*
+ * Rule-probability front-end (the softmaxes that end the neural parameterisation, App. A) and its backward.
+ * The scores ("logits") are what the paper's networks produce; the outputs are what spcfg_inside consumes.
+ *   root_logits dev [N], L_logits / R_logits dev [N x M], emis_logits dev [P x V]  (V = vocabulary size)
+ *   tokens      dev [B x n_max] int32 token ids in [0, V); entries at i >= lengths[b] are ignored
+ *   lengths     host [B], 0 <= lengths[b] <= n_max
+ * spcfg_rules_forward writes
+ *   log_root = log_softmax(root_logits) [N];  L = softmax rows of L_logits, R likewise [N x M];
+ *   log_emit[b, i, T] = log_softmax(emis_logits[T, :])[tokens[b, i]]  [B x n_max x P], 0 at padded positions
+ *                       (NaN if a token id is out of range);
+ *   emis_lse[T] = logsumexp(emis_logits[T, :]) [P], kept for the backward call.
+ * The P x V emission table is the dominant cost here at scale (paper, Limitations): it is read once for
+ * the row reductions and gathered once per token.
+ */
+int spcfg_rules_forward(int32_t N, int32_t P, int32_t V, const float* root_logits, const float* L_logits,
+                        const float* R_logits, const float* emis_logits, const int32_t* tokens, const int32_t* lengths,
+                        int32_t B, int32_t n_max, float* log_root, float* L, float* R, float* log_emit, float* emis_lse,
+                        void* hip_stream);
+
+/*
+ * Backward of spcfg_rules_forward: gradients w.r.t. the four logit arrays given gradients w.r.t. its outputs
+ * (e.g. those written by spcfg_inside_backward).  log_root, L, R, emis_lse are the forward outputs.
+ *   grad_root_logits dev [N], grad_L_logits / grad_R_logits dev [N x M], grad_emis_logits dev [P x V]: overwritten
+ *   scratch          dev [32 x P] floats of scratch
+ * Deterministic: equal tokens are accumulated in a fixed order, no floating-point atomics.
+ */
+int spcfg_rules_backward(int32_t N, int32_t P, int32_t V, const float* log_root, const float* L, const float* R,
+                         const float* emis_logits, const float* emis_lse, const int32_t* tokens,
+                         const int32_t* lengths, int32_t B, int32_t n_max, const float* grad_log_root,
+                         const float* grad_L, const float* grad_R, const float* grad_log_emit, float* grad_root_logits,
+                         float* grad_L_logits, float* grad_R_logits, float* grad_emis_logits, float* scratch,
+                         void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

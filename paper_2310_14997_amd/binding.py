@@ -49,6 +49,10 @@ def load():
     lib.spcfg_inside_backward.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.spcfg_inside_forward_backward.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp,
                                                   vp, sz, vp]
+    lib.spcfg_rules_forward.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.spcfg_rules_backward.argtypes = [i32, i32, i32] + [vp] * 7 + [i32, i32] + [vp] * 10
+    lib.spcfg_rules_forward.restype = C.c_int
+    lib.spcfg_rules_backward.restype = C.c_int
     lib.spcfg_strerror.argtypes = [C.c_int]
     lib.spcfg_strerror.restype = C.c_char_p
     lib.spcfg_last_hip_error.restype = C.c_char_p
@@ -155,6 +159,46 @@ def spcfg_inside_forward_backward(cfg, log_root, L, R, log_emit, lengths, grad_l
         _dev(log_emit, "log_emit"), lptr, B, n_max, _dev(grad_logZ, "grad_logZ", (B,)), _dev(logZ, "logZ", (B,)),
         _dev(grad_L, "grad_L", (N, M)), _dev(grad_R, "grad_R", (N, M)), _dev(grad_log_root, "grad_log_root", (N,)),
         _dev(grad_log_emit, "grad_log_emit", (B, n_max, P)), wp, wb, _stream()))
+
+
+def _dev_i32(t, name, shape):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == torch.int32):
+        raise TypeError(f"{name} must be a contiguous int32 device tensor")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return t.data_ptr()
+
+
+def spcfg_rules_forward(root_logits, L_logits, R_logits, emis_logits, tokens, lengths, log_root, L, R, log_emit,
+                        emis_lse):
+    """Softmaxes of the rule scores and the per-token emission gather (see include/spcfg.h)."""
+    N, M = L_logits.shape
+    P, V = emis_logits.shape
+    B, n_max = tokens.shape
+    arr, lptr = _lengths_array(lengths)
+    _check(load().spcfg_rules_forward(
+        N, P, V, _dev(root_logits, "root_logits", (N,)), _dev(L_logits, "L_logits", (N, M)),
+        _dev(R_logits, "R_logits", (N, M)), _dev(emis_logits, "emis_logits", (P, V)),
+        _dev_i32(tokens, "tokens", (B, n_max)), lptr, B, n_max, _dev(log_root, "log_root", (N,)), _dev(L, "L", (N, M)),
+        _dev(R, "R", (N, M)), _dev(log_emit, "log_emit", (B, n_max, P)), _dev(emis_lse, "emis_lse", (P,)), _stream()))
+
+
+def spcfg_rules_backward(log_root, L, R, emis_logits, emis_lse, tokens, lengths, grad_log_root, grad_L, grad_R,
+                         grad_log_emit, grad_root_logits, grad_L_logits, grad_R_logits, grad_emis_logits, scratch):
+    """Backward of spcfg_rules_forward: gradients w.r.t. the four logit arrays."""
+    N, M = L.shape
+    P, V = emis_logits.shape
+    B, n_max = tokens.shape
+    arr, lptr = _lengths_array(lengths)
+    _check(load().spcfg_rules_backward(
+        N, P, V, _dev(log_root, "log_root", (N,)), _dev(L, "L", (N, M)), _dev(R, "R", (N, M)),
+        _dev(emis_logits, "emis_logits", (P, V)), _dev(emis_lse, "emis_lse", (P,)),
+        _dev_i32(tokens, "tokens", (B, n_max)), lptr, B, n_max, _dev(grad_log_root, "grad_log_root", (N,)),
+        _dev(grad_L, "grad_L", (N, M)), _dev(grad_R, "grad_R", (N, M)),
+        _dev(grad_log_emit, "grad_log_emit", (B, n_max, P)), _dev(grad_root_logits, "grad_root_logits", (N,)),
+        _dev(grad_L_logits, "grad_L_logits", (N, M)), _dev(grad_R_logits, "grad_R_logits", (N, M)),
+        _dev(grad_emis_logits, "grad_emis_logits", (P, V)), _dev(scratch, "scratch", (32, P)), _stream()))
 
 
 def spcfg_profile_enable(on):

@@ -113,6 +113,29 @@ def make_inputs(name="tiny", seed=None, pad_value=0.0, **overrides):
                 log_emit=log_emit, lengths=lengths, tokens=tokens)
 
 
+def make_logits(name="tiny", seed=None, **overrides):
+    """Scores for the rule-probability front-end of one named workload: root [N], L/R [N, N+P] (scaled like the
+    workload's grammar), emission [P, V] logits, int32 tokens [B, n_max] (-1 on padding) and lengths."""
+    cfg = dict(CONFIGS[name])
+    cfg.update(overrides)
+    if seed is None:
+        seed = BASE_SEED + 100 + _ORDER.index(name)
+    rng = np.random.default_rng(seed)
+    B, N, P, V = int(cfg["B"]), int(cfg["N"]), int(cfg["P"]), int(cfg["V"])
+    law = cfg["lengths"]
+    lengths = draw_lengths(rng, law, B) if isinstance(law, tuple) else np.asarray(law, dtype=np.int32)
+    n_max = int(lengths.max())
+    tokens = np.full((B, n_max), -1, dtype=np.int32)
+    for b in range(B):
+        tokens[b, : int(lengths[b])] = zipf_tokens(rng, V, int(lengths[b]))
+    f = np.float32
+    return dict(name=name, seed=seed, B=B, N=N, P=P, V=V, n_max=n_max, lengths=lengths, tokens=tokens,
+                root_logits=rng.normal(size=N).astype(f),
+                L_logits=(cfg["lr_scale"] * rng.normal(size=(N, N + P))).astype(f),
+                R_logits=(cfg["lr_scale"] * rng.normal(size=(N, N + P))).astype(f),
+                emis_logits=rng.normal(size=(P, V)).astype(f))
+
+
 def work_counts(lengths, N, P):
     """Algorithmic work of one forward pass: projected spans, split terms, GEMM flop, split-reduction bytes."""
     n = np.asarray(lengths, dtype=np.int64)
