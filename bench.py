@@ -88,6 +88,37 @@ def time_frontend(workload, wl, steps):
     return res
 
 
+def time_decode(wl, steps):
+    """Span-posterior export and best-tree decoding on the workspace the last step left behind."""
+    import torch
+    from paper_2310_14997_amd import binding as bd
+    dev = wl.logZ.device
+    B, n_max = wl.B, wl.n_max
+    mu = torch.empty(B, n_max, n_max, dtype=torch.float32, device=dev)
+    lab = torch.empty(B, n_max, n_max, dtype=torch.int32, device=dev)
+    spans = torch.empty(B, n_max - 1, 2, dtype=torch.int32, device=dev)
+    score = torch.empty(B, dtype=torch.float32, device=dev)
+    scratch = torch.empty(bd.spcfg_mbr_decode_scratch_bytes(B, n_max), dtype=torch.uint8, device=dev)
+    n = wl.lengths.astype(np.int64)
+    rows = int((n * (n + 1) // 2).sum())  # one root row per width-1 entry plus every wider span
+    res = {}
+    for name, fn, byt in (("span_marginals", lambda: bd.spcfg_span_marginals(wl.cfg, wl.lengths, n_max, wl.workspace,
+                                                                             mu, lab), 8.0 * wl.N * rows),
+                          ("mbr_decode", lambda: bd.spcfg_mbr_decode(mu, wl.lengths, spans, score, scratch), None)):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        res[name] = {"ms": ms}
+        if byt:
+            res[name]["algorithmic_GBps"] = byt / (ms * 1e-3) / 1e9
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -103,6 +134,9 @@ def main():
     ap.add_argument("--frontend", action="store_true",
                     help="also time the rule-probability front-end (softmaxes + emission gather) and its backward "
                          "at the workload's shape; reported under \"frontend\", not part of the step")
+    ap.add_argument("--decode", action="store_true",
+                    help="also time the span-posterior export and the best-tree decoder on the step's workspace; "
+                         "reported under \"decode\", not part of the step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of known size (1 GiB read + 1 GiB written per launch, 5 "
                          "launches): the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -194,6 +228,8 @@ def main():
     }
     if args.frontend:
         out["frontend"] = time_frontend(args.workload, wl, args.steps)
+    if args.decode:
+        out["decode"] = time_decode(wl, args.steps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(d, args.cpu_sentences)
     print(json.dumps(out))

@@ -170,6 +170,36 @@ int spcfg_rules_backward(int32_t N, int32_t P, int32_t V, const float* log_root,
                          float* grad_L_logits, float* grad_R_logits, float* grad_emis_logits, float* scratch,
                          void* hip_stream);
 
+/*
+ * Span posteriors (the quantity the reverse pass of the inside algorithm yields, Sec. 3.2: back-propagation
+ * through the inside recursion is the outside pass, and beta * d logZ / d beta is the span marginal).
+ * Reads the workspace left by spcfg_inside + spcfg_inside_backward (or the fused call) for the same cfg,
+ * lengths, B, n_max; the workspace is not modified.
+ *   span_post  dev [B x n_max x n_max], entry ((b * n_max + i) * n_max + (j - 1)) for the fencepost span
+ *              (i, j), 0 <= i < j <= lengths[b]:  sum_A P(A spans (i,j) | sentence b) * grad_logZ[b].
+ *              Width-1 entries carry the root span's value (both are in every tree); all other entries 0.
+ *   span_label dev, same shape, or NULL: the nonterminal with the largest marginal on spans of width >= 2
+ *              (smallest index on ties), -1 elsewhere or where the posterior is 0.
+ */
+int spcfg_span_marginals(const spcfg_config* cfg, const int32_t* lengths, int32_t B, int32_t n_max,
+                         const void* workspace, size_t workspace_bytes, float* span_post, int32_t* span_label,
+                         void* hip_stream);
+
+/*
+ * Minimum-Bayes-risk tree (the parse used to score a grammar as an unsupervised parser, Sec. 4 "Evaluation"):
+ * the binary bracketing of each sentence that maximises the sum of span_post over its spans of width >= 2,
+ * by CKY over split points; the smallest split point wins ties.
+ *   span_post  dev [B x n_max x n_max], layout as written by spcfg_span_marginals (any non-negative scores)
+ *   lengths    host [B], 2 <= lengths[b] <= n_max <= 1024;  B <= 960
+ *   tree_spans dev [B x (n_max - 1) x 2] int32: the lengths[b] - 1 spans (i, j) of width >= 2 in pre-order
+ *              (parent, left subtree, right subtree), then -1 padding
+ *   tree_score dev [B]: the maximised sum
+ *   scratch    dev, 16-byte aligned, >= spcfg_mbr_decode_scratch_bytes(B, n_max) bytes
+ */
+int spcfg_mbr_decode_scratch_bytes(int32_t B, int32_t n_max, size_t* out_bytes);
+int spcfg_mbr_decode(const float* span_post, const int32_t* lengths, int32_t B, int32_t n_max, int32_t* tree_spans,
+                     float* tree_score, void* scratch, size_t scratch_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -51,6 +51,9 @@ def load():
                                                   vp, sz, vp]
     lib.spcfg_rules_forward.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.spcfg_rules_backward.argtypes = [i32, i32, i32] + [vp] * 7 + [i32, i32] + [vp] * 10
+    lib.spcfg_span_marginals.argtypes = [cfgp, vp, i32, i32, vp, sz, vp, vp, vp]
+    lib.spcfg_mbr_decode_scratch_bytes.argtypes = [i32, i32, C.POINTER(sz)]
+    lib.spcfg_mbr_decode.argtypes = [vp, vp, i32, i32, vp, vp, vp, sz, vp]
     lib.spcfg_rules_forward.restype = C.c_int
     lib.spcfg_rules_backward.restype = C.c_int
     lib.spcfg_strerror.argtypes = [C.c_int]
@@ -201,6 +204,32 @@ def spcfg_rules_backward(log_root, L, R, emis_logits, emis_lse, tokens, lengths,
         _dev(grad_emis_logits, "grad_emis_logits", (P, V)), _dev(scratch, "scratch", (32, P)), _stream()))
 
 
+def spcfg_span_marginals(cfg, lengths, n_max, workspace, span_post, span_label=None):
+    """Span posteriors (and arg-max labels) from the workspace left by the forward + reverse pass."""
+    arr, lptr = _lengths_array(lengths)
+    B = len(arr)
+    wp, wb = _ws(workspace)
+    lab = None if span_label is None else _dev_i32(span_label, "span_label", (B, n_max, n_max))
+    _check(load().spcfg_span_marginals(C.byref(cfg), lptr, B, int(n_max), wp, wb,
+                                       _dev(span_post, "span_post", (B, n_max, n_max)), lab, _stream()))
+
+
+def spcfg_mbr_decode_scratch_bytes(B, n_max):
+    out = C.c_size_t(0)
+    _check(load().spcfg_mbr_decode_scratch_bytes(int(B), int(n_max), C.byref(out)))
+    return out.value
+
+
+def spcfg_mbr_decode(span_post, lengths, tree_spans, tree_score, scratch):
+    """Best bracketing per sentence under the span posteriors (see include/spcfg.h)."""
+    arr, lptr = _lengths_array(lengths)
+    B, n_max, _ = span_post.shape
+    sp, sb = _ws(scratch)
+    _check(load().spcfg_mbr_decode(_dev(span_post, "span_post", (B, n_max, n_max)), lptr, B, n_max,
+                                   _dev_i32(tree_spans, "tree_spans", (B, n_max - 1, 2)),
+                                   _dev(tree_score, "tree_score", (B,)), sp, sb, _stream()))
+
+
 def spcfg_profile_enable(on):
     _check(load().spcfg_profile_enable(1 if on else 0))
 
@@ -250,6 +279,25 @@ class Workload:
         spcfg_inside_forward_backward(self.cfg, self.log_root, self.L, self.R, self.log_emit, self.lengths,
                                       grad_logZ, self.logZ, self.grad_L, self.grad_R, self.grad_log_root,
                                       self.grad_log_emit, self.workspace)
+
+    def span_marginals(self, with_labels=True):
+        """Span posteriors [B, n_max, n_max] (and labels) of the last forward + backward."""
+        torch = self.torch
+        dev = self.logZ.device
+        mu = torch.empty(self.B, self.n_max, self.n_max, dtype=torch.float32, device=dev)
+        lab = torch.empty(self.B, self.n_max, self.n_max, dtype=torch.int32, device=dev) if with_labels else None
+        spcfg_span_marginals(self.cfg, self.lengths, self.n_max, self.workspace, mu, lab)
+        return mu, lab
+
+    def mbr_decode(self, span_post):
+        """(tree_spans [B, n_max-1, 2] int32, tree_score [B]) for the given span scores."""
+        torch = self.torch
+        dev = span_post.device
+        spans = torch.empty(self.B, self.n_max - 1, 2, dtype=torch.int32, device=dev)
+        score = torch.empty(self.B, dtype=torch.float32, device=dev)
+        scratch = torch.empty(spcfg_mbr_decode_scratch_bytes(self.B, self.n_max), dtype=torch.uint8, device=dev)
+        spcfg_mbr_decode(span_post, self.lengths, spans, score, scratch)
+        return spans, score
 
     def results(self):
         self.torch.cuda.synchronize()

@@ -503,6 +503,60 @@ __global__ void k_zero_pad_emit(int P, int n_max, const int32_t* __restrict__ le
   for (int64_t t = threadIdx.x; t < cnt; t += blockDim.x) base[t] = 0.0f;
 }
 
+// ------------------------------------------------------------------------------------------ span posteriors
+// mu(i,j) = sum_A beta_ij[A] * d logZ / d beta_ij[A]: the posterior probability that some nonterminal spans
+// (i,j) (inside-outside by back-propagation, Sec. 3.2).  Both factors are still in the workspace after the
+// reverse pass: beta = 2^mexp * T and its adjoint = 2^(uexp + f') * BH.  One wavefront per (sentence, i, j-1)
+// entry of the dense output; entries that are no span get 0 / -1.  Width-1 spans carry the same mass as the
+// root span (both are in every tree), so they read the root row.  label = first arg-max nonterminal.
+__global__ void __launch_bounds__(64)
+k_span_marginals(int B, int N, int Np, int n_max, int64_t S1, const int32_t* __restrict__ lens,
+                 const int32_t* __restrict__ rowbase, const float* __restrict__ T, const float* __restrict__ BH,
+                 const int32_t* __restrict__ mexp, const int32_t* __restrict__ uexp,
+                 const uint32_t* __restrict__ umaxb, float* __restrict__ mu, int32_t* __restrict__ label) {
+  const int lane = threadIdx.x;
+  const int b = blockIdx.y;
+  const int i = blockIdx.x / n_max, j = blockIdx.x % n_max + 1;
+  const int n = lens[b];
+  const int64_t out = ((int64_t)b * n_max + i) * n_max + (j - 1);
+  if (j <= i || j > n) {
+    if (lane == 0) {
+      mu[out] = 0.0f;
+      if (label) label[out] = -1;
+    }
+    return;
+  }
+  const int w = j - i;
+  const int64_t r = (w == 1) ? rowbase[n * B + b] : rowbase[w * B + b] + i;
+  const float* t = T + (r - S1) * Np;
+  const float* h = BH + (r - S1) * Np;
+  float sum = 0.0f, best = 0.0f;
+  int arg = -1;
+  for (int a = lane * 4; a < Np; a += 256) {
+    const float4 x = *reinterpret_cast<const float4*>(t + a);
+    const float4 y = *reinterpret_cast<const float4*>(h + a);
+    const float p0 = x.x * y.x, p1 = x.y * y.y, p2 = x.z * y.z, p3 = x.w * y.w;
+    sum += (p0 + p1) + (p2 + p3);
+    if (p0 > best) { best = p0; arg = a; }
+    if (p1 > best) { best = p1; arg = a + 1; }
+    if (p2 > best) { best = p2; arg = a + 2; }
+    if (p3 > best) { best = p3; arg = a + 3; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    sum += __shfl_xor(sum, o, 64);
+    const float ob = __shfl_xor(best, o, 64);
+    const int oa = __shfl_xor(arg, o, 64);
+    if (ob > best || (ob == best && oa >= 0 && (arg < 0 || oa < arg))) { best = ob; arg = oa; }
+  }
+  if (lane == 0) {
+    const int d = add_exp(mexp[r], norm_exp(uexp[r], umaxb[r]));
+    const float m = (d == kExpZero) ? 0.0f : pow2i(d) * sum;
+    mu[out] = m;
+    if (label) label[out] = (w >= 2 && m > 0.0f && arg < N) ? arg : -1;
+  }
+}
+
 }  // namespace
 
 void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_t st) {
@@ -562,6 +616,12 @@ void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int6
 
 void launch_zero_pad_emit(const Layout& ly, const Ptrs& p, float* grad_log_emit, hipStream_t st) {
   hipLaunchKernelGGL(k_zero_pad_emit, dim3(ly.B), dim3(256), 0, st, ly.P, ly.n_max, p.lens, grad_log_emit);
+}
+
+void launch_span_marginals(const Layout& ly, const Ptrs& p, float* mu, int32_t* label, hipStream_t st) {
+  const dim3 grid((unsigned)(ly.n_max * ly.n_max), (unsigned)ly.B);
+  hipLaunchKernelGGL(k_span_marginals, grid, dim3(64), 0, st, ly.B, ly.N, ly.Np, ly.n_max, ly.S1, p.lens, p.rowbase,
+                     p.T, p.BH, p.mexp, p.uexp, p.umaxb, mu, label);
 }
 
 }  // namespace spcfg

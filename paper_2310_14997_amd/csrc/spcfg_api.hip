@@ -364,6 +364,21 @@ int spcfg_inside_forward_backward(const spcfg_config* cfg, const float* log_root
                   (hipStream_t)hip_stream);
 }
 
+int spcfg_span_marginals(const spcfg_config* cfg, const int32_t* lengths, int32_t B, int32_t n_max,
+                         const void* workspace, size_t workspace_bytes, float* span_post, int32_t* span_label,
+                         void* hip_stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (!span_post) return SPCFG_ERR_ARG;
+  Plan plan; Layout ly;
+  rc = make_plan(cfg, lengths, B, n_max, &plan, &ly);
+  if (rc) return rc;
+  rc = check_ws(ly, const_cast<void*>(workspace), workspace_bytes);
+  if (rc) return rc;
+  launch_span_marginals(ly, resolve(ly, const_cast<void*>(workspace)), span_post, span_label, (hipStream_t)hip_stream);
+  return hip_status();
+}
+
 const char* spcfg_strerror(int code) {
   switch (code) {
     case SPCFG_OK: return "ok";

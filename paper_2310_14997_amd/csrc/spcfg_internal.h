@@ -67,6 +67,7 @@ void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, con
                      float* grad_log_root, int accumulate, hipStream_t st);
 void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st);
 void launch_zero_pad_emit(const Layout& ly, const Ptrs& p, float* grad_log_emit, hipStream_t st);
+void launch_span_marginals(const Layout& ly, const Ptrs& p, float* mu, int32_t* label, hipStream_t st);
 
 // C[r][c] = sum_k A[r][k] * Bm[c][k]   (both operands K-contiguous), r < rows, c < cols, K % 32 == 0.
 enum NtEpilogue { NT_EPI_ROWSCALE = 0, NT_EPI_MASKROWS = 1, NT_EPI_LEAF_EMIT = 2, NT_EPI_GRAD = 3 };

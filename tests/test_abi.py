@@ -80,3 +80,22 @@ def test_null_pointers_are_rejected_before_any_launch():
     assert rc == -4
     rc = lib.spcfg_inside(C.byref(cfg), fake, fake, fake, fake, lens.ctypes.data, 2, 6, fake, C.c_void_p(100), 1 << 40, None)
     assert rc == -4  # misaligned
+
+
+def test_decode_argument_checks_run_before_any_launch():
+    lib = bd.load()
+    fake = C.c_void_p(4096)
+    lens = np.array([3, 4], dtype=np.int32)
+    out = C.c_size_t(0)
+    assert lib.spcfg_mbr_decode_scratch_bytes(2, 6, C.byref(out)) == 0 and out.value == 2 * 36 * 12
+    assert lib.spcfg_mbr_decode_scratch_bytes(2, 1, C.byref(out)) == -2
+    assert lib.spcfg_mbr_decode_scratch_bytes(961, 6, C.byref(out)) == -2
+    assert lib.spcfg_mbr_decode_scratch_bytes(2, 6, None) == -1
+    assert lib.spcfg_mbr_decode(None, lens.ctypes.data, 2, 6, fake, fake, fake, 1 << 20, None) == -1
+    assert lib.spcfg_mbr_decode(fake, lens.ctypes.data, 2, 6, fake, fake, fake, 16, None) == -4
+    assert lib.spcfg_mbr_decode(fake, lens.ctypes.data, 2, 6, fake, fake, C.c_void_p(4100), 1 << 20, None) == -4
+    bad = np.array([3, 7], dtype=np.int32)
+    assert lib.spcfg_mbr_decode(fake, bad.ctypes.data, 2, 6, fake, fake, fake, 1 << 20, None) == -3
+    cfg = bd.make_config(8, 8, 2, 6)
+    assert lib.spcfg_span_marginals(C.byref(cfg), lens.ctypes.data, 2, 6, fake, 1 << 30, None, None, None) == -1
+    assert lib.spcfg_span_marginals(C.byref(cfg), lens.ctypes.data, 2, 6, C.c_void_p(4096), 16, fake, None, None) == -4

@@ -1,0 +1,177 @@
+"""GPU parity of the span-posterior export and the minimum-Bayes-risk tree decoder against the CPU oracle."""
+import numpy as np
+import pytest
+
+from oracle import decode_oracle as D
+from paper_2310_14997_amd import binding as bd
+from paper_2310_14997_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+MU_RTOL = 1e-4       # span posteriors are sums of products of gradient-grade quantities: the gradient tolerance
+MU_ATOL = 1e-7
+MU_RTOL_BF16 = 2e-2  # bf16 operands (unit roundoff 2^-9) in every projection below the span
+
+
+def gpu_marginals(d, precision=bd.PRECISION_FP32, grad_logZ=None):
+    import torch
+    wl = bd.Workload(d, precision=precision)
+    g = None if grad_logZ is None else torch.tensor(grad_logZ, dtype=torch.float32, device="cuda:0")
+    wl.forward_backward(g)
+    mu, lab = wl.span_marginals()
+    torch.cuda.synchronize()
+    return wl, mu, mu.cpu().numpy().astype(np.float64), lab.cpu().numpy()
+
+
+def check_sentence_marginals(d, b, mu_b, lab_b, rtol, g=1.0):
+    n = int(d["lengths"][b])
+    n_max = d["n_max"]
+    ref, ref_lab, obar = oracle_posteriors(d, b)
+    dense = np.zeros((n_max, n_max))
+    for i in range(n):
+        for j in range(i + 1, n + 1):
+            dense[i, j - 1] = g * ref[i, j]
+    err = np.abs(mu_b - dense)
+    tol = rtol * np.abs(dense) + MU_ATOL
+    worst = np.unravel_index(np.argmax(err - tol), err.shape)
+    assert np.all(err <= tol), f"sentence {b}: span {worst} got {mu_b[worst]:.8e} ref {dense[worst]:.8e}"
+    mask = np.triu(np.ones((n_max, n_max), bool))
+    mask[n:, :] = False
+    mask[:, n:] = False
+    assert np.all(mu_b[~mask] == 0.0) and np.all(lab_b[~mask] == -1)
+    assert np.all(np.diag(lab_b) == -1)
+    for i in range(n):
+        for j in range(i + 2, n + 1):
+            a = int(lab_b[i, j - 1])
+            if dense[i, j - 1] <= 0.0:
+                assert a == -1
+                continue
+            assert 0 <= a < d["N"]
+            # near-ties may resolve differently in fp32: the chosen label must carry the largest marginal up to tolerance
+            assert obar[(i, j)][a] >= (1.0 - 10 * rtol) * obar[(i, j)].max()
+    return ref
+
+
+def oracle_posteriors(d, b):
+    from oracle import spcfg_oracle as O
+    n = int(d["lengths"][b])
+    e = d["log_emit"][b, :n]
+    out = O.inside_backward_sentence(d["log_root"], d["L"], d["R"], e, 1.0, return_marginals=True)
+    obar = out[-1]
+    mu, lab = D.span_posteriors(d["log_root"], d["L"], d["R"], e)
+    return mu, lab, obar
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("tiny", {}),
+    ("tiny", dict(N=70, P=45, B=7, lengths=[2, 3, 9, 17, 5, 2, 12])),
+    ("adversarial", {}),
+])
+def test_span_marginals_match_oracle(name, kw):
+    d = synth.make_inputs(name, pad_value=np.nan, **kw)
+    print("case", name, kw, flush=True)
+    wl, mu_dev, mu, lab = gpu_marginals(d)
+    for b in range(d["B"]):
+        check_sentence_marginals(d, b, mu[b], lab[b], MU_RTOL)
+
+
+def test_span_marginals_scale_with_upstream_weights_and_bf16():
+    d = synth.make_inputs("tiny", pad_value=np.nan, B=5, lengths=[4, 11, 2, 8, 15])
+    g = np.array([0.5, 2.0, 1.0, 0.0, 3.0])
+    print("case upstream weights", flush=True)
+    wl, mu_dev, mu, lab = gpu_marginals(d, grad_logZ=g)
+    for b in range(d["B"]):
+        check_sentence_marginals(d, b, mu[b], lab[b], MU_RTOL, g=float(g[b]))
+    print("case bf16", flush=True)
+    wl, mu_dev, mu, lab = gpu_marginals(d, precision=bd.PRECISION_BF16)
+    for b in range(d["B"]):
+        check_sentence_marginals(d, b, mu[b], lab[b], MU_RTOL_BF16)
+
+
+def decode_on_gpu(mu_np, lengths):
+    import torch
+    B, n_max, _ = mu_np.shape
+    mu = torch.from_numpy(np.ascontiguousarray(mu_np, dtype=np.float32)).to("cuda:0")
+    spans = torch.full((B, n_max - 1, 2), -7, dtype=torch.int32, device="cuda:0")
+    score = torch.empty(B, dtype=torch.float32, device="cuda:0")
+    scratch = torch.empty(bd.spcfg_mbr_decode_scratch_bytes(B, n_max), dtype=torch.uint8, device="cuda:0")
+    bd.spcfg_mbr_decode(mu, np.asarray(lengths, np.int32), spans, score, scratch)
+    torch.cuda.synchronize()
+    return spans.cpu().numpy(), score.cpu().numpy().astype(np.float64)
+
+
+def to_oracle_layout(mu_b, n):
+    m = np.zeros((n + 1, n + 1))
+    for i in range(n):
+        m[i, i + 1:n + 1] = mu_b[i, i:n]
+    return m
+
+
+@pytest.mark.parametrize("lengths", [
+    [2, 3, 4, 5, 9, 16, 37, 40],   # chart in LDS
+    [2, 64, 65, 90],               # multi-pass over split points within a wavefront; largest LDS chart
+    [130, 91, 2, 7],               # chart in device scratch
+])
+def test_mbr_decode_is_bit_exact_on_exactly_representable_scores(lengths):
+    """Scores on a 1/64 grid: every fp32 sum in the chart is exact, so arg-max decisions (ties to the smallest
+    split point) and scores must agree with the double-precision oracle bit for bit."""
+    rng = np.random.default_rng(sum(lengths))
+    B, n_max = len(lengths), max(lengths)
+    mu = rng.integers(0, 65, size=(B, n_max, n_max)).astype(np.float64) / 64.0
+    mu[rng.random(mu.shape) < 0.3] = 0.5  # many exact ties
+    print("case decode exact", lengths, flush=True)
+    spans, score = decode_on_gpu(mu, lengths)
+    for b, n in enumerate(lengths):
+        ref_score, ref_spans = D.mbr_decode(to_oracle_layout(mu[b], n), n)
+        got = [tuple(x) for x in spans[b, : n - 1]]
+        assert got == ref_spans, f"sentence {b} (n={n})"
+        assert score[b] == ref_score
+        assert np.all(spans[b, n - 1:] == -1)
+
+
+def test_marginals_then_decode_end_to_end():
+    d = synth.make_inputs("small", pad_value=np.nan, B=6, N=96, P=80)
+    print("case end to end", flush=True)
+    wl, mu_dev, mu, lab = gpu_marginals(d)
+    spans_dev, score_dev = wl.mbr_decode(mu_dev)
+    import torch
+    torch.cuda.synchronize()
+    spans, score = spans_dev.cpu().numpy(), score_dev.cpu().numpy().astype(np.float64)
+    for b in range(d["B"]):
+        n = int(d["lengths"][b])
+        ref = check_sentence_marginals(d, b, mu[b], lab[b], MU_RTOL)
+        best, _ = D.mbr_decode(ref, n)
+        got = [tuple(x) for x in spans[b, : n - 1]]
+        assert D.is_binary_tree(got, n)
+        # several trees may be optimal up to rounding: the tree must be valid and its exact score optimal
+        assert D.tree_score(ref, got) >= best - 1e-4 * n
+        assert score[b] == pytest.approx(D.tree_score(ref, got), rel=1e-4)
+
+
+def test_ptb_full_size_marginals_and_trees():
+    """Headline configuration: properties that hold at any size, plus sampled sentences against the oracle."""
+    d = synth.make_inputs("ptb", pad_value=np.nan)
+    print("case ptb full size decode", flush=True)
+    wl, mu_dev, mu, lab = gpu_marginals(d)
+    spans_dev, score_dev = wl.mbr_decode(mu_dev)
+    import torch
+    torch.cuda.synchronize()
+    spans, score = spans_dev.cpu().numpy(), score_dev.cpu().numpy().astype(np.float64)
+    lens = d["lengths"]
+    for b in range(d["B"]):
+        n = int(lens[b])
+        m = to_oracle_layout(mu[b], n)
+        assert m[0, n] == pytest.approx(1.0, rel=1e-4)
+        assert np.all(np.diag(mu[b])[:n] == mu[b][0, n - 1])
+        wide = sum(m[i, j] for i in range(n) for j in range(i + 2, n + 1))
+        assert wide == pytest.approx(n - 1, rel=1e-4)      # expected number of internal nodes
+        got = [tuple(x) for x in spans[b, : n - 1]]
+        assert D.is_binary_tree(got, n)
+        ref_score, ref_spans = D.mbr_decode(m, n)          # CKY in double precision on the GPU's own scores
+        assert D.tree_score(m, got) >= ref_score - 1e-5 * n
+        assert score[b] == pytest.approx(ref_score, rel=1e-5)
+        assert np.all(spans[b, n - 1:] == -1)
+    order = np.argsort(lens)
+    for b in (int(order[0]), int(order[len(order) // 3])):
+        print("  oracle sentence", b, "length", int(lens[b]), flush=True)
+        check_sentence_marginals(d, b, mu[b], lab[b], MU_RTOL)
