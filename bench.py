@@ -134,6 +134,8 @@ def main():
     ap.add_argument("--frontend", action="store_true",
                     help="also time the rule-probability front-end (softmaxes + emission gather) and its backward "
                          "at the workload's shape; reported under \"frontend\", not part of the step")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step into a HIP graph once and time its replays instead of eager launches")
     ap.add_argument("--decode", action="store_true",
                     help="also time the span-posterior export and the best-tree decoder on the step's workspace; "
                          "reported under \"decode\", not part of the step")
@@ -168,12 +170,25 @@ def main():
     wc = synth.work_counts(d["lengths"], d["N"], d["P"])
     stream = torch.cuda.current_stream()
 
-    for _ in range(args.warmup):
+    step = wl.forward_backward
+    if args.graph:  # the step only enqueues kernels, so it can be captured once and replayed
         wl.forward_backward()
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            wl.forward_backward()
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            wl.forward_backward()
+        step = graph.replay
+    for _ in range(args.warmup):
+        step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        wl.forward_backward()
+        step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -209,7 +224,7 @@ def main():
         "metric": f"sentences/sec inside fwd+bwd at N=P={d['N']}, n<={d['n_max']}",
         "value": sent_per_s, "unit": "sentences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic", "launch": "hip graph replay" if args.graph else "eager",
         "config": {"workload": f"{args.workload}: B={d['B']}, N={d['N']}, P={d['P']}, n_max={d['n_max']}, "
                                f"sum_n={wc['leaves']}, projected_spans={wc['proj_spans']}, "
                                f"split_terms={wc['split_terms']}, seed={d['seed']}",

@@ -123,34 +123,50 @@ int make_plan(const spcfg_config* cfg, const int32_t* lengths, int B, int n_max,
 }
 
 // ---- profiling -------------------------------------------------------------------------------------
+// One event after every kernel class scope; a scope's start is the end mark of the scope before it (launches
+// on one stream run back to back), so only one event sits between two kernels.  Each API call starts with a
+// fresh mark: idle time between calls is not charged to anybody.
 struct Prof {
   bool on = false;
-  struct Rec { hipEvent_t a, b; int cls; };
+  struct Rec { int a, b, cls; };      // indices into marks
   std::vector<Rec> recs;
+  std::vector<hipEvent_t> marks;      // recorded boundary events, in order
   std::vector<hipEvent_t> pool;
+  int last = -1;                      // latest boundary of the current call, -1: none yet
   double work[SPCFG_PROF_CLASSES] = {0};
   int64_t launches[SPCFG_PROF_CLASSES] = {0};
-  hipEvent_t get() {
-    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
-    hipEvent_t e;
-    if (hipEventCreate(&e) != hipSuccess) return nullptr;
-    return e;
+  int mark(hipStream_t st) {
+    hipEvent_t e = nullptr;
+    if (!pool.empty()) { e = pool.back(); pool.pop_back(); }
+    else if (hipEventCreate(&e) != hipSuccess) return -1;
+    if (hipEventRecord(e, st) != hipSuccess) { pool.push_back(e); return -1; }
+    marks.push_back(e);
+    return (int)marks.size() - 1;
+  }
+  void recycle() {
+    for (hipEvent_t e : marks) pool.push_back(e);
+    marks.clear();
+    recs.clear();
+    last = -1;
   }
 } g_prof;
 
-struct Scope {  // brackets the launches of one kernel class with events when profiling is enabled
-  hipStream_t st; int cls; hipEvent_t a = nullptr, b = nullptr;
+void prof_begin_call() { g_prof.last = -1; }
+
+struct Scope {  // charges the device time of the launches made during its lifetime to one kernel class
+  hipStream_t st; int cls; int a = -1;
   Scope(hipStream_t s, int c, double work, int nlaunch = 1) : st(s), cls(c) {
     if (!g_prof.on) return;
-    a = g_prof.get(); b = g_prof.get();
+    if (g_prof.last < 0) g_prof.last = g_prof.mark(st);
+    a = g_prof.last;
     g_prof.work[c] += work;
     g_prof.launches[c] += nlaunch;
-    if (a) (void)hipEventRecord(a, st);
   }
   ~Scope() {
-    if (!g_prof.on || !a || !b) return;
-    (void)hipEventRecord(b, st);
-    g_prof.recs.push_back({a, b, cls});
+    if (!g_prof.on || a < 0) return;
+    const int b = g_prof.mark(st);
+    if (b >= 0) g_prof.recs.push_back({a, b, cls});
+    g_prof.last = b;
   }
 };
 
@@ -171,6 +187,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
             const float* L, const float* R, const float* log_emit, float* logZ, hipStream_t st) {
   const int n_max = ly.n_max;
   const int64_t Np = ly.Np, Pp = ly.Pp;
+  prof_begin_call();
   {
     Scope s(st, SPCFG_PROF_SETUP, 4.0 * 2 * (double)ly.N * (ly.N + ly.P) * 3 + 8.0 * ly.S1 * ly.P, 4);
     launch_plan(ly, p, plan.lens, st);
@@ -217,6 +234,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
   const int n_max = ly.n_max;
   const int64_t Np = ly.Np, Pp = ly.Pp;
   const int acc = (cfg->flags & SPCFG_FLAG_ACCUMULATE_GRADS) ? 1 : 0;
+  prof_begin_call();
   {
     Scope s(st, SPCFG_PROF_ROOT, 16.0 * ly.N * ly.B, 3);
     launch_root_bwd(ly, p, log_root, grad_logZ, grad_log_root, acc, st);
@@ -397,8 +415,7 @@ const char* spcfg_last_hip_error(void) { return g_hip_err; }
 int spcfg_profile_enable(int on) {
   g_prof.on = on != 0;
   if (g_prof.on) {
-    for (auto& r : g_prof.recs) { g_prof.pool.push_back(r.a); g_prof.pool.push_back(r.b); }
-    g_prof.recs.clear();
+    g_prof.recycle();
     for (int c = 0; c < SPCFG_PROF_CLASSES; ++c) { g_prof.work[c] = 0; g_prof.launches[c] = 0; }
   }
   return SPCFG_OK;
@@ -408,14 +425,13 @@ int spcfg_profile_read(double* ms, int64_t* launches, double* work) {
   if (!ms || !launches || !work) return SPCFG_ERR_ARG;
   for (int c = 0; c < SPCFG_PROF_CLASSES; ++c) ms[c] = 0.0;
   int rc = SPCFG_OK;
+  if (!g_prof.marks.empty() && hipEventSynchronize(g_prof.marks.back()) != hipSuccess) rc = SPCFG_ERR_HIP;
   for (auto& r : g_prof.recs) {
     float t = 0.0f;
-    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) rc = SPCFG_ERR_HIP;
+    if (hipEventElapsedTime(&t, g_prof.marks[r.a], g_prof.marks[r.b]) != hipSuccess) rc = SPCFG_ERR_HIP;
     ms[r.cls] += t;
-    g_prof.pool.push_back(r.a);
-    g_prof.pool.push_back(r.b);
   }
-  g_prof.recs.clear();
+  g_prof.recycle();
   for (int c = 0; c < SPCFG_PROF_CLASSES; ++c) {
     launches[c] = g_prof.launches[c];
     work[c] = g_prof.work[c];
