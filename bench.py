@@ -36,7 +36,10 @@ def cpu_baseline(d, max_sentences, budget_s=30.0):
     done, t0 = 0, time.perf_counter()
     for b in range(min(max_sentences, d["B"])):
         n = int(d["lengths"][b])
-        O.inside_backward_sentence(d["log_root"], d["L"], d["R"], d["log_emit"][b, :n])
+        if d["L"].ndim == 3:  # one grammar per sentence
+            O.inside_backward_sentence(d["log_root"][b], d["L"][b], d["R"][b], d["log_emit"][b, :n])
+        else:
+            O.inside_backward_sentence(d["log_root"], d["L"], d["R"], d["log_emit"][b, :n])
         done += 1
         if time.perf_counter() - t0 > budget_s:
             break
@@ -134,6 +137,8 @@ def main():
     ap.add_argument("--frontend", action="store_true",
                     help="also time the rule-probability front-end (softmaxes + emission gather) and its backward "
                          "at the workload's shape; reported under \"frontend\", not part of the step")
+    ap.add_argument("--per-sentence", action="store_true",
+                    help="one grammar per sentence (grouped projection products) at the workload's shape")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step into a HIP graph once and time its replays instead of eager launches")
     ap.add_argument("--decode", action="store_true",
@@ -162,7 +167,7 @@ def main():
                           "bytes_written_per_launch": src.numel() * 4, "launches": 5}))
         return
 
-    d = synth.make_inputs(args.workload)
+    d = synth.make_inputs_per_sentence(args.workload) if args.per_sentence else synth.make_inputs(args.workload)
     precision = args.precision or d["precision"]
     bf16 = precision == "bf16"
     wl = bd.Workload(d, precision=bd.PRECISION_BF16 if bf16 else bd.PRECISION_FP32)
@@ -225,6 +230,7 @@ def main():
         "value": sent_per_s, "unit": "sentences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic", "launch": "hip graph replay" if args.graph else "eager",
+        "grammars": "one per sentence" if args.per_sentence else "shared",
         "config": {"workload": f"{args.workload}: B={d['B']}, N={d['N']}, P={d['P']}, n_max={d['n_max']}, "
                                f"sum_n={wc['leaves']}, projected_spans={wc['proj_spans']}, "
                                f"split_terms={wc['split_terms']}, seed={d['seed']}",

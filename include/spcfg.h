@@ -46,7 +46,12 @@ enum {
 enum { SPCFG_PRECISION_FP32 = 0, SPCFG_PRECISION_BF16 = 1 };
 
 enum {
-  SPCFG_FLAG_ACCUMULATE_GRADS = 1u /* add into grad_L / grad_R / grad_log_root instead of overwriting */
+  SPCFG_FLAG_ACCUMULATE_GRADS = 1u, /* add into grad_L / grad_R / grad_log_root instead of overwriting */
+  /* One grammar per sentence (the dynamic program of the compound variant, App. A: rule probabilities that
+     depend on a per-sentence latent vector).  log_root is then [B x N], L and R are [B x N x M], and
+     grad_log_root, grad_L, grad_R have the same per-sentence shapes (no sum over the batch).  The projections
+     become grouped products: each sentence's spans meet that sentence's [L;R] panel.  fp32 only. */
+  SPCFG_FLAG_PER_SENTENCE_GRAMMAR = 2u
 };
 
 /* Plain-old-data configuration; set struct_size = sizeof(spcfg_config). */

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libspcfg.so")
 
 PRECISION_FP32, PRECISION_BF16 = 0, 1
-FLAG_ACCUMULATE_GRADS = 1
+FLAG_ACCUMULATE_GRADS, FLAG_PER_SENTENCE_GRAMMAR = 1, 2
 PROF_CLASSES = 7
 
 
@@ -125,14 +125,22 @@ def _ws(workspace):
     return workspace.data_ptr(), workspace.numel()
 
 
+def _grammar_shapes(cfg, L, B):
+    """(N, M, shape of log_root, shape of L / R): per-sentence grammars carry a leading batch dimension."""
+    N, M = L.shape[-2:]
+    if cfg.flags & FLAG_PER_SENTENCE_GRAMMAR:
+        return N, M, (B, N), (B, N, M)
+    return N, M, (N,), (N, M)
+
+
 def spcfg_inside(cfg, log_root, L, R, log_emit, lengths, logZ, workspace):
     """Enqueue the inside pass on torch's current stream; logZ [B] is written (see include/spcfg.h)."""
     B, n_max, P = log_emit.shape
-    N, M = L.shape
+    N, M, rs, gs = _grammar_shapes(cfg, L, B)
     arr, lptr = _lengths_array(lengths)
     wp, wb = _ws(workspace)
-    _check(load().spcfg_inside(C.byref(cfg), _dev(log_root, "log_root", (N,)), _dev(L, "L", (N, M)),
-                               _dev(R, "R", (N, M)), _dev(log_emit, "log_emit"), lptr, B, n_max,
+    _check(load().spcfg_inside(C.byref(cfg), _dev(log_root, "log_root", rs), _dev(L, "L", gs),
+                               _dev(R, "R", gs), _dev(log_emit, "log_emit"), lptr, B, n_max,
                                _dev(logZ, "logZ", (B,)), wp, wb, _stream()))
 
 
@@ -140,13 +148,13 @@ def spcfg_inside_backward(cfg, log_root, L, R, log_emit, lengths, grad_logZ, gra
                           grad_log_emit, workspace):
     """Enqueue the reverse pass; must follow spcfg_inside on the same inputs and workspace."""
     B, n_max, P = log_emit.shape
-    N, M = L.shape
+    N, M, rs, gs = _grammar_shapes(cfg, L, B)
     arr, lptr = _lengths_array(lengths)
     wp, wb = _ws(workspace)
     _check(load().spcfg_inside_backward(
-        C.byref(cfg), _dev(log_root, "log_root", (N,)), _dev(L, "L", (N, M)), _dev(R, "R", (N, M)),
+        C.byref(cfg), _dev(log_root, "log_root", rs), _dev(L, "L", gs), _dev(R, "R", gs),
         _dev(log_emit, "log_emit"), lptr, B, n_max, _dev(grad_logZ, "grad_logZ", (B,)),
-        _dev(grad_L, "grad_L", (N, M)), _dev(grad_R, "grad_R", (N, M)), _dev(grad_log_root, "grad_log_root", (N,)),
+        _dev(grad_L, "grad_L", gs), _dev(grad_R, "grad_R", gs), _dev(grad_log_root, "grad_log_root", rs),
         _dev(grad_log_emit, "grad_log_emit", (B, n_max, P)), wp, wb, _stream()))
 
 
@@ -154,13 +162,13 @@ def spcfg_inside_forward_backward(cfg, log_root, L, R, log_emit, lengths, grad_l
                                   grad_log_root, grad_log_emit, workspace):
     """Enqueue forward then reverse pass in one call."""
     B, n_max, P = log_emit.shape
-    N, M = L.shape
+    N, M, rs, gs = _grammar_shapes(cfg, L, B)
     arr, lptr = _lengths_array(lengths)
     wp, wb = _ws(workspace)
     _check(load().spcfg_inside_forward_backward(
-        C.byref(cfg), _dev(log_root, "log_root", (N,)), _dev(L, "L", (N, M)), _dev(R, "R", (N, M)),
+        C.byref(cfg), _dev(log_root, "log_root", rs), _dev(L, "L", gs), _dev(R, "R", gs),
         _dev(log_emit, "log_emit"), lptr, B, n_max, _dev(grad_logZ, "grad_logZ", (B,)), _dev(logZ, "logZ", (B,)),
-        _dev(grad_L, "grad_L", (N, M)), _dev(grad_R, "grad_R", (N, M)), _dev(grad_log_root, "grad_log_root", (N,)),
+        _dev(grad_L, "grad_L", gs), _dev(grad_R, "grad_R", gs), _dev(grad_log_root, "grad_log_root", rs),
         _dev(grad_log_emit, "grad_log_emit", (B, n_max, P)), wp, wb, _stream()))
 
 
@@ -257,14 +265,16 @@ class Workload:
         dev = torch.device(device)
         t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
         self.log_root, self.L, self.R, self.log_emit = t(d["log_root"]), t(d["L"]), t(d["R"]), t(d["log_emit"])
+        if self.L.dim() == 3:  # one grammar per sentence
+            flags |= FLAG_PER_SENTENCE_GRAMMAR
         self.cfg = make_config(self.N, self.P, self.B, self.n_max, precision, flags)
         nbytes = spcfg_workspace_bytes_for(self.cfg, self.lengths, self.n_max)
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
         M = self.N + self.P
         f = dict(dtype=torch.float32, device=dev)
         self.logZ = torch.empty(self.B, **f)
-        self.grad_L, self.grad_R = torch.empty(self.N, M, **f), torch.empty(self.N, M, **f)
-        self.grad_log_root = torch.empty(self.N, **f)
+        self.grad_L, self.grad_R = torch.empty_like(self.L), torch.empty_like(self.R)
+        self.grad_log_root = torch.empty_like(self.log_root)
         self.grad_log_emit = torch.empty(self.B, self.n_max, self.P, **f)
 
     def forward(self):

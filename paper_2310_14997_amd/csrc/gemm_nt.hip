@@ -16,15 +16,54 @@ namespace {
 using namespace nt;
 constexpr int BK = 32;
 
-template <int EPI, int BM>
+template <int EPI, int BM, bool GROUPED>
 __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total_iters) {
   using G = Geo<BM>;
   extern __shared__ __align__(16) float lds[];
   __shared__ int s_last;
+  // grouped mode: first row tile, first row and row count of every sentence
+  __shared__ int s_tile0[GROUPED ? kMaxB + 1 : 1], s_row0[GROUPED ? kMaxB : 1], s_cnt[GROUPED ? kMaxB : 1];
+  __shared__ int s_wsum[4];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave % G::WM, wn = wave / G::WM;
-  const int tiles_m = (g.rows + BM - 1) / BM;
+  int tiles_m = (g.rows + BM - 1) / BM;
+  if (GROUPED) {
+    // exclusive prefix sum of the row-tile counts over the sentences (four sentences per thread)
+    int c[4], local = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int b = 4 * tid + q;
+      int cnt = 0;
+      if (b < g.ngroups) {
+        cnt = max(0, g.grp_lens[b] - g.grp_w + 1);
+        s_cnt[b] = cnt;
+        s_row0[b] = cnt > 0 ? (int)(g.grp_rowbase[b] - g.grp_row_first) : 0;
+      }
+      c[q] = (cnt + BM - 1) / BM;
+      local += c[q];
+    }
+    int x = local;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_up(x, o, 64);
+      if (lane >= o) x += y;
+    }
+    if (lane == 63) s_wsum[wave] = x;
+    __syncthreads();
+    int base = 0;
+    for (int i = 0; i < wave; ++i) base += s_wsum[i];
+    int excl = base + x - local;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int b = 4 * tid + q;
+      if (b < g.ngroups) s_tile0[b] = excl;
+      excl += c[q];
+    }
+    tiles_m = s_wsum[0] + s_wsum[1] + s_wsum[2] + s_wsum[3];
+    if (tid == 0) s_tile0[g.ngroups] = tiles_m;
+    __syncthreads();
+  }
   const int KT = g.K / BK;
   const int lc4 = tid & 7, lr = tid >> 3;  // staging: 8 float4 per tile row, 32 rows per pass
   const int lds_st = lr * LDT + lc4 * 4;
@@ -41,16 +80,28 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
     const int k0 = it - tile * KT;
     const int k1 = min(KT, k0 + (wg_end - it));
     const int tile_m = tile % tiles_m, tile_n = tile / tiles_m;
-    const int row0 = tile_m * BM, col0 = tile_n * BN;
+    int row0 = tile_m * BM, row_end = g.rows;
+    const int col0 = tile_n * BN;
+    const float* bmat = static_cast<const float*>(g.Bm);
+    if (GROUPED) {
+      int lo = 0, hi = g.ngroups;  // the sentence whose row tiles contain tile_m: s_tile0[lo] <= tile_m < s_tile0[lo + 1]
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (s_tile0[mid] <= tile_m) lo = mid; else hi = mid;
+      }
+      row0 = s_row0[lo] + (tile_m - s_tile0[lo]) * BM;
+      row_end = s_row0[lo] + s_cnt[lo];
+      bmat += (int64_t)lo * g.grp_b_stride;
+    }
 
     const float* ga[G::QA];
     const float* gb[4];
 #pragma unroll
     for (int q = 0; q < G::QA; ++q)
-      ga[q] = static_cast<const float*>(g.A) + (int64_t)min(row0 + lr + 32 * q, g.rows - 1) * g.lda + lc4 * 4;
+      ga[q] = static_cast<const float*>(g.A) + (int64_t)min(row0 + lr + 32 * q, row_end - 1) * g.lda + lc4 * 4;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      gb[q] = static_cast<const float*>(g.Bm) + (int64_t)min(col0 + lr + 32 * q, g.cols - 1) * g.ldb + lc4 * 4;
+      gb[q] = bmat + (int64_t)min(col0 + lr + 32 * q, g.cols - 1) * g.ldb + lc4 * 4;
     float4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;  // named scalars: arrays here end up in scratch memory
     floatx16 acc[G::MI][G::NI];
 #pragma unroll
@@ -134,29 +185,37 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
 #undef SPCFG_MFMA4
 
     finish_tile<BM>(g.partial, g.counters, acc, tile, k0, k1, KT, ipw, wg, it, wg_begin, tid, &s_last,
-                    [&](floatx16(&t)[G::MI][G::NI]) { epilogue<EPI, BM>(g, t, row0, col0, wm, wn, lane); });
+                    [&](floatx16(&t)[G::MI][G::NI]) { epilogue<EPI, BM>(g, t, row0, col0, wm, wn, lane, row_end); });
     it += k1 - k0;
   }
 }
 
-template <int EPI, int BM>
+template <int EPI, int BM, bool GROUPED>
 void launch(const NtArgs& a, hipStream_t st) {
   using G = Geo<BM>;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI, BM>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI, BM, GROUPED>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::kLdsBytes);
     attr_set = true;
   }
-  launch_shared(k_gemm_nt<EPI, BM>, a, BM, BK, G::kLdsBytes, st);
+  launch_shared(k_gemm_nt<EPI, BM, GROUPED>, a, BM, BK, G::kLdsBytes, st);
 }
 
 template <int EPI>
 void launch_bm(const NtArgs& a, hipStream_t st) {
+  if (a.grouped) {
+    switch (chosen_bm(a)) {
+      case 32: launch<EPI, 32, true>(a, st); break;
+      case 64: launch<EPI, 64, true>(a, st); break;
+      default: launch<EPI, 128, true>(a, st); break;
+    }
+    return;
+  }
   switch (chosen_bm(a)) {
-    case 32: launch<EPI, 32>(a, st); break;
-    case 64: launch<EPI, 64>(a, st); break;
-    default: launch<EPI, 128>(a, st); break;
+    case 32: launch<EPI, 32, false>(a, st); break;
+    case 64: launch<EPI, 64, false>(a, st); break;
+    default: launch<EPI, 128, false>(a, st); break;
   }
 }
 

@@ -53,7 +53,7 @@ template <int BM> struct Geo {
 
 template <int EPI, int BM>
 __device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[Geo<BM>::MI][Geo<BM>::NI], int row0, int col0,
-                                         int wm, int wn, int lane) {
+                                         int wm, int wn, int lane, int row_end) {
   using G = Geo<BM>;
   // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
 #pragma unroll
@@ -61,7 +61,7 @@ __device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[Geo<BM
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int r = row0 + (wm * G::MI + mi) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-      if (r >= g.rows) continue;
+      if (r >= row_end) continue;
       float scale = 1.0f;
       int64_t drow = r;
       if (EPI == NT_EPI_MASKROWS) {
@@ -199,7 +199,8 @@ inline int pick_wgs(int rows, int cols, int K) {
 // Launch helper: splits total = tiles * KT K-steps into equal shares.
 template <typename Kernel>
 void launch_shared(Kernel kernel, const NtArgs& a, int BM, int BKelems, size_t lds_bytes, hipStream_t st) {
-  const int tiles = ((a.rows + BM - 1) / BM) * ((a.cols + BN - 1) / BN);
+  const int tiles_m = a.grouped ? a.grp_tiles_m[BM == 32 ? 0 : (BM == 64 ? 1 : 2)] : (a.rows + BM - 1) / BM;
+  const int tiles = tiles_m * ((a.cols + BN - 1) / BN);
   const int KT = a.K / BKelems;
   const int total = tiles * KT;
   int Gn = pick_wgs(a.rows, a.cols, a.K);
@@ -217,7 +218,7 @@ void launch_shared(Kernel kernel, const NtArgs& a, int BM, int BKelems, size_t l
 }
 
 inline int chosen_bm(const NtArgs& a) {
-  int bm = pick_bm(a.rows, a.cols, a.K);
+  int bm = pick_bm(a.grouped ? a.grp_max_rows : a.rows, a.cols, a.K);
 #ifdef SPCFG_TUNING
   if (getenv("SPCFG_NT_BM")) bm = atoi(getenv("SPCFG_NT_BM"));
 #endif

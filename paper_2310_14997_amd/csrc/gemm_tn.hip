@@ -18,6 +18,9 @@ constexpr int TM = 128, TN = 128, TK = 32;
 constexpr int kStageT = (TM + TN) * TK + TK;  // A tile, B tile, scales
 constexpr size_t kLdsBytesT = 2 * kStageT * sizeof(float);
 
+// MODE 0: one reduction over the contiguous rows [0, S).  MODE 1, 2: one reduction per sentence (grouped mode of
+// TnArgs); every workgroup share is a whole number of output tiles, so no partial tiles are exchanged.
+template <int MODE>
 __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total_iters) {
   extern __shared__ __align__(16) float lds[];
   __shared__ int s_last;
@@ -25,7 +28,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
   const int tiles_a = (2 * g.Np) / TM;
-  const int KT = (int)((g.S + TK - 1) / TK);
+  const int KT = MODE ? g.grp_kt_max : (int)((g.S + TK - 1) / TK);
   const int wg = nt::renumbered_wg();
   const int wg_begin = wg * ipw;
   const int wg_end = min(wg_begin + ipw, total_iters);
@@ -33,8 +36,26 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
   while (it < wg_end) {
   const int tile = it / KT;
   const int k0 = it - tile * KT;
-  const int k1 = min(KT, k0 + (wg_end - it));
-  const int tile_a = tile % tiles_a, tile_b = tile / tiles_a;
+  int k1 = min(KT, k0 + (wg_end - it));
+  const int advance = k1 - k0;
+  int tile_l = tile, KTg = KT;
+  int64_t S = g.S, rbase = 0;
+  const int32_t* rl = nullptr;
+  float* gL = g.gL;
+  float* gR = g.gR;
+  if (MODE) {
+    const int tiles_pg = tiles_a * ((g.cols + TN - 1) / TN);
+    const int grp = tile / tiles_pg;
+    tile_l = tile - grp * tiles_pg;
+    const int n = g.grp_lens[grp];
+    S = MODE == 1 ? (int64_t)n * (n - 1) / 2 : n;
+    if (MODE == 1) rl = g.rowlist + g.grp_off[grp]; else rbase = g.grp_base[grp];
+    KTg = (int)((S + TK - 1) / TK);
+    k1 = min(k1, KTg);
+    gL += grp * g.grp_gstride;
+    gR += grp * g.grp_gstride;
+  }
+  const int tile_a = tile_l % tiles_a, tile_b = tile_l / tiles_a;
   const int a0 = tile_a * TM, b0 = tile_b * TN;
 
   const int lc4 = tid & 31, lr = tid >> 5;  // 32 float4 per tile row, 8 rows per pass
@@ -50,21 +71,22 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
 #define SPCFG_TN_LOAD1(RA, RB, Q, S0)                                              \
   {                                                                                \
     const int64_t s = (S0) + lr + 8 * (Q);                                         \
-    const bool ok = s < g.S;                                                       \
-    const int64_t sc = ok ? s : g.S - 1;                                           \
-    RA = *reinterpret_cast<const floatx4*>(gA + sc * g.lda);                        \
-    RB = *reinterpret_cast<const floatx4*>(gB + sc * g.ldb);                        \
+    const bool ok = s < S;                                                         \
+    const int64_t sc = ok ? s : S - 1;                                             \
+    const int64_t sr = MODE == 1 ? (int64_t)rl[sc] : rbase + sc;                   \
+    RA = *reinterpret_cast<const floatx4*>(gA + sr * g.lda);                        \
+    RB = *reinterpret_cast<const floatx4*>(gB + (MODE == 1 ? sr - g.brow0 : sr) * g.ldb); \
   }
 #define SPCFG_TN_LOAD(S0)                                                          \
   SPCFG_TN_LOAD1(ra0, rb0, 0, S0) SPCFG_TN_LOAD1(ra1, rb1, 1, S0)                  \
   SPCFG_TN_LOAD1(ra2, rb2, 2, S0) SPCFG_TN_LOAD1(ra3, rb3, 3, S0)                  \
-  if (tid < TK) rsc = ((S0) + tid < g.S) ? g.sc[(S0) + tid] : 0.0f;
+  if (tid < TK) rsc = ((S0) + tid < S) ? g.sc[MODE == 1 ? (int64_t)rl[(S0) + tid] : rbase + (S0) + tid] : 0.0f;
 #define SPCFG_TN_STORE(BUF, S0)                                                    \
   {                                                                                \
     float* as_ = lds + (BUF)*kStageT + lr * TM + lc4 * 4;                          \
     float* bs_ = lds + (BUF)*kStageT + TM * TK + lr * TN + lc4 * 4;                \
-    const bool k0_ = (S0) + lr < g.S, k1_ = (S0) + lr + 8 < g.S;                   \
-    const bool k2_ = (S0) + lr + 16 < g.S, k3_ = (S0) + lr + 24 < g.S;             \
+    const bool k0_ = (S0) + lr < S, k1_ = (S0) + lr + 8 < S;                       \
+    const bool k2_ = (S0) + lr + 16 < S, k3_ = (S0) + lr + 24 < S;                 \
     *reinterpret_cast<floatx4*>(as_) = k0_ ? ra0 : zero4;                           \
     *reinterpret_cast<floatx4*>(as_ + 8 * TM) = k1_ ? ra1 : zero4;                  \
     *reinterpret_cast<floatx4*>(as_ + 16 * TM) = k2_ ? ra2 : zero4;                 \
@@ -162,7 +184,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
 #undef SPCFG_TN_LOAD1
 #undef SPCFG_TN_STORE
 
-  nt::finish_tile<128>(g.partial, g.counters, acc, tile, k0, k1, KT, ipw, wg, it, wg_begin, tid, &s_last,
+  nt::finish_tile<128>(g.partial, g.counters, acc, tile, k0, k1, KTg, ipw, wg, it, wg_begin, tid, &s_last,
                        [&](floatx16(&t)[2][2]) {
     // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
 #pragma unroll
@@ -173,7 +195,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
         const int half = ar >= g.Np;
         const int arow = ar - half * g.Np;
         if (arow >= g.N) continue;
-        float* dst = (half ? g.gR : g.gL) + (int64_t)arow * g.ldg + g.col0;
+        float* dst = (half ? gR : gL) + (int64_t)arow * g.ldg + g.col0;
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) {
           const int c = b0 + wn * 64 + ni * 32 + (lane & 31);
@@ -184,7 +206,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
       }
     }
   });
-  it += k1 - k0;
+  it += advance;
   }  // share loop
 }
 
@@ -193,12 +215,28 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
 void launch_gemm_tn(const TnArgs& a, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_tn), hipFuncAttributeMaxDynamicSharedMemorySize,
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_tn<0>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)kLdsBytesT);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_tn<1>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)kLdsBytesT);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_tn<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)kLdsBytesT);
     attr_set = true;
   }
-  if (a.S <= 0) return;
   const int tiles = ((2 * a.Np) / TM) * ((a.cols + TN - 1) / TN);
+  if (a.grp_mode) {
+    // one workgroup per (sentence, output tile); the hardware scheduler balances sentences of different length
+    if (a.ngroups <= 0 || a.grp_kt_max <= 0) return;
+    const int64_t tiles_total = (int64_t)a.ngroups * tiles;
+    const int64_t total64 = tiles_total * a.grp_kt_max;
+    if (total64 >= ((int64_t)1 << 31)) return;  // guarded by the row-count limit of the layout
+    if (a.grp_mode == 1)
+      hipLaunchKernelGGL(k_gemm_tn<1>, dim3((unsigned)tiles_total), dim3(256), kLdsBytesT, st, a, a.grp_kt_max, (int)total64);
+    else
+      hipLaunchKernelGGL(k_gemm_tn<2>, dim3((unsigned)tiles_total), dim3(256), kLdsBytesT, st, a, a.grp_kt_max, (int)total64);
+    return;
+  }
+  if (a.S <= 0) return;
   const int KT = (int)((a.S + TK - 1) / TK);
   const int64_t total64 = (int64_t)tiles * KT;
   if (total64 >= ((int64_t)1 << 31)) return;  // guarded by the row-count limit of the layout
@@ -207,7 +245,7 @@ void launch_gemm_tn(const TnArgs& a, hipStream_t st) {
   if (Gn > total / 2) Gn = total / 2 > 0 ? total / 2 : 1;
   int ipw = (total + Gn - 1) / Gn;
   Gn = (total + ipw - 1) / ipw;
-  hipLaunchKernelGGL(k_gemm_tn, dim3(Gn), dim3(256), kLdsBytesT, st, a, ipw, total);
+  hipLaunchKernelGGL(k_gemm_tn<0>, dim3(Gn), dim3(256), kLdsBytesT, st, a, ipw, total);
 }
 
 }  // namespace spcfg

@@ -122,6 +122,22 @@ __global__ void k_plan_rows(int B, const int32_t* __restrict__ lens, const int32
   }
 }
 
+// Rows of width >= 2 listed sentence by sentence (width, then start): the reduction order of the per-sentence
+// rule gradients.  Sentence b owns entries [sum_{b'<b} n_b'(n_b'-1)/2, + n_b(n_b-1)/2).
+__global__ void k_plan_sentrows(int B, const int32_t* __restrict__ lens, const int32_t* __restrict__ rowbase,
+                                int32_t* __restrict__ sentrows, int32_t* __restrict__ sentoff) {
+  const int w = blockIdx.x + 2, b = blockIdx.y;
+  const int n = lens[b];
+  if (w > n) return;
+  int64_t off = 0;
+  for (int bb = 0; bb < b; ++bb) off += (int64_t)lens[bb] * (lens[bb] - 1) / 2;
+  if (w == 2 && threadIdx.x == 0) sentoff[b] = (int32_t)off;
+  // spans of widths 2..w-1 of this sentence: sum_{v=2}^{w-1} (n - v + 1)
+  off += (int64_t)(w - 2) * (n + 1) - ((int64_t)w * (w - 1) / 2 - 1);
+  const int base = rowbase[w * B + b];
+  for (int i = threadIdx.x; i <= n - w; i += blockDim.x) sentrows[off + i] = base + i;
+}
+
 // ------------------------------------------------------------------------------------------ weights
 // Stacks [L;R] (Sec. 3.2, kernel fusion: one matrix product for both projections) into zero-padded,
 // K-contiguous operands: Wn [2Np x Np] / Wp [2Np x Pp] for the forward products and their transposes
@@ -131,9 +147,12 @@ __global__ void k_pack_weights(const float* __restrict__ L, const float* __restr
                                int Pp, OutT* __restrict__ Wn, OutT* __restrict__ Wp, OutT* __restrict__ Wtn,
                                OutT* __restrict__ Wtp) {
   __shared__ float tile[32][33];
-  const float* src = blockIdx.z ? R : L;
   const int M = N + P;
-  const int half = blockIdx.z * Np;
+  const int gi = blockIdx.z >> 1, lr = blockIdx.z & 1;  // grammar, left / right factor
+  const float* src = (lr ? R : L) + (int64_t)gi * N * M;
+  Wn += (int64_t)gi * 2 * Np * Np; Wtn += (int64_t)gi * 2 * Np * Np;
+  Wp += (int64_t)gi * 2 * Np * Pp; Wtp += (int64_t)gi * 2 * Np * Pp;
+  const int half = lr * Np;
   const int c0 = blockIdx.x * 32;  // padded column: [0,Np) nonterminal part, [Np, Np+Pp) preterminal part
   const int a0 = blockIdx.y * 32;
   const bool ppart = c0 >= Np;
@@ -299,10 +318,11 @@ __global__ void k_root_fwd(int B, int N, int Np, int64_t S1, const int32_t* __re
                            const float* __restrict__ log_root, const float* __restrict__ T,
                            const int32_t* __restrict__ mexp, const uint32_t* __restrict__ tmaxb,
                            const float* __restrict__ xs, float* __restrict__ logZ, float* __restrict__ ztil,
-                           float* __restrict__ rmaxs) {
+                           float* __restrict__ rmaxs, int64_t root_stride) {
   __shared__ float redf[16];
   __shared__ double redd[16];
   const int b = blockIdx.x;
+  log_root += b * root_stride;
   const int64_t r = rootrow[b];
   float rm = -INFINITY;
   for (int a = threadIdx.x; a < N; a += blockDim.x) rm = fmaxf(rm, log_root[a]);
@@ -334,8 +354,9 @@ __global__ void k_root_bwd(int N, int Np, int64_t S1, const int32_t* __restrict_
                            const float* __restrict__ ztil, const float* __restrict__ rmaxs,
                            const int32_t* __restrict__ mexp, const uint32_t* __restrict__ tmaxb,
                            float* __restrict__ BH, float* __restrict__ UV, int32_t* __restrict__ uexp,
-                           uint32_t* __restrict__ umaxb, float* __restrict__ gsc) {
+                           uint32_t* __restrict__ umaxb, float* __restrict__ gsc, int64_t root_stride) {
   const int b = blockIdx.x;
+  log_root += b * root_stride;
   const int64_t r = rootrow[b];
   const float g = grad_logZ ? grad_logZ[b] : 1.0f;
   const float zt = ztil[b];
@@ -362,12 +383,18 @@ __global__ void k_grad_log_root(int B, int N, int Np, int64_t S1, const int32_t*
                                 const float* __restrict__ log_root, const float* __restrict__ grad_logZ,
                                 const float* __restrict__ ztil, const float* __restrict__ rmaxs,
                                 const float* __restrict__ T, const uint32_t* __restrict__ tmaxb,
-                                float* __restrict__ grad_log_root, int accumulate) {
+                                float* __restrict__ grad_log_root, int accumulate, int per_sentence) {
   const int a = blockIdx.x * blockDim.x + threadIdx.x;
   if (a >= N) return;
+  int b_lo = 0, b_hi = B;
+  if (per_sentence) {  // one root vector and one gradient per sentence: no sum over the batch
+    b_lo = blockIdx.y; b_hi = b_lo + 1;
+    log_root += (int64_t)b_lo * N;
+    grad_log_root += (int64_t)b_lo * N;
+  }
   const float lr = log_root[a];
   float acc = 0.0f;
-  for (int b = 0; b < B; ++b) {
+  for (int b = b_lo; b < b_hi; ++b) {
     const float zt = ztil[b];
     if (!(zt > 0.0f)) continue;
     const int64_t r = rootrow[b];
@@ -566,8 +593,14 @@ void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_
                      p.rootmask, p.tmaxb, p.umaxb);
 }
 
+void launch_plan_sentrows(const Layout& ly, const Ptrs& p, hipStream_t st) {
+  if (ly.n_max < 2) return;
+  hipLaunchKernelGGL(k_plan_sentrows, dim3(ly.n_max - 1, ly.B), dim3(64), 0, st, ly.B, p.lens, p.rowbase, p.sentrows,
+                     p.sentoff);
+}
+
 void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const float* R, hipStream_t st) {
-  dim3 grid((ly.Np + ly.Pp) / 32, ly.Np / 32, 2);
+  dim3 grid((ly.Np + ly.Pp) / 32, ly.Np / 32, 2 * ly.G);
   if (ly.bf16)
     hipLaunchKernelGGL(k_pack_weights<__bf16>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
                        (__bf16*)p.Wn, (__bf16*)p.Wp, (__bf16*)p.Wtn, (__bf16*)p.Wtp);
@@ -596,15 +629,18 @@ void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int6
 
 void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st) {
   hipLaunchKernelGGL(k_root_fwd, dim3(ly.B), dim3(256), 0, st, ly.B, ly.N, ly.Np, ly.S1, p.lens, p.rowbase,
-                     p.rootrow, log_root, p.T, p.mexp, p.tmaxb, p.xs, logZ, p.ztil, p.rmax);
+                     p.rootrow, log_root, p.T, p.mexp, p.tmaxb, p.xs, logZ, p.ztil, p.rmax,
+                     (int64_t)(ly.G > 1 ? ly.N : 0));
 }
 
 void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, const float* grad_logZ,
                      float* grad_log_root, int accumulate, hipStream_t st) {
   hipLaunchKernelGGL(k_root_bwd, dim3(ly.B), dim3(256), 0, st, ly.N, ly.Np, ly.S1, p.rootrow, log_root, grad_logZ,
-                     p.ztil, p.rmax, p.mexp, p.tmaxb, p.BH, p.UV, p.uexp, p.umaxb, p.gsc);
-  hipLaunchKernelGGL(k_grad_log_root, dim3((ly.N + 255) / 256), dim3(256), 0, st, ly.B, ly.N, ly.Np, ly.S1,
-                     p.rootrow, log_root, grad_logZ, p.ztil, p.rmax, p.T, p.tmaxb, grad_log_root, accumulate);
+                     p.ztil, p.rmax, p.mexp, p.tmaxb, p.BH, p.UV, p.uexp, p.umaxb, p.gsc,
+                     (int64_t)(ly.G > 1 ? ly.N : 0));
+  hipLaunchKernelGGL(k_grad_log_root, dim3((ly.N + 255) / 256, ly.G > 1 ? ly.B : 1), dim3(256), 0, st, ly.B, ly.N,
+                     ly.Np, ly.S1, p.rootrow, log_root, grad_logZ, p.ztil, p.rmax, p.T, p.tmaxb, grad_log_root,
+                     accumulate, ly.G > 1 ? 1 : 0);
 }
 
 void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {

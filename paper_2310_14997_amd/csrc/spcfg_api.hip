@@ -26,14 +26,16 @@ int check_cfg(const spcfg_config* c) {
   if (c->N < 1 || c->P < 1 || c->N > (1 << 16) || c->P > (1 << 16)) return SPCFG_ERR_SHAPE;
   if (c->max_B < 1 || c->max_B > kMaxB || c->max_n < 2 || c->max_n > kMaxLen) return SPCFG_ERR_SHAPE;
   if (c->precision != SPCFG_PRECISION_FP32 && c->precision != SPCFG_PRECISION_BF16) return SPCFG_ERR_UNSUPPORTED;
-  if (c->flags & ~(uint32_t)SPCFG_FLAG_ACCUMULATE_GRADS) return SPCFG_ERR_UNSUPPORTED;
+  if (c->flags & ~(uint32_t)(SPCFG_FLAG_ACCUMULATE_GRADS | SPCFG_FLAG_PER_SENTENCE_GRAMMAR)) return SPCFG_ERR_UNSUPPORTED;
+  if ((c->flags & SPCFG_FLAG_PER_SENTENCE_GRAMMAR) && c->precision != SPCFG_PRECISION_FP32) return SPCFG_ERR_UNSUPPORTED;
   return SPCFG_OK;
 }
 
 // Byte layout of the workspace for a batch with S1 leaf rows and S2 rows of width >= 2.
-Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int bf16) {
+Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int bf16, int per_sentence) {
   Layout ly{};
   ly.N = N; ly.P = P; ly.B = B; ly.n_max = n_max; ly.bf16 = bf16;
+  ly.G = per_sentence ? B : 1;
   ly.S1pad = (S1 + 63) / 64 * 64; ly.S2pad = (S2 + 63) / 64 * 64;
   ly.Np = round_up(N, kPad);
   ly.Pp = round_up(P, kPad);
@@ -56,7 +58,8 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   ly.gsc = take(f4 * ly.Sall);
   ly.xs = take(f4 * S1);
   // the widest launch has at most max(S1, S2) rows (one width) and 2Np columns
-  ly.n_counters = gemm_nt_tiles((int)(S1 > S2 ? S1 : S2), 2 * ly.Np);
+  // (grouped launches round every sentence's rows up to whole row tiles: at most one extra tile per sentence)
+  ly.n_counters = gemm_nt_tiles((int)(S1 > S2 ? S1 : S2) + (per_sentence ? 32 * B : 0), 2 * ly.Np);
   {  // the bf16 rule-gradient product has 2Np rows and up to max(Np, Pp) columns
     const int g = (2 * ly.Np / 128 + 1) * ((ly.Np > ly.Pp ? ly.Np : ly.Pp) / 128 + 1);
     if (g > ly.n_counters) ly.n_counters = g;
@@ -64,10 +67,11 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   ly.counters = take(i4 * (size_t)ly.n_counters);
   ly.partial = take(gemm_nt_partial_bytes(kGemmWgs));
   const size_t w4 = bf16 ? 2 : 4;  // bytes per packed weight
-  ly.Wn = take(w4 * 2 * (size_t)ly.Np * ly.Np);
-  ly.Wp = take(w4 * 2 * (size_t)ly.Np * ly.Pp);
-  ly.Wtn = take(w4 * 2 * (size_t)ly.Np * ly.Np);
-  ly.Wtp = take(w4 * 2 * (size_t)ly.Np * ly.Pp);
+  ly.Wn = take(w4 * 2 * (size_t)ly.Np * ly.Np * ly.G);
+  ly.Wp = take(w4 * 2 * (size_t)ly.Np * ly.Pp * ly.G);
+  ly.Wtn = take(w4 * 2 * (size_t)ly.Np * ly.Np * ly.G);
+  ly.Wtp = take(w4 * 2 * (size_t)ly.Np * ly.Pp * ly.G);
+  if (per_sentence) { ly.sentrows = take(i4 * (size_t)S2); ly.sentoff = take(i4 * (size_t)B); }
   if (bf16) {
     ly.UVt_n = take(2 * 2 * (size_t)ly.Np * ly.S2pad);
     ly.Tt = take(2 * (size_t)ly.Np * ly.S2pad);
@@ -95,6 +99,7 @@ Ptrs resolve(const Layout& ly, void* ws) {
   p.leafE = (float*)(b + ly.leafE); p.T = (float*)(b + ly.T); p.HZ = (float*)(b + ly.HZ);
   p.UV = (float*)(b + ly.UV); p.BH = (float*)(b + ly.BH);
   p.partial = (float*)(b + ly.partial); p.counters = (int32_t*)(b + ly.counters);
+  p.sentrows = (int32_t*)(b + ly.sentrows); p.sentoff = (int32_t*)(b + ly.sentoff);
   p.UVt_n = b + ly.UVt_n; p.Tt = b + ly.Tt; p.UVt_p = b + ly.UVt_p; p.Et = b + ly.Et;
   p.Wn = (float*)(b + ly.Wn); p.Wp = (float*)(b + ly.Wp); p.Wtn = (float*)(b + ly.Wtn); p.Wtp = (float*)(b + ly.Wtp);
   return p;
@@ -118,7 +123,8 @@ int make_plan(const spcfg_config* cfg, const int32_t* lengths, int B, int n_max,
   }
   const int64_t S1 = plan->cnt[1], Sall = run;
   if (Sall >= (int64_t)1 << 30) return SPCFG_ERR_SHAPE;
-  *ly = make_layout(cfg->N, cfg->P, B, n_max, S1, Sall - S1, cfg->precision == SPCFG_PRECISION_BF16);
+  *ly = make_layout(cfg->N, cfg->P, B, n_max, S1, Sall - S1, cfg->precision == SPCFG_PRECISION_BF16,
+                    (cfg->flags & SPCFG_FLAG_PER_SENTENCE_GRAMMAR) != 0);
   return SPCFG_OK;
 }
 
@@ -183,6 +189,21 @@ int check_ws(const Layout& ly, void* ws, size_t bytes) {
   return SPCFG_OK;
 }
 
+// One grammar per sentence: the launch for width w multiplies each sentence's rows with that sentence's panel.
+void set_groups(NtArgs& a, const Plan& plan, const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t b_stride) {
+  if (ly.G == 1) return;
+  a.grouped = 1; a.ngroups = ly.B; a.grp_w = w;
+  a.grp_lens = p.lens; a.grp_rowbase = p.rowbase + (size_t)w * ly.B; a.grp_row_first = row0; a.grp_b_stride = b_stride;
+  a.grp_tiles_m[0] = a.grp_tiles_m[1] = a.grp_tiles_m[2] = 0;
+  a.grp_max_rows = 0;
+  for (int b = 0; b < ly.B; ++b) {
+    const int cnt = plan.lens.v[b] - w + 1;
+    if (cnt <= 0) continue;
+    a.grp_tiles_m[0] += (cnt + 31) / 32; a.grp_tiles_m[1] += (cnt + 63) / 64; a.grp_tiles_m[2] += (cnt + 127) / 128;
+    if (cnt > a.grp_max_rows) a.grp_max_rows = cnt;
+  }
+}
+
 int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const Ptrs& p, const float* log_root,
             const float* L, const float* R, const float* log_emit, float* logZ, hipStream_t st) {
   const int n_max = ly.n_max;
@@ -191,6 +212,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
   {
     Scope s(st, SPCFG_PROF_SETUP, 4.0 * 2 * (double)ly.N * (ly.N + ly.P) * 3 + 8.0 * ly.S1 * ly.P, 4);
     launch_plan(ly, p, plan.lens, st);
+    if (ly.G > 1) launch_plan_sentrows(ly, p, st);
     launch_pack_weights(ly, p, L, R, st);
     launch_leaf_prep(ly, p, log_emit, st);
   }
@@ -201,6 +223,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     a.A = p.leafE; a.lda = Pp; a.Bm = p.Wp; a.ldb = Pp; a.C = p.HZ; a.ldc = 2 * Np;
     a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
     a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb;
+    set_groups(a, plan, ly, p, 1, 0, 2 * Np * Pp);
     launch_gemm_nt(a, st);
   }
   for (int w = 2; w <= n_max; ++w) {
@@ -218,6 +241,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
     a.rows = (int)rows; a.cols = (int)(2 * Np); a.K = (int)Np;
     a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb + row0;
+    set_groups(a, plan, ly, p, w, row0, 2 * Np * Np);
     launch_gemm_nt(a, st);
   }
   {
@@ -260,18 +284,36 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.N * rows);
       a.Bm = p.Wtn; a.ldb = 2 * Np; a.C = p.BH + (row0 - ly.S1) * Np; a.ldc = Np; a.cols = (int)Np;
       a.epilogue = NT_EPI_MASKROWS; a.rowmask = p.rootmask + row0; a.rowmaxb = p.umaxb + row0;
+      set_groups(a, plan, ly, p, w, row0, 2 * Np * Np);
       launch_gemm_nt(a, st);
     } else {
       Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.P * rows);
       a.Bm = p.Wtp; a.ldb = 2 * Np; a.C = grad_log_emit; a.ldc = ly.P; a.cols = ly.P;
       a.epilogue = NT_EPI_LEAF_EMIT; a.E = p.leafE; a.lde = Pp; a.rowexp = p.uexp;
       a.row_b = p.row_b; a.row_i = p.row_i; a.n_max = n_max;
+      set_groups(a, plan, ly, p, 1, 0, 2 * Np * Pp);
       launch_gemm_nt(a, st);
     }
   }
   {
     Scope s(st, SPCFG_PROF_GEMM_GRAD, 4.0 * ly.N * ((double)ly.N * ly.S2 + (double)ly.P * ly.S1), 2);
-    if (!ly.bf16) {
+    if (ly.G > 1) {
+      // one reduction per sentence over its own spans of width >= 2 (listed in sentrows), one over its leaves
+      int n_longest = 2;
+      for (int b = 0; b < ly.B; ++b) n_longest = plan.lens.v[b] > n_longest ? plan.lens.v[b] : n_longest;
+      TnArgs t{};
+      t.Np = (int)Np; t.N = ly.N; t.gL = grad_L; t.gR = grad_R; t.ldg = ly.N + ly.P; t.accumulate = acc;
+      t.ngroups = ly.B; t.grp_lens = p.lens; t.grp_gstride = (int64_t)ly.N * (ly.N + ly.P);
+      t.A = p.UV; t.lda = 2 * Np; t.sc = p.gsc;
+      t.grp_mode = 1; t.rowlist = p.sentrows; t.grp_off = p.sentoff; t.brow0 = ly.S1;
+      t.Bm = p.T; t.ldb = Np; t.cols = ly.N; t.col0 = 0;
+      t.grp_kt_max = (int)(((int64_t)n_longest * (n_longest - 1) / 2 + 31) / 32);
+      launch_gemm_tn(t, st);
+      t.grp_mode = 2; t.grp_base = p.rowbase + ly.B;  // first leaf row of every sentence
+      t.Bm = p.leafE; t.ldb = Pp; t.cols = ly.P; t.col0 = ly.N;
+      t.grp_kt_max = (n_longest + 31) / 32;
+      launch_gemm_tn(t, st);
+    } else if (!ly.bf16) {
       TnArgs t{};
       t.partial = p.partial; t.counters = p.counters; t.max_wgs = kGemmWgs;
       t.Np = (int)Np; t.N = ly.N; t.gL = grad_L; t.gR = grad_R; t.ldg = ly.N + ly.P; t.accumulate = acc;
@@ -314,7 +356,8 @@ int spcfg_workspace_bytes(const spcfg_config* cfg, size_t* out_bytes) {
   const int64_t Sall = (int64_t)cfg->max_B * cfg->max_n * (cfg->max_n + 1) / 2;
   if (Sall >= (int64_t)1 << 30) return SPCFG_ERR_SHAPE;
   *out_bytes = make_layout(cfg->N, cfg->P, cfg->max_B, cfg->max_n, S1, Sall - S1,
-                           cfg->precision == SPCFG_PRECISION_BF16).total;
+                           cfg->precision == SPCFG_PRECISION_BF16,
+                           (cfg->flags & SPCFG_FLAG_PER_SENTENCE_GRAMMAR) != 0).total;
   return SPCFG_OK;
 }
 

@@ -31,6 +31,7 @@ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 struct Layout {
   int N, P, Np, Pp, B, n_max;
+  int G;                 // number of grammars: 1 (shared by the batch) or B (one per sentence)
   int bf16;              // projections with bf16 operands: packed weights are bf16, transposed bf16 copies for the rule gradients
   int64_t S1pad, S2pad;  // row counts rounded up to 64 (K of the bf16 rule-gradient product)
   int64_t S1, S2, Sall;  // leaf rows, rows of width >= 2, all rows
@@ -38,6 +39,7 @@ struct Layout {
   size_t lens, rowbase, row_b, row_i, rootmask, rootrow, mexp, uexp, tmaxb, umaxb, gsc, xs, ztil, rmax;
   size_t leafE, T, HZ, UV, BH, Wn, Wp, Wtn, Wtp, partial, counters;
   size_t UVt_n, Tt, UVt_p, Et;  // bf16 mode only
+  size_t sentrows, sentoff;     // per-sentence grammars only: rows of width >= 2 listed sentence by sentence, first entry of each
   int n_counters;
   size_t total;
 };
@@ -49,6 +51,7 @@ struct Ptrs {  // device pointers resolved from a Layout
   float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp, *partial;  // W* hold bf16 data in bf16 mode
   void *UVt_n, *Tt, *UVt_p, *Et;
   int32_t* counters;
+  int32_t* sentrows; int32_t* sentoff;
 };
 
 struct LenArg {  // lengths passed by value: no host buffer has to outlive the call
@@ -57,11 +60,13 @@ struct LenArg {  // lengths passed by value: no host buffer has to outlive the c
 
 // ---- launchers (each only enqueues on `st`) -------------------------------------------------------
 void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_t st);
+void launch_plan_sentrows(const Layout& ly, const Ptrs& p, hipStream_t st);
 void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const float* R, hipStream_t st);
 void launch_transpose_bf16(const float* X, int64_t ldx, int cols, const float* sc, int64_t S, int64_t Spad, void* Xt,
                            hipStream_t st);
 void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hipStream_t st);
 void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st);
+// log_root (and grad_log_root) hold one vector per grammar: [G x N]
 void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st);
 void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, const float* grad_logZ,
                      float* grad_log_root, int accumulate, hipStream_t st);
@@ -90,6 +95,13 @@ struct NtArgs {
   float* gL; float* gR; int64_t ldg; int col0, Np, Nvalid, accumulate;
   // work sharing across workgroups: scratch for partial tiles and per-tile arrival counters (zero between launches)
   float* partial; int32_t* counters; int max_wgs;
+  // Grouped mode (one grammar per sentence; fp32 only): the rows of the launch are the spans of one width, sentence
+  // after sentence; sentence b owns rows [grp_rowbase[b] - grp_row_first, + max(0, grp_lens[b] - grp_w + 1)) and
+  // multiplies them with its own operand Bm + b * grp_b_stride.  Row tiles never straddle two sentences.
+  int grouped, ngroups, grp_w;
+  const int32_t* grp_lens; const int32_t* grp_rowbase; int64_t grp_row_first; int64_t grp_b_stride;
+  int grp_tiles_m[3];  // host: number of row tiles for tile heights 32, 64, 128
+  int grp_max_rows;    // host: largest row count of one sentence
 };
 void launch_gemm_nt(const NtArgs& a, hipStream_t st);
 void launch_gemm_nt16(const NtArgs& a, hipStream_t st);  // bf16-operand variant (called through launch_gemm_nt)
@@ -109,6 +121,14 @@ struct TnArgs {
   float* gL; float* gR; int64_t ldg; int col0;  // destination column offset (0 or N)
   int accumulate;
   float* partial; int32_t* counters; int max_wgs;  // work sharing scratch, as in NtArgs
+  // Grouped mode (one grammar per sentence): sentence b reduces over its own rows only and writes gL / gR + b * grp_gstride;
+  // A, Bm, sc are then the whole arrays, indexed by span row.
+  //   grp_mode 1: rows rowlist[grp_off[b] + s], s < n_b (n_b - 1) / 2  (spans of width >= 2; the Bm row is row - brow0)
+  //   grp_mode 2: rows grp_base[b] + s, s < n_b                        (leaves)
+  int grp_mode, ngroups;
+  const int32_t* grp_lens; const int32_t* grp_off; const int32_t* grp_base; const int32_t* rowlist;
+  int64_t brow0, grp_gstride;
+  int grp_kt_max;  // number of 32-row steps of the longest per-sentence reduction
 };
 void launch_gemm_tn(const TnArgs& a, hipStream_t st);
 

@@ -113,6 +113,43 @@ def make_inputs(name="tiny", seed=None, pad_value=0.0, **overrides):
                 log_emit=log_emit, lengths=lengths, tokens=tokens)
 
 
+def make_inputs_per_sentence(name="tiny", seed=None, pad_value=0.0, **overrides):
+    """Like make_inputs, but every sentence has a grammar of its own (the setting of the compound variant,
+    App. A, where rule probabilities depend on a per-sentence latent vector): log_root [B, N], L, R [B, N, N+P],
+    and emissions drawn from a per-sentence table.  A shared random part plus a per-sentence perturbation of the
+    logits, so the grammars are related but distinct."""
+    cfg = dict(CONFIGS[name])
+    cfg.update(overrides)
+    if seed is None:
+        seed = BASE_SEED + 200 + _ORDER.index(name)
+    rng = np.random.default_rng(seed)
+    B, N, P, V = int(cfg["B"]), int(cfg["N"]), int(cfg["P"]), int(cfg["V"])
+    M = N + P
+    law = cfg["lengths"]
+    lengths = draw_lengths(rng, law, B) if isinstance(law, tuple) else np.asarray(law, dtype=np.int32)
+    assert lengths.shape == (B,)
+    n_max = int(lengths.max())
+    sc = cfg["lr_scale"]
+    base = dict(root=rng.normal(size=N), L=sc * rng.normal(size=(N, M)), R=sc * rng.normal(size=(N, M)),
+                E=rng.normal(size=(P, V)))
+    log_root = np.empty((B, N), np.float32)
+    L = np.empty((B, N, M), np.float32)
+    R = np.empty((B, N, M), np.float32)
+    tokens = np.full((B, n_max), -1, dtype=np.int64)
+    log_emit = np.full((B, n_max, P), pad_value, dtype=np.float32)
+    for b in range(B):
+        log_root[b] = _log_softmax_rows((base["root"] + 0.5 * rng.normal(size=N))[None, :])[0]
+        L[b] = _softmax_rows(base["L"] + 0.5 * sc * rng.normal(size=(N, M)))
+        R[b] = _softmax_rows(base["R"] + 0.5 * sc * rng.normal(size=(N, M)))
+        n = int(lengths[b])
+        tok = zipf_tokens(rng, V, n)
+        tokens[b, :n] = tok
+        log_emis = _log_softmax_rows(base["E"][:, tok].T + 0.5 * rng.normal(size=(n, P)))  # only the columns in use
+        log_emit[b, :n, :] = log_emis.astype(np.float32)
+    return dict(name=name, seed=seed, B=B, N=N, P=P, V=V, n_max=n_max, precision="fp32", log_root=log_root, L=L, R=R,
+                log_emit=log_emit, lengths=lengths, tokens=tokens)
+
+
 def make_logits(name="tiny", seed=None, **overrides):
     """Scores for the rule-probability front-end of one named workload: root [N], L/R [N, N+P] (scaled like the
     workload's grammar), emission [P, V] logits, int32 tokens [B, n_max] (-1 on padding) and lengths."""
