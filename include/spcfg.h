@@ -120,9 +120,9 @@ const char* spcfg_strerror(int code);
 const char* spcfg_last_hip_error(void);
 
 /*
- * Per-kernel-class timing.  While enabled, a HIP event is recorded on the caller's stream after every kernel
- * class step (launches on one stream run back to back, so the time between two consecutive events is the
- * step's; this perturbs the schedule slightly, so whole-step timing should be taken with profiling disabled).
+ * Per-kernel-class timing.  While enabled, every kernel launch carries a pair of HIP events bound to the start
+ * and the end of that kernel on the caller's stream; a class's time is the sum of its kernels' durations
+ * (this perturbs the schedule slightly, so whole-step timing should be taken with profiling disabled).
  * spcfg_profile_read synchronises the recorded events, then fills, for class c in [0, SPCFG_PROF_CLASSES):
  *   ms[c]      total device time of the class since spcfg_profile_enable(1)
  *   launches[c] number of launches

@@ -214,7 +214,7 @@ void launch_shared(Kernel kernel, const NtArgs& a, int BM, int BKelems, size_t l
 #endif
   int ipw = (total + Gn - 1) / Gn;
   Gn = (total + ipw - 1) / ipw;
-  hipLaunchKernelGGL(kernel, dim3(Gn), dim3(256), lds_bytes, st, a, ipw, total);
+  launch_k(kernel, dim3(Gn), dim3(256), lds_bytes, st, a, ipw, total);
 }
 
 inline int chosen_bm(const NtArgs& a) {

@@ -231,9 +231,9 @@ void launch_gemm_tn(const TnArgs& a, hipStream_t st) {
     const int64_t total64 = tiles_total * a.grp_kt_max;
     if (total64 >= ((int64_t)1 << 31)) return;  // guarded by the row-count limit of the layout
     if (a.grp_mode == 1)
-      hipLaunchKernelGGL(k_gemm_tn<1>, dim3((unsigned)tiles_total), dim3(256), kLdsBytesT, st, a, a.grp_kt_max, (int)total64);
+      launch_k(k_gemm_tn<1>, dim3((unsigned)tiles_total), dim3(256), kLdsBytesT, st, a, a.grp_kt_max, (int)total64);
     else
-      hipLaunchKernelGGL(k_gemm_tn<2>, dim3((unsigned)tiles_total), dim3(256), kLdsBytesT, st, a, a.grp_kt_max, (int)total64);
+      launch_k(k_gemm_tn<2>, dim3((unsigned)tiles_total), dim3(256), kLdsBytesT, st, a, a.grp_kt_max, (int)total64);
     return;
   }
   if (a.S <= 0) return;
@@ -245,7 +245,7 @@ void launch_gemm_tn(const TnArgs& a, hipStream_t st) {
   if (Gn > total / 2) Gn = total / 2 > 0 ? total / 2 : 1;
   int ipw = (total + Gn - 1) / Gn;
   Gn = (total + ipw - 1) / ipw;
-  hipLaunchKernelGGL(k_gemm_tn<0>, dim3(Gn), dim3(256), kLdsBytesT, st, a, ipw, total);
+  launch_k(k_gemm_tn<0>, dim3(Gn), dim3(256), kLdsBytesT, st, a, ipw, total);
 }
 
 }  // namespace spcfg

@@ -587,58 +587,58 @@ k_span_marginals(int B, int N, int Np, int n_max, int64_t S1, const int32_t* __r
 }  // namespace
 
 void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_t st) {
-  hipLaunchKernelGGL(k_plan_rowbase, dim3(1), dim3(256), 0, st, lens, ly.B, ly.n_max, p.lens, p.rowbase, p.rootrow,
+  launch_k(k_plan_rowbase, dim3(1), dim3(256), 0, st, lens, ly.B, ly.n_max, p.lens, p.rowbase, p.rootrow,
                      p.counters, ly.n_counters);
-  hipLaunchKernelGGL(k_plan_rows, dim3(ly.n_max, ly.B), dim3(64), 0, st, ly.B, p.lens, p.rowbase, p.row_b, p.row_i,
+  launch_k(k_plan_rows, dim3(ly.n_max, ly.B), dim3(64), 0, st, ly.B, p.lens, p.rowbase, p.row_b, p.row_i,
                      p.rootmask, p.tmaxb, p.umaxb);
 }
 
 void launch_plan_sentrows(const Layout& ly, const Ptrs& p, hipStream_t st) {
   if (ly.n_max < 2) return;
-  hipLaunchKernelGGL(k_plan_sentrows, dim3(ly.n_max - 1, ly.B), dim3(64), 0, st, ly.B, p.lens, p.rowbase, p.sentrows,
+  launch_k(k_plan_sentrows, dim3(ly.n_max - 1, ly.B), dim3(64), 0, st, ly.B, p.lens, p.rowbase, p.sentrows,
                      p.sentoff);
 }
 
 void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const float* R, hipStream_t st) {
   dim3 grid((ly.Np + ly.Pp) / 32, ly.Np / 32, 2 * ly.G);
   if (ly.bf16)
-    hipLaunchKernelGGL(k_pack_weights<__bf16>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
+    launch_k(k_pack_weights<__bf16>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
                        (__bf16*)p.Wn, (__bf16*)p.Wp, (__bf16*)p.Wtn, (__bf16*)p.Wtp);
   else
-    hipLaunchKernelGGL(k_pack_weights<float>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp, p.Wn, p.Wp,
+    launch_k(k_pack_weights<float>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp, p.Wn, p.Wp,
                        p.Wtn, p.Wtp);
 }
 
 void launch_transpose_bf16(const float* X, int64_t ldx, int cols, const float* sc, int64_t S, int64_t Spad, void* Xt,
                            hipStream_t st) {
   dim3 grid((unsigned)(Spad / 64), (unsigned)(cols / 64));
-  hipLaunchKernelGGL(k_transpose_bf16, grid, dim3(256), 0, st, X, ldx, sc, S, Spad, (__bf16*)Xt);
+  launch_k(k_transpose_bf16, grid, dim3(256), 0, st, X, ldx, sc, S, Spad, (__bf16*)Xt);
 }
 
 void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hipStream_t st) {
-  hipLaunchKernelGGL(k_leaf_prep, dim3((unsigned)ly.S1), dim3(256), 0, st, log_emit, ly.P, ly.Pp, ly.n_max, p.row_b,
+  launch_k(k_leaf_prep, dim3((unsigned)ly.S1), dim3(256), 0, st, log_emit, ly.P, ly.Pp, ly.n_max, p.row_b,
                      p.row_i, p.leafE, p.xs, p.mexp, p.tmaxb);
 }
 
 void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
   const size_t sh = (size_t)(w - 1) * 12;
   const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
-  hipLaunchKernelGGL(k_split_fwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.rowbase, p.row_b, p.row_i,
+  launch_k(k_split_fwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.rowbase, p.row_b, p.row_i,
                      p.HZ, p.T, p.mexp, p.tmaxb);
 }
 
 void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st) {
-  hipLaunchKernelGGL(k_root_fwd, dim3(ly.B), dim3(256), 0, st, ly.B, ly.N, ly.Np, ly.S1, p.lens, p.rowbase,
+  launch_k(k_root_fwd, dim3(ly.B), dim3(256), 0, st, ly.B, ly.N, ly.Np, ly.S1, p.lens, p.rowbase,
                      p.rootrow, log_root, p.T, p.mexp, p.tmaxb, p.xs, logZ, p.ztil, p.rmax,
                      (int64_t)(ly.G > 1 ? ly.N : 0));
 }
 
 void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, const float* grad_logZ,
                      float* grad_log_root, int accumulate, hipStream_t st) {
-  hipLaunchKernelGGL(k_root_bwd, dim3(ly.B), dim3(256), 0, st, ly.N, ly.Np, ly.S1, p.rootrow, log_root, grad_logZ,
+  launch_k(k_root_bwd, dim3(ly.B), dim3(256), 0, st, ly.N, ly.Np, ly.S1, p.rootrow, log_root, grad_logZ,
                      p.ztil, p.rmax, p.mexp, p.tmaxb, p.BH, p.UV, p.uexp, p.umaxb, p.gsc,
                      (int64_t)(ly.G > 1 ? ly.N : 0));
-  hipLaunchKernelGGL(k_grad_log_root, dim3((ly.N + 255) / 256, ly.G > 1 ? ly.B : 1), dim3(256), 0, st, ly.B, ly.N,
+  launch_k(k_grad_log_root, dim3((ly.N + 255) / 256, ly.G > 1 ? ly.B : 1), dim3(256), 0, st, ly.B, ly.N,
                      ly.Np, ly.S1, p.rootrow, log_root, grad_logZ, p.ztil, p.rmax, p.T, p.tmaxb, grad_log_root,
                      accumulate, ly.G > 1 ? 1 : 0);
 }
@@ -646,17 +646,17 @@ void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, con
 void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
   const size_t sh = (size_t)ly.n_max * 12;
   const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
-  hipLaunchKernelGGL(k_split_bwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.lens, p.rowbase, p.row_b,
+  launch_k(k_split_bwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.lens, p.rowbase, p.row_b,
                      p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc);
 }
 
 void launch_zero_pad_emit(const Layout& ly, const Ptrs& p, float* grad_log_emit, hipStream_t st) {
-  hipLaunchKernelGGL(k_zero_pad_emit, dim3(ly.B), dim3(256), 0, st, ly.P, ly.n_max, p.lens, grad_log_emit);
+  launch_k(k_zero_pad_emit, dim3(ly.B), dim3(256), 0, st, ly.P, ly.n_max, p.lens, grad_log_emit);
 }
 
 void launch_span_marginals(const Layout& ly, const Ptrs& p, float* mu, int32_t* label, hipStream_t st) {
   const dim3 grid((unsigned)(ly.n_max * ly.n_max), (unsigned)ly.B);
-  hipLaunchKernelGGL(k_span_marginals, grid, dim3(64), 0, st, ly.B, ly.N, ly.Np, ly.n_max, ly.S1, p.lens, p.rowbase,
+  launch_k(k_span_marginals, grid, dim3(64), 0, st, ly.B, ly.N, ly.Np, ly.n_max, ly.S1, p.lens, p.rowbase,
                      p.T, p.BH, p.mexp, p.uexp, p.umaxb, mu, label);
 }
 

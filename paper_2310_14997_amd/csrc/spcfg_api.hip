@@ -129,52 +129,56 @@ int make_plan(const spcfg_config* cfg, const int32_t* lengths, int B, int n_max,
 }
 
 // ---- profiling -------------------------------------------------------------------------------------
-// One event after every kernel class scope; a scope's start is the end mark of the scope before it (launches
-// on one stream run back to back), so only one event sits between two kernels.  Each API call starts with a
-// fresh mark: idle time between calls is not charged to anybody.
+// A Scope names the kernel class of the launches made during its lifetime; every such launch gets its own
+// start/stop event pair (see launch_k), so a class's time is the sum of its kernels' own durations.
 struct Prof {
   bool on = false;
-  struct Rec { int a, b, cls; };      // indices into marks
+  int cur_cls = -1;
+  struct Rec { hipEvent_t a, b; int cls; };
   std::vector<Rec> recs;
-  std::vector<hipEvent_t> marks;      // recorded boundary events, in order
   std::vector<hipEvent_t> pool;
-  int last = -1;                      // latest boundary of the current call, -1: none yet
   double work[SPCFG_PROF_CLASSES] = {0};
   int64_t launches[SPCFG_PROF_CLASSES] = {0};
-  int mark(hipStream_t st) {
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
     hipEvent_t e = nullptr;
-    if (!pool.empty()) { e = pool.back(); pool.pop_back(); }
-    else if (hipEventCreate(&e) != hipSuccess) return -1;
-    if (hipEventRecord(e, st) != hipSuccess) { pool.push_back(e); return -1; }
-    marks.push_back(e);
-    return (int)marks.size() - 1;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
   }
   void recycle() {
-    for (hipEvent_t e : marks) pool.push_back(e);
-    marks.clear();
+    for (auto& r : recs) { pool.push_back(r.a); pool.push_back(r.b); }
     recs.clear();
-    last = -1;
   }
 } g_prof;
 
-void prof_begin_call() { g_prof.last = -1; }
-
-struct Scope {  // charges the device time of the launches made during its lifetime to one kernel class
-  hipStream_t st; int cls; int a = -1;
-  Scope(hipStream_t s, int c, double work, int nlaunch = 1) : st(s), cls(c) {
+struct Scope {
+  int prev;
+  Scope(hipStream_t, int c, double work, int nlaunch = 1) : prev(g_prof.cur_cls) {
     if (!g_prof.on) return;
-    if (g_prof.last < 0) g_prof.last = g_prof.mark(st);
-    a = g_prof.last;
+    g_prof.cur_cls = c;
     g_prof.work[c] += work;
     g_prof.launches[c] += nlaunch;
   }
-  ~Scope() {
-    if (!g_prof.on || a < 0) return;
-    const int b = g_prof.mark(st);
-    if (b >= 0) g_prof.recs.push_back({a, b, cls});
-    g_prof.last = b;
-  }
+  ~Scope() { g_prof.cur_cls = prev; }
 };
+
+}  // namespace
+
+LaunchEvents prof_launch_events() {
+  LaunchEvents ev;
+  if (!g_prof.on || g_prof.cur_cls < 0) return ev;
+  ev.start = g_prof.get();
+  ev.stop = g_prof.get();
+  if (!ev.start || !ev.stop) {
+    if (ev.start) g_prof.pool.push_back(ev.start);
+    if (ev.stop) g_prof.pool.push_back(ev.stop);
+    return LaunchEvents{};
+  }
+  g_prof.recs.push_back({ev.start, ev.stop, g_prof.cur_cls});
+  return ev;
+}
+
+namespace {
 
 int hip_status() {
   hipError_t e = hipGetLastError();
@@ -208,7 +212,6 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
             const float* L, const float* R, const float* log_emit, float* logZ, hipStream_t st) {
   const int n_max = ly.n_max;
   const int64_t Np = ly.Np, Pp = ly.Pp;
-  prof_begin_call();
   {
     Scope s(st, SPCFG_PROF_SETUP, 4.0 * 2 * (double)ly.N * (ly.N + ly.P) * 3 + 8.0 * ly.S1 * ly.P, 4);
     launch_plan(ly, p, plan.lens, st);
@@ -258,7 +261,6 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
   const int n_max = ly.n_max;
   const int64_t Np = ly.Np, Pp = ly.Pp;
   const int acc = (cfg->flags & SPCFG_FLAG_ACCUMULATE_GRADS) ? 1 : 0;
-  prof_begin_call();
   {
     Scope s(st, SPCFG_PROF_ROOT, 16.0 * ly.N * ly.B, 3);
     launch_root_bwd(ly, p, log_root, grad_logZ, grad_log_root, acc, st);
@@ -468,10 +470,9 @@ int spcfg_profile_read(double* ms, int64_t* launches, double* work) {
   if (!ms || !launches || !work) return SPCFG_ERR_ARG;
   for (int c = 0; c < SPCFG_PROF_CLASSES; ++c) ms[c] = 0.0;
   int rc = SPCFG_OK;
-  if (!g_prof.marks.empty() && hipEventSynchronize(g_prof.marks.back()) != hipSuccess) rc = SPCFG_ERR_HIP;
   for (auto& r : g_prof.recs) {
     float t = 0.0f;
-    if (hipEventElapsedTime(&t, g_prof.marks[r.a], g_prof.marks[r.b]) != hipSuccess) rc = SPCFG_ERR_HIP;
+    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) rc = SPCFG_ERR_HIP;
     ms[r.cls] += t;
   }
   g_prof.recycle();

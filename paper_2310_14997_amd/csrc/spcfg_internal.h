@@ -15,8 +15,12 @@
 // Rows are ordered by width, then sentence, then start position, so each width is one contiguous block.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
+
+#include <tuple>
+#include <utility>
 
 #include "../../include/spcfg.h"
 
@@ -57,6 +61,30 @@ struct Ptrs {  // device pointers resolved from a Layout
 struct LenArg {  // lengths passed by value: no host buffer has to outlive the call
   int32_t v[kMaxB];
 };
+
+// ---- kernel launch ------------------------------------------------------------------------------------
+// While per-kernel-class timing is enabled every launch carries a start and a stop event that are bound to the
+// kernel's own dispatch (hipExtLaunchKernel), so the measured time is the kernel's and nothing is inserted
+// between two kernels; otherwise the events are null and the launch is an ordinary one.
+struct LaunchEvents { hipEvent_t start = nullptr, stop = nullptr; };
+LaunchEvents prof_launch_events();  // a fresh pair charged to the current kernel class, or nulls
+
+template <typename... P, typename... A, size_t... I>
+inline void launch_k_impl(void (*kernel)(P...), dim3 grid, dim3 block, size_t shmem, hipStream_t st,
+                          std::index_sequence<I...>, A&&... args) {
+  std::tuple<P...> vals{static_cast<P>(std::forward<A>(args))...};  // copies with the kernel's parameter types
+  void* ptrs[sizeof...(P) > 0 ? sizeof...(P) : 1] = {static_cast<void*>(&std::get<I>(vals))...};
+  const LaunchEvents ev = prof_launch_events();
+  if (ev.start && ev.stop)
+    (void)hipExtLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, shmem, st, ev.start, ev.stop, 0);
+  else
+    (void)hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, shmem, st);
+}
+template <typename... P, typename... A>
+inline void launch_k(void (*kernel)(P...), dim3 grid, dim3 block, size_t shmem, hipStream_t st, A&&... args) {
+  static_assert(sizeof...(P) == sizeof...(A), "argument count does not match the kernel");
+  launch_k_impl(kernel, grid, block, shmem, st, std::index_sequence_for<P...>{}, std::forward<A>(args)...);
+}
 
 // ---- launchers (each only enqueues on `st`) -------------------------------------------------------
 void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_t st);
