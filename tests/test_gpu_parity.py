@@ -349,3 +349,33 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed():
             assert np.array_equal(got[k], eager[k], equal_nan=True), f"replay {rep}: {k} differs from the eager run"
         other.forward_backward()   # unrelated eager work between replays
         other.results()
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_seeded_random_shapes(seed):
+    """Random small shapes (sizes around the padding and tile boundaries, ragged lengths), shared and per-sentence
+    grammars alternating, against the oracle."""
+    rng = np.random.default_rng(9000 + seed)
+    N = int(rng.choice([1, 2, 7, 31, 32, 33, 63, 64, 65, 96, 129]))
+    P = int(rng.choice([1, 3, 17, 32, 64, 65, 100, 130]))
+    B = int(rng.integers(1, 9))
+    hi = int(rng.choice([3, 6, 12, 33, 47]))
+    lens = rng.integers(2, hi + 1, size=B).tolist()
+    per_sentence = seed % 2 == 1
+    print("case random", seed, dict(N=N, P=P, lens=lens, per_sentence=per_sentence), flush=True)
+    make = synth.make_inputs_per_sentence if per_sentence else synth.make_inputs
+    d = make("tiny", seed=777 + seed, pad_value=np.nan, N=N, P=P, B=B, lengths=lens, V=50)
+    g = rng.uniform(0.25, 2.0, size=B)
+    got, _ = gpu_run(d, grad_logZ=g, fused=bool(seed % 3))
+    if per_sentence:
+        for b in range(B):
+            n = lens[b]
+            lz, gL, gR, gr, ge = O.inside_backward_sentence(d["log_root"][b], d["L"][b], d["R"][b],
+                                                            d["log_emit"][b, :n], float(g[b]))
+            check_logZ(got["logZ"][b:b + 1], np.array([lz]))
+            check_grad(f"grad_L[{b}]", got["grad_L"][b], gL)
+            check_grad(f"grad_R[{b}]", got["grad_R"][b], gR)
+            check_grad(f"grad_log_root[{b}]", got["grad_log_root"][b], gr)
+            check_grad(f"grad_log_emit[{b}]", got["grad_log_emit"][b, :n], ge)
+    else:
+        check_all(got, oracle_run(d, g))
