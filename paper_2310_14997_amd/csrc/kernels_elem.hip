@@ -55,6 +55,14 @@ __device__ __forceinline__ double block_sum_d(double v, double* red) {
   return r;
 }
 
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+// bf16 copy of four consecutive values (round to nearest even): the operand the bf16 projection products read
+__device__ __forceinline__ void store_bf16x4(void* base, int64_t idx, float4 v) {
+  bf16x4_t r;
+  r[0] = (__bf16)v.x; r[1] = (__bf16)v.y; r[2] = (__bf16)v.z; r[3] = (__bf16)v.w;
+  *reinterpret_cast<bf16x4_t*>(static_cast<__bf16*>(base) + idx) = r;
+}
+
 // 2^d as a float for an integer d (0 below the fp32 range); exact.
 __device__ __forceinline__ float pow2i(int d) { return d < -160 ? 0.0f : ldexpf(1.0f, min(d, 127)); }
 
@@ -203,7 +211,7 @@ __global__ void k_transpose_bf16(const float* __restrict__ X, int64_t ldx, const
 __global__ void k_leaf_prep(const float* __restrict__ log_emit, int P, int Pp, int n_max,
                             const int32_t* __restrict__ row_b, const int32_t* __restrict__ row_i,
                             float* __restrict__ leafE, float* __restrict__ xs, int32_t* __restrict__ mexp,
-                            uint32_t* __restrict__ tmaxb) {
+                            uint32_t* __restrict__ tmaxb, __bf16* __restrict__ leafEb) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   const float* e = log_emit + ((int64_t)row_b[r] * n_max + row_i[r]) * P;
@@ -213,7 +221,11 @@ __global__ void k_leaf_prep(const float* __restrict__ log_emit, int P, int Pp, i
   const bool dead = !(mx > -INFINITY);
   const float x = dead ? 0.0f : mx;
   float* out = leafE + (int64_t)r * Pp;
-  for (int t = threadIdx.x; t < Pp; t += blockDim.x) out[t] = (t < P && !dead) ? expf(e[t] - x) : 0.0f;
+  for (int t = threadIdx.x; t < Pp; t += blockDim.x) {
+    const float v = (t < P && !dead) ? expf(e[t] - x) : 0.0f;
+    out[t] = v;
+    if (leafEb) leafEb[(int64_t)r * Pp + t] = (__bf16)v;
+  }
   if (threadIdx.x == 0) {
     xs[r] = x;
     mexp[r] = dead ? kExpZero : 0;
@@ -233,7 +245,7 @@ constexpr int kChunk = 256;  // nonterminals per wavefront (4 per lane)
 __global__ void __launch_bounds__(64)
 k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __restrict__ rowbase,
             const int32_t* __restrict__ row_b, const int32_t* __restrict__ row_i, const float* __restrict__ HZ,
-            float* __restrict__ T, int32_t* __restrict__ mexp, uint32_t* __restrict__ tmaxb) {
+            float* __restrict__ T, int32_t* __restrict__ mexp, uint32_t* __restrict__ tmaxb, void* __restrict__ Tb) {
   extern __shared__ __align__(16) unsigned char smem[];
   float* s_c = reinterpret_cast<float*>(smem);                 // [w-1]
   int32_t* s_l = reinterpret_cast<int32_t*>(s_c + (w - 1));    // [w-1] row of the left child
@@ -302,6 +314,7 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __res
       }
     }
     *reinterpret_cast<float4*>(T + (r - S1) * Np + a) = acc;
+    if (Tb) store_bf16x4(Tb, (r - S1) * Np + a, acc);
     tmax = fmaxf(fmaxf(acc.x, acc.y), fmaxf(acc.z, acc.w));
   }
   tmax = wave_max(tmax);
@@ -354,7 +367,8 @@ __global__ void k_root_bwd(int N, int Np, int64_t S1, const int32_t* __restrict_
                            const float* __restrict__ ztil, const float* __restrict__ rmaxs,
                            const int32_t* __restrict__ mexp, const uint32_t* __restrict__ tmaxb,
                            float* __restrict__ BH, float* __restrict__ UV, int32_t* __restrict__ uexp,
-                           uint32_t* __restrict__ umaxb, float* __restrict__ gsc, int64_t root_stride) {
+                           uint32_t* __restrict__ umaxb, float* __restrict__ gsc, int64_t root_stride,
+                           __bf16* __restrict__ UVb) {
   const int b = blockIdx.x;
   log_root += b * root_stride;
   const int64_t r = rootrow[b];
@@ -369,6 +383,10 @@ __global__ void k_root_bwd(int N, int Np, int64_t S1, const int32_t* __restrict_
     bh[a] = (a < N && !dead) ? s * expf(log_root[a] - rmx) : 0.0f;
     uv[a] = 0.0f;
     uv[Np + a] = 0.0f;
+    if (UVb) {
+      UVb[r * 2 * (int64_t)Np + a] = (__bf16)0.0f;
+      UVb[r * 2 * (int64_t)Np + Np + a] = (__bf16)0.0f;
+    }
   }
   if (threadIdx.x == 0) {
     // consumers read the exponent of BH as uexp + norm_shift(umaxb); 0.5 has shift 0
@@ -418,7 +436,7 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __res
             const int32_t* __restrict__ row_i, const int32_t* __restrict__ rootmask,
             const float* __restrict__ HZ, const float* __restrict__ BH, const int32_t* __restrict__ mexp,
             const uint32_t* __restrict__ tmaxb, float* __restrict__ UV, int32_t* __restrict__ uexp,
-            uint32_t* __restrict__ umaxb, float* __restrict__ gsc) {
+            uint32_t* __restrict__ umaxb, float* __restrict__ gsc, void* __restrict__ UVb) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x;
   const int64_t r = row0 + blockIdx.x;
@@ -506,6 +524,10 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __res
     float* out = UV + r * ld;
     *reinterpret_cast<float4*>(out + a) = u;
     *reinterpret_cast<float4*>(out + Np + a) = v;
+    if (UVb) {
+      store_bf16x4(UVb, r * ld + a, u);
+      store_bf16x4(UVb, r * ld + Np + a, v);
+    }
     amax = fmaxf(fmaxf(fmaxf(fabsf(u.x), fabsf(u.y)), fmaxf(fabsf(u.z), fabsf(u.w))),
                  fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
   }
@@ -617,14 +639,14 @@ void launch_transpose_bf16(const float* X, int64_t ldx, int cols, const float* s
 
 void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hipStream_t st) {
   launch_k(k_leaf_prep, dim3((unsigned)ly.S1), dim3(256), 0, st, log_emit, ly.P, ly.Pp, ly.n_max, p.row_b,
-                     p.row_i, p.leafE, p.xs, p.mexp, p.tmaxb);
+                     p.row_i, p.leafE, p.xs, p.mexp, p.tmaxb, static_cast<__bf16*>(p.leafEb));
 }
 
 void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
   const size_t sh = (size_t)(w - 1) * 12;
   const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
   launch_k(k_split_fwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.rowbase, p.row_b, p.row_i,
-                     p.HZ, p.T, p.mexp, p.tmaxb);
+                     p.HZ, p.T, p.mexp, p.tmaxb, p.Tb);
 }
 
 void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st) {
@@ -637,7 +659,7 @@ void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, con
                      float* grad_log_root, int accumulate, hipStream_t st) {
   launch_k(k_root_bwd, dim3(ly.B), dim3(256), 0, st, ly.N, ly.Np, ly.S1, p.rootrow, log_root, grad_logZ,
                      p.ztil, p.rmax, p.mexp, p.tmaxb, p.BH, p.UV, p.uexp, p.umaxb, p.gsc,
-                     (int64_t)(ly.G > 1 ? ly.N : 0));
+                     (int64_t)(ly.G > 1 ? ly.N : 0), static_cast<__bf16*>(p.UVb));
   launch_k(k_grad_log_root, dim3((ly.N + 255) / 256, ly.G > 1 ? ly.B : 1), dim3(256), 0, st, ly.B, ly.N,
                      ly.Np, ly.S1, p.rootrow, log_root, grad_logZ, p.ztil, p.rmax, p.T, p.tmaxb, grad_log_root,
                      accumulate, ly.G > 1 ? 1 : 0);
@@ -647,7 +669,7 @@ void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int6
   const size_t sh = (size_t)ly.n_max * 12;
   const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
   launch_k(k_split_bwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.lens, p.rowbase, p.row_b,
-                     p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc);
+                     p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc, p.UVb);
 }
 
 void launch_zero_pad_emit(const Layout& ly, const Ptrs& p, float* grad_log_emit, hipStream_t st) {

@@ -77,6 +77,9 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
     ly.Tt = take(2 * (size_t)ly.Np * ly.S2pad);
     ly.UVt_p = take(2 * 2 * (size_t)ly.Np * ly.S1pad);
     ly.Et = take(2 * (size_t)ly.Pp * ly.S1pad);
+    ly.Tb = take(2 * (size_t)S2 * ly.Np);
+    ly.UVb = take(2 * (size_t)ly.Sall * 2 * ly.Np);
+    ly.leafEb = take(2 * (size_t)S1 * ly.Pp);
   }
   ly.leafE = take(f4 * (size_t)S1 * ly.Pp);
   ly.T = take(f4 * (size_t)S2 * ly.Np);
@@ -100,6 +103,7 @@ Ptrs resolve(const Layout& ly, void* ws) {
   p.UV = (float*)(b + ly.UV); p.BH = (float*)(b + ly.BH);
   p.partial = (float*)(b + ly.partial); p.counters = (int32_t*)(b + ly.counters);
   p.sentrows = (int32_t*)(b + ly.sentrows); p.sentoff = (int32_t*)(b + ly.sentoff);
+  p.Tb = ly.bf16 ? b + ly.Tb : nullptr; p.UVb = ly.bf16 ? b + ly.UVb : nullptr; p.leafEb = ly.bf16 ? b + ly.leafEb : nullptr;
   p.UVt_n = b + ly.UVt_n; p.Tt = b + ly.Tt; p.UVt_p = b + ly.UVt_p; p.Et = b + ly.Et;
   p.Wn = (float*)(b + ly.Wn); p.Wp = (float*)(b + ly.Wp); p.Wtn = (float*)(b + ly.Wtn); p.Wtp = (float*)(b + ly.Wtp);
   return p;
@@ -224,6 +228,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     NtArgs a{};
     a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.b_bf16 = ly.bf16;
     a.A = p.leafE; a.lda = Pp; a.Bm = p.Wp; a.ldb = Pp; a.C = p.HZ; a.ldc = 2 * Np;
+    if (ly.bf16) { a.A = p.leafEb; a.a_bf16 = 1; }
     a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
     a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb;
     set_groups(a, plan, ly, p, 1, 0, 2 * Np * Pp);
@@ -241,6 +246,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     NtArgs a{};
     a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.b_bf16 = ly.bf16;
     a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
+    if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.a_bf16 = 1; }
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
     a.rows = (int)rows; a.cols = (int)(2 * Np); a.K = (int)Np;
     a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb + row0;
@@ -282,6 +288,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
     NtArgs a{};
     a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.b_bf16 = ly.bf16;
     a.A = p.UV + row0 * 2 * Np; a.lda = 2 * Np; a.K = (int)(2 * Np); a.rows = (int)rows;
+    if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np; a.a_bf16 = 1; }
     if (w >= 2) {
       Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.N * rows);
       a.Bm = p.Wtn; a.ldb = 2 * Np; a.C = p.BH + (row0 - ly.S1) * Np; a.ldc = Np; a.cols = (int)Np;

@@ -43,6 +43,7 @@ struct Layout {
   size_t lens, rowbase, row_b, row_i, rootmask, rootrow, mexp, uexp, tmaxb, umaxb, gsc, xs, ztil, rmax;
   size_t leafE, T, HZ, UV, BH, Wn, Wp, Wtn, Wtp, partial, counters;
   size_t UVt_n, Tt, UVt_p, Et;  // bf16 mode only
+  size_t Tb, UVb, leafEb;       // bf16 mode only: bf16 copies of T, UV, leafE, written by their producers
   size_t sentrows, sentoff;     // per-sentence grammars only: rows of width >= 2 listed sentence by sentence, first entry of each
   int n_counters;
   size_t total;
@@ -54,6 +55,7 @@ struct Ptrs {  // device pointers resolved from a Layout
   float *gsc, *xs, *ztil, *rmax;
   float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp, *partial;  // W* hold bf16 data in bf16 mode
   void *UVt_n, *Tt, *UVt_p, *Et;
+  void *Tb, *UVb, *leafEb;  // null in fp32 mode
   int32_t* counters;
   int32_t* sentrows; int32_t* sentoff;
 };
@@ -105,8 +107,8 @@ void launch_span_marginals(const Layout& ly, const Ptrs& p, float* mu, int32_t* 
 // C[r][c] = sum_k A[r][k] * Bm[c][k]   (both operands K-contiguous), r < rows, c < cols, K % 32 == 0.
 enum NtEpilogue { NT_EPI_ROWSCALE = 0, NT_EPI_MASKROWS = 1, NT_EPI_LEAF_EMIT = 2, NT_EPI_GRAD = 3 };
 struct NtArgs {
-  // fp32 mode: A, Bm are float.  bf16 mode (b_bf16): Bm points to bf16 data; A is float and rounded to bf16
-  // while it is staged (a_bf16 = 0) or already bf16 (a_bf16 = 1).  lda/ldb count elements; K % 64 == 0 then.
+  // fp32 mode: A, Bm are float.  bf16 mode (a_bf16 = b_bf16 = 1): both point to bf16 data.  lda/ldb count
+  // elements; K % 64 == 0 in bf16 mode.
   const void* A; int64_t lda;
   const void* Bm; int64_t ldb;
   int a_bf16, b_bf16;
