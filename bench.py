@@ -149,8 +149,8 @@ def main():
                          "launches): the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (data-parallel sharding over sentences is described in "
-              "DESIGN.md but not built); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (sharding over sentences with one all-reduce of the rule "
+              "gradients is designed but not built); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -201,8 +201,8 @@ def main():
     logz = wl.logZ.cpu().numpy()
     assert np.all(np.isfinite(logz)), "non-finite log Z in the benchmark batch"
 
-    # per-kernel-class device time: the same steps again, every launch bracketed by HIP events on the launch
-    # stream (kept out of the timed region above because the events perturb the whole-step time by a few %)
+    # per-kernel-class device time: the same steps again, every launch carrying start/stop HIP events bound to
+    # its own dispatch on the launch stream (kept out of the timed region above: the events perturb the schedule)
     bd.spcfg_profile_enable(True)
     psteps = max(args.profile_steps if args.profile_steps is not None else args.steps, 1)
     for _ in range(psteps):
