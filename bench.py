@@ -25,7 +25,7 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 
 
-def cpu_baseline(d, max_sentences, budget_s=30.0):
+def cpu_baseline(d, max_sentences, budget_s=25.0):
     """Time the oracle (as it stands, fp64 numpy) on the first sentences of the batch; bounded by budget_s."""
     from oracle import spcfg_oracle as O
     try:
@@ -132,7 +132,8 @@ def main():
                     help="operand type of the projection GEMMs (default: the workload's own: bf16 for scaled)")
     ap.add_argument("--profile-steps", type=int, default=None,
                     help="steps repeated with HIP events around every kernel launch (default: as many as --steps)")
-    ap.add_argument("--cpu-sentences", type=int, default=12)
+    ap.add_argument("--cpu-sentences", type=int, default=64,
+                    help="sentences of the batch the CPU oracle is timed on (stops after about 25 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--frontend", action="store_true",
                     help="also time the rule-probability front-end (softmaxes + emission gather) and its backward "
