@@ -240,8 +240,12 @@ __global__ void k_leaf_prep(const float* __restrict__ log_emit, int P, int Pp, i
 // LDS, eight split points (16 row loads) are in flight per lane, the per-span maximum that drives the
 // rescaling of Sec. 3.2 is a wavefront reduction followed by one integer atomicMax, and nothing per split
 // point goes to HBM.  The normalisation itself is applied by the projection GEMM's epilogue.
-constexpr int kChunk = 256;  // nonterminals per wavefront (4 per lane)
+// KG = 4 is the shape for launches with few spans and many split points (the late widths), which would leave
+// most of the chip idle: the wavefront covers 64 nonterminals and its four groups of 16 lanes take every fourth
+// split point, so four times as many wavefronts run and each walks a quarter of the split points.
+constexpr int kChunk = 256;  // nonterminals per wavefront (4 per lane) when KG = 1
 
+template <int KG>
 __global__ void __launch_bounds__(64)
 k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __restrict__ rowbase,
             const int32_t* __restrict__ row_b, const int32_t* __restrict__ row_i, const float* __restrict__ HZ,
@@ -272,36 +276,39 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __res
   __syncthreads();
 
   const int64_t ld = 2 * (int64_t)Np;
-  const int a = blockIdx.y * kChunk + lane * 4;
+  constexpr int LG = 64 / KG;          // lanes per split-point group
+  const int kg = lane / LG;            // this lane's group: it takes the split points kg, kg + KG, ...
+  const int a = blockIdx.y * (LG * 4) + (lane % LG) * 4;
   float tmax = 0.0f;
-  if (a < Np) {
+  if (a < Np) {  // always true for KG > 1 (the padded width is a multiple of 64): the shuffles below see every lane
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     const float* hz_l = HZ + a;
     const float* hz_r = HZ + Np + a;
     int k = 0;
-    for (; k + 8 <= w - 1; k += 8) {
+    for (; k + 8 * KG <= w - 1; k += 8 * KG) {
       float4 h[8], z[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        h[u] = *reinterpret_cast<const float4*>(hz_l + s_l[k + u] * ld);
-        z[u] = *reinterpret_cast<const float4*>(hz_r + s_r[k + u] * ld);
+        h[u] = *reinterpret_cast<const float4*>(hz_l + s_l[k + u * KG + kg] * ld);
+        z[u] = *reinterpret_cast<const float4*>(hz_r + s_r[k + u * KG + kg] * ld);
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        const float c = s_c[k + u];
+        const float c = s_c[k + u * KG + kg];
         acc.x = fmaf(c * h[u].x, z[u].x, acc.x);
         acc.y = fmaf(c * h[u].y, z[u].y, acc.y);
         acc.z = fmaf(c * h[u].z, z[u].z, acc.z);
         acc.w = fmaf(c * h[u].w, z[u].w, acc.w);
       }
     }
-    for (; k < w - 1; k += 4) {  // remainder in masked groups of four: no serial chain of dependent loads
+    for (; k < w - 1; k += 4 * KG) {  // remainder in masked groups of four: no serial chain of dependent loads
       float4 h[4], z[4];
       float c[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const int kk = min(k + u, w - 2);
-        c[u] = (k + u < w - 1) ? s_c[kk] : 0.0f;
+        const int idx = k + u * KG + kg;
+        const int kk = min(idx, w - 2);
+        c[u] = (idx < w - 1) ? s_c[kk] : 0.0f;
         h[u] = *reinterpret_cast<const float4*>(hz_l + s_l[kk] * ld);
         z[u] = *reinterpret_cast<const float4*>(hz_r + s_r[kk] * ld);
       }
@@ -313,8 +320,19 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __res
         acc.w = fmaf(c[u] * h[u].w, z[u].w, acc.w);
       }
     }
-    *reinterpret_cast<float4*>(T + (r - S1) * Np + a) = acc;
-    if (Tb) store_bf16x4(Tb, (r - S1) * Np + a, acc);
+    if (KG > 1) {  // sum of the groups' partial sums, in a fixed order
+#pragma unroll
+      for (int o = LG; o < 64; o <<= 1) {
+        acc.x += __shfl_xor(acc.x, o, 64);
+        acc.y += __shfl_xor(acc.y, o, 64);
+        acc.z += __shfl_xor(acc.z, o, 64);
+        acc.w += __shfl_xor(acc.w, o, 64);
+      }
+    }
+    if (kg == 0) {
+      *reinterpret_cast<float4*>(T + (r - S1) * Np + a) = acc;
+      if (Tb) store_bf16x4(Tb, (r - S1) * Np + a, acc);
+    }
     tmax = fmaxf(fmaxf(acc.x, acc.y), fmaxf(acc.z, acc.w));
   }
   tmax = wave_max(tmax);
@@ -644,9 +662,16 @@ void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hi
 
 void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
   const size_t sh = (size_t)(w - 1) * 12;
-  const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
-  launch_k(k_split_fwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.rowbase, p.row_b, p.row_i,
-                     p.HZ, p.T, p.mexp, p.tmaxb, p.Tb);
+  const int chunks = (ly.Np + kChunk - 1) / kChunk;
+  if (rows * chunks < 1024 && w - 1 >= 64) {  // fewer than one wavefront per SIMD, long chains of split points
+    const dim3 grid((unsigned)rows, (unsigned)(ly.Np / 64));
+    launch_k(k_split_fwd<4>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.rowbase, p.row_b, p.row_i, p.HZ,
+             p.T, p.mexp, p.tmaxb, p.Tb);
+    return;
+  }
+  const dim3 grid((unsigned)rows, (unsigned)chunks);
+  launch_k(k_split_fwd<1>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.rowbase, p.row_b, p.row_i, p.HZ,
+           p.T, p.mexp, p.tmaxb, p.Tb);
 }
 
 void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st) {
