@@ -50,7 +50,9 @@ enum {
   /* One grammar per sentence (the dynamic program of the compound variant, App. A: rule probabilities that
      depend on a per-sentence latent vector).  log_root is then [B x N], L and R are [B x N x M], and
      grad_log_root, grad_L, grad_R have the same per-sentence shapes (no sum over the batch).  The projections
-     become grouped products: each sentence's spans meet that sentence's [L;R] panel.  fp32 only. */
+     become grouped products: each sentence's spans meet that sentence's [L;R] panel.  With
+     SPCFG_PRECISION_BF16 the projections round their operands to bf16 as usual; the per-sentence rule
+     gradients are then reduced with fp32 operands. */
   SPCFG_FLAG_PER_SENTENCE_GRAMMAR = 2u
 };
 

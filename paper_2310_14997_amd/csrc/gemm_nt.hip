@@ -28,42 +28,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave % G::WM, wn = wave / G::WM;
   int tiles_m = (g.rows + BM - 1) / BM;
-  if (GROUPED) {
-    // exclusive prefix sum of the row-tile counts over the sentences (four sentences per thread)
-    int c[4], local = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int b = 4 * tid + q;
-      int cnt = 0;
-      if (b < g.ngroups) {
-        cnt = max(0, g.grp_lens[b] - g.grp_w + 1);
-        s_cnt[b] = cnt;
-        s_row0[b] = cnt > 0 ? (int)(g.grp_rowbase[b] - g.grp_row_first) : 0;
-      }
-      c[q] = (cnt + BM - 1) / BM;
-      local += c[q];
-    }
-    int x = local;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int y = __shfl_up(x, o, 64);
-      if (lane >= o) x += y;
-    }
-    if (lane == 63) s_wsum[wave] = x;
-    __syncthreads();
-    int base = 0;
-    for (int i = 0; i < wave; ++i) base += s_wsum[i];
-    int excl = base + x - local;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int b = 4 * tid + q;
-      if (b < g.ngroups) s_tile0[b] = excl;
-      excl += c[q];
-    }
-    tiles_m = s_wsum[0] + s_wsum[1] + s_wsum[2] + s_wsum[3];
-    if (tid == 0) s_tile0[g.ngroups] = tiles_m;
-    __syncthreads();
-  }
+  if (GROUPED) tiles_m = build_group_table<BM>(g, s_tile0, s_row0, s_cnt, s_wsum, tid);
   const int KT = g.K / BK;
   const int lc4 = tid & 7, lr = tid >> 3;  // staging: 8 float4 per tile row, 32 rows per pass
   const int lds_st = lr * LDT + lc4 * 4;
@@ -83,16 +48,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
     int row0 = tile_m * BM, row_end = g.rows;
     const int col0 = tile_n * BN;
     const float* bmat = static_cast<const float*>(g.Bm);
-    if (GROUPED) {
-      int lo = 0, hi = g.ngroups;  // the sentence whose row tiles contain tile_m: s_tile0[lo] <= tile_m < s_tile0[lo + 1]
-      while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (s_tile0[mid] <= tile_m) lo = mid; else hi = mid;
-      }
-      row0 = s_row0[lo] + (tile_m - s_tile0[lo]) * BM;
-      row_end = s_row0[lo] + s_cnt[lo];
-      bmat += (int64_t)lo * g.grp_b_stride;
-    }
+    if (GROUPED) bmat += (int64_t)find_group<BM>(g, s_tile0, s_row0, s_cnt, tile_m, &row0, &row_end) * g.grp_b_stride;
 
     const float* ga[G::QA];
     const float* gb[4];

@@ -14,15 +14,19 @@ using namespace nt;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int BK = 64;  // bf16 values per K-step
 
-template <int EPI, int BM>
+template <int EPI, int BM, bool GROUPED>
 __global__ void __launch_bounds__(256, 2) k_gemm_nt16(NtArgs g, int ipw, int total_iters) {
   using G = Geo<BM>;
   extern __shared__ __align__(16) float lds[];
   __shared__ int s_last;
+  // grouped mode (one grammar per sentence): first row tile, first row and row count of every sentence
+  __shared__ int s_tile0[GROUPED ? kMaxB + 1 : 1], s_row0[GROUPED ? kMaxB : 1], s_cnt[GROUPED ? kMaxB : 1];
+  __shared__ int s_wsum[4];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave % G::WM, wn = wave / G::WM;
-  const int tiles_m = (g.rows + BM - 1) / BM;
+  int tiles_m = (g.rows + BM - 1) / BM;
+  if (GROUPED) tiles_m = build_group_table<BM>(g, s_tile0, s_row0, s_cnt, s_wsum, tid);
   const int KT = g.K / BK;
   // staging of both operands: 8 chunks of 16 bytes (8 bf16) per row and K-step, 32 rows per pass
   const int lc8 = tid & 7, lr8 = tid >> 3;
@@ -40,17 +44,19 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt16(NtArgs g, int ipw, int tot
     const int k0 = it - tile * KT;
     const int k1 = min(KT, k0 + (wg_end - it));
     const int tile_m = tile % tiles_m, tile_n = tile / tiles_m;
-    const int row0 = tile_m * BM, col0 = tile_n * BN;
+    int row0 = tile_m * BM, row_end = g.rows;
+    const int col0 = tile_n * BN;
+    const __bf16* Bh = static_cast<const __bf16*>(g.Bm);
+    if (GROUPED) Bh += (int64_t)find_group<BM>(g, s_tile0, s_row0, s_cnt, tile_m, &row0, &row_end) * g.grp_b_stride;
 
     // element offsets of this thread's chunks (row clamped into range: out-of-range rows are never stored)
     int64_t oa[QA], ob[4];
 #pragma unroll
     for (int q = 0; q < QA; ++q)
-      oa[q] = (int64_t)min(row0 + lr8 + 32 * q, g.rows - 1) * g.lda + lc8 * 8;
+      oa[q] = (int64_t)min(row0 + lr8 + 32 * q, row_end - 1) * g.lda + lc8 * 8;
 #pragma unroll
     for (int q = 0; q < 4; ++q) ob[q] = (int64_t)min(col0 + lr8 + 32 * q, g.cols - 1) * g.ldb + lc8 * 8;
     const __bf16* Ah = static_cast<const __bf16*>(g.A);
-    const __bf16* Bh = static_cast<const __bf16*>(g.Bm);
 
     floatx4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;  // 8 bf16 each; named: arrays would go to scratch
 #define SPCFG_LDA(R, Q, KOFF) \
@@ -126,29 +132,37 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt16(NtArgs g, int ipw, int tot
 #undef SPCFG_STORE_TILE
 
     finish_tile<BM>(g.partial, g.counters, acc, tile, k0, k1, KT, ipw, wg, it, wg_begin, tid, &s_last,
-                    [&](floatx16(&t)[G::MI][G::NI]) { epilogue<EPI, BM>(g, t, row0, col0, wm, wn, lane, g.rows); });
+                    [&](floatx16(&t)[G::MI][G::NI]) { epilogue<EPI, BM>(g, t, row0, col0, wm, wn, lane, row_end); });
     it += k1 - k0;
   }
 }
 
-template <int EPI, int BM>
+template <int EPI, int BM, bool GROUPED>
 void launch(const NtArgs& a, hipStream_t st) {
   using G = Geo<BM>;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt16<EPI, BM>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt16<EPI, BM, GROUPED>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::kLdsBytes);
     attr_set = true;
   }
-  launch_shared(k_gemm_nt16<EPI, BM>, a, BM, BK, G::kLdsBytes, st);
+  launch_shared(k_gemm_nt16<EPI, BM, GROUPED>, a, BM, BK, G::kLdsBytes, st);
 }
 
 template <int EPI>
 void launch_bm(const NtArgs& a, hipStream_t st) {
+  if (a.grouped) {
+    switch (chosen_bm(a)) {
+      case 32: launch<EPI, 32, true>(a, st); break;
+      case 64: launch<EPI, 64, true>(a, st); break;
+      default: launch<EPI, 128, true>(a, st); break;
+    }
+    return;
+  }
   switch (chosen_bm(a)) {
-    case 32: launch<EPI, 32>(a, st); break;
-    case 64: launch<EPI, 64>(a, st); break;
-    default: launch<EPI, 128>(a, st); break;
+    case 32: launch<EPI, 32, false>(a, st); break;
+    case 64: launch<EPI, 64, false>(a, st); break;
+    default: launch<EPI, 128, false>(a, st); break;
   }
 }
 
@@ -157,7 +171,7 @@ void launch_bm(const NtArgs& a, hipStream_t st) {
 void launch_gemm_nt16(const NtArgs& a, hipStream_t st) {
   if (a.rows <= 0 || a.cols <= 0 || !a.a_bf16 || !a.b_bf16) return;  // both operands are bf16 here
   switch (a.epilogue) {
-    case NT_EPI_GRAD: launch<NT_EPI_GRAD, 128>(a, st); break;
+    case NT_EPI_GRAD: launch<NT_EPI_GRAD, 128, false>(a, st); break;
     case NT_EPI_ROWSCALE: launch_bm<NT_EPI_ROWSCALE>(a, st); break;
     case NT_EPI_MASKROWS: launch_bm<NT_EPI_MASKROWS>(a, st); break;
     default: launch_bm<NT_EPI_LEAF_EMIT>(a, st); break;

@@ -112,6 +112,63 @@ __device__ __forceinline__ int renumbered_wg() {
   return xcd * qx + min(xcd, rx) + (blockIdx.x >> 3);
 }
 
+// Grouped mode (one grammar per sentence): table of the sentences' first row tile, first row and row count in
+// LDS, built by every workgroup with one block scan over the lengths (four sentences per thread); returns
+// the number of row tiles of the launch.  s_tile0 has ngroups + 1 entries.
+template <int BM>
+__device__ __forceinline__ int build_group_table(const NtArgs& g, int* s_tile0, int* s_row0, int* s_cnt, int* s_wsum,
+                                                 int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
+  int c[4], local = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int b = 4 * tid + q;
+    int cnt = 0;
+    if (b < g.ngroups) {
+      cnt = max(0, g.grp_lens[b] - g.grp_w + 1);
+      s_cnt[b] = cnt;
+      s_row0[b] = cnt > 0 ? (int)(g.grp_rowbase[b] - g.grp_row_first) : 0;
+    }
+    c[q] = (cnt + BM - 1) / BM;
+    local += c[q];
+  }
+  int x = local;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int y = __shfl_up(x, o, 64);
+    if (lane >= o) x += y;
+  }
+  if (lane == 63) s_wsum[wave] = x;
+  __syncthreads();
+  int base = 0;
+  for (int i = 0; i < wave; ++i) base += s_wsum[i];
+  int excl = base + x - local;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int b = 4 * tid + q;
+    if (b < g.ngroups) s_tile0[b] = excl;
+    excl += c[q];
+  }
+  const int tiles_m = s_wsum[0] + s_wsum[1] + s_wsum[2] + s_wsum[3];
+  if (tid == 0) s_tile0[g.ngroups] = tiles_m;
+  __syncthreads();
+  return tiles_m;
+}
+// The sentence whose row tiles contain tile_m (s_tile0[b] <= tile_m < s_tile0[b + 1]); sets the tile's first row
+// and the end of the sentence's rows.
+template <int BM>
+__device__ __forceinline__ int find_group(const NtArgs& g, const int* s_tile0, const int* s_row0, const int* s_cnt,
+                                          int tile_m, int* row0, int* row_end) {
+  int lo = 0, hi = g.ngroups;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (s_tile0[mid] <= tile_m) lo = mid; else hi = mid;
+  }
+  *row0 = s_row0[lo] + (tile_m - s_tile0[lo]) * BM;
+  *row_end = s_row0[lo] + s_cnt[lo];
+  return lo;
+}
+
 // After the K loop of one tile segment [k0, k1): run the epilogue if the segment is the whole tile, else
 // publish the partial tile, count the arrival, and let the last arriver reduce in fixed order.
 template <int BM, typename Epi>

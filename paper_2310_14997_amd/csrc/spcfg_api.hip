@@ -27,7 +27,6 @@ int check_cfg(const spcfg_config* c) {
   if (c->max_B < 1 || c->max_B > kMaxB || c->max_n < 2 || c->max_n > kMaxLen) return SPCFG_ERR_SHAPE;
   if (c->precision != SPCFG_PRECISION_FP32 && c->precision != SPCFG_PRECISION_BF16) return SPCFG_ERR_UNSUPPORTED;
   if (c->flags & ~(uint32_t)(SPCFG_FLAG_ACCUMULATE_GRADS | SPCFG_FLAG_PER_SENTENCE_GRAMMAR)) return SPCFG_ERR_UNSUPPORTED;
-  if ((c->flags & SPCFG_FLAG_PER_SENTENCE_GRAMMAR) && c->precision != SPCFG_PRECISION_FP32) return SPCFG_ERR_UNSUPPORTED;
   return SPCFG_OK;
 }
 

@@ -106,8 +106,19 @@ def test_per_sentence_marginals_and_decode():
         assert D.tree_score(ref, tree) >= D.mbr_decode(ref, n)[0] - 1e-4 * n
 
 
-def test_per_sentence_mode_rejects_bf16():
-    cfg = bd.make_config(8, 8, 2, 6, precision=bd.PRECISION_BF16, flags=bd.FLAG_PER_SENTENCE_GRAMMAR)
-    with pytest.raises(bd.SpcfgError) as e:
-        bd.spcfg_workspace_bytes(cfg)
-    assert e.value.code == -5
+def test_per_sentence_grammars_with_bf16_operands():
+    """bf16 projections: log Z within 2e-3 absolute, gradients within a relative L2 error of 1e-2 per tensor (the
+    bounds of the shared-grammar bf16 path; unit roundoff of the operands is 2^-9)."""
+    d = synth.make_inputs_per_sentence("tiny", pad_value=np.nan, N=70, P=45, B=5, lengths=[12, 3, 40, 21, 2])
+    print("case per-sentence bf16", flush=True)
+    wl = bd.Workload(d, precision=bd.PRECISION_BF16)
+    wl.forward_backward()
+    got = wl.results()
+    for b in range(d["B"]):
+        n = int(d["lengths"][b])
+        lz, gL, gR, gr, ge = O.inside_backward_sentence(d["log_root"][b], d["L"][b], d["R"][b], d["log_emit"][b, :n])
+        assert abs(got["logZ"][b] - lz) <= 2e-3
+        for name, x, y in (("grad_L", got["grad_L"][b], gL), ("grad_R", got["grad_R"][b], gR),
+                           ("grad_log_root", got["grad_log_root"][b], gr), ("grad_log_emit", got["grad_log_emit"][b, :n], ge)):
+            rel = np.linalg.norm(x - y) / max(np.linalg.norm(y), 1e-300)
+            assert rel <= 1e-2, f"{name}[{b}]: relative L2 error {rel:.3e}"
