@@ -260,6 +260,7 @@ void launch_shared(Kernel kernel, const NtArgs& a, int BM, int BKelems, size_t l
   const int tiles = tiles_m * ((a.cols + BN - 1) / BN);
   const int KT = a.K / BKelems;
   const int total = tiles * KT;
+  if (tiles > a.n_counters) { launch_refused("projection product: more output tiles than arrival counters"); return; }
   int Gn = pick_wgs(a.rows, a.cols, a.K);
   const int cap = a.max_wgs * (128 / BM);  // the partial-tile scratch holds 2 * max_wgs slots of 128 x 128
   if (Gn > cap) Gn = cap;

@@ -237,6 +237,7 @@ void launch_gemm_tn(const TnArgs& a, hipStream_t st) {
     return;
   }
   if (a.S <= 0) return;
+  if (tiles > a.n_counters) { launch_refused("rule-gradient product: more output tiles than arrival counters"); return; }
   const int KT = (int)((a.S + TK - 1) / TK);
   const int64_t total64 = (int64_t)tiles * KT;
   if (total64 >= ((int64_t)1 << 31)) return;  // guarded by the row-count limit of the layout

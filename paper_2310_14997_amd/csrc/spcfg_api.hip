@@ -12,6 +12,7 @@ namespace spcfg {
 namespace {
 
 thread_local char g_hip_err[256] = "";
+thread_local const char* g_refused = nullptr;  // set by a launcher that refused to launch
 
 struct Plan {            // host-side copy of the span schedule
   std::vector<int64_t> off;   // off[w] = first row of width w (1-based), off[n_max+1] = Sall
@@ -56,9 +57,11 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   ly.umaxb = take(i4 * ly.Sall);
   ly.gsc = take(f4 * ly.Sall);
   ly.xs = take(f4 * S1);
-  // the widest launch has at most max(S1, S2) rows (one width) and 2Np columns
-  // (grouped launches round every sentence's rows up to whole row tiles: at most one extra tile per sentence)
-  ly.n_counters = gemm_nt_tiles((int)(S1 > S2 ? S1 : S2) + (per_sentence ? 32 * B : 0), 2 * ly.Np);
+  // One arrival counter per output tile of the largest launch: at most max(S1, S2) rows (one width; grouped
+  // launches round every sentence's rows up to whole row tiles, at most one extra tile per sentence) and
+  // max(2Np, Pp) columns (the projections write 2Np columns, the leaf reverse product P of them).
+  ly.n_counters = gemm_nt_tiles((int)(S1 > S2 ? S1 : S2) + (per_sentence ? 32 * B : 0),
+                                2 * ly.Np > ly.Pp ? 2 * ly.Np : ly.Pp);
   {  // the bf16 rule-gradient product has 2Np rows and up to max(Np, Pp) columns
     const int g = (2 * ly.Np / 128 + 1) * ((ly.Np > ly.Pp ? ly.Np : ly.Pp) / 128 + 1);
     if (g > ly.n_counters) ly.n_counters = g;
@@ -167,6 +170,8 @@ struct Scope {
 
 }  // namespace
 
+void launch_refused(const char* what) { g_refused = what; }
+
 LaunchEvents prof_launch_events() {
   LaunchEvents ev;
   if (!g_prof.on || g_prof.cur_cls < 0) return ev;
@@ -184,6 +189,12 @@ LaunchEvents prof_launch_events() {
 namespace {
 
 int hip_status() {
+  if (g_refused) {
+    snprintf(g_hip_err, sizeof(g_hip_err), "%s", g_refused);
+    g_refused = nullptr;
+    (void)hipGetLastError();
+    return SPCFG_ERR_WORKSPACE;
+  }
   hipError_t e = hipGetLastError();
   if (e == hipSuccess) return SPCFG_OK;
   snprintf(g_hip_err, sizeof(g_hip_err), "%s", hipGetErrorString(e));
@@ -225,7 +236,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
   {  // width 1: [eta | zeta] = [L_P ; R_P] * emission vector
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.P * ly.S1);
     NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.b_bf16 = ly.bf16;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16;
     a.A = p.leafE; a.lda = Pp; a.Bm = p.Wp; a.ldb = Pp; a.C = p.HZ; a.ldc = 2 * Np;
     if (ly.bf16) { a.A = p.leafEb; a.a_bf16 = 1; }
     a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
@@ -243,7 +254,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     if (w == n_max) break;  // every span of the largest width is a root span: never a child, not projected
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.N * rows);
     NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.b_bf16 = ly.bf16;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16;
     a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.a_bf16 = 1; }
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
@@ -285,7 +296,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       launch_split_bwd(ly, p, w, row0, rows, st);
     }
     NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.b_bf16 = ly.bf16;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16;
     a.A = p.UV + row0 * 2 * Np; a.lda = 2 * Np; a.K = (int)(2 * Np); a.rows = (int)rows;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np; a.a_bf16 = 1; }
     if (w >= 2) {
@@ -323,7 +334,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       launch_gemm_tn(t, st);
     } else if (!ly.bf16) {
       TnArgs t{};
-      t.partial = p.partial; t.counters = p.counters; t.max_wgs = kGemmWgs;
+      t.partial = p.partial; t.counters = p.counters; t.max_wgs = kGemmWgs; t.n_counters = ly.n_counters;
       t.Np = (int)Np; t.N = ly.N; t.gL = grad_L; t.gR = grad_R; t.ldg = ly.N + ly.P; t.accumulate = acc;
       t.A = p.UV + ly.S1 * 2 * Np; t.lda = 2 * Np; t.Bm = p.T; t.ldb = Np; t.sc = p.gsc + ly.S1; t.S = ly.S2;
       t.cols = ly.N; t.col0 = 0;
@@ -337,7 +348,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       launch_transpose_bf16(p.UV, 2 * Np, (int)(2 * Np), p.gsc, ly.S1, ly.S1pad, p.UVt_p, st);
       launch_transpose_bf16(p.leafE, Pp, (int)Pp, nullptr, ly.S1, ly.S1pad, p.Et, st);
       NtArgs a{};
-      a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.a_bf16 = 1; a.b_bf16 = 1;
+      a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.a_bf16 = 1; a.b_bf16 = 1;
       a.epilogue = NT_EPI_GRAD; a.gL = grad_L; a.gR = grad_R; a.ldg = ly.N + ly.P; a.Np = (int)Np; a.Nvalid = ly.N;
       a.accumulate = acc; a.rows = (int)(2 * Np);
       a.A = p.UVt_n; a.lda = ly.S2pad; a.Bm = p.Tt; a.ldb = ly.S2pad; a.K = (int)ly.S2pad; a.cols = ly.N; a.col0 = 0;

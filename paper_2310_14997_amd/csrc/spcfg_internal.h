@@ -88,6 +88,10 @@ inline void launch_k(void (*kernel)(P...), dim3 grid, dim3 block, size_t shmem, 
   launch_k_impl(kernel, grid, block, shmem, st, std::index_sequence_for<P...>{}, std::forward<A>(args)...);
 }
 
+// A launcher that finds its launch outside what the workspace was sized for does not launch and reports it here;
+// the API call then returns SPCFG_ERR_WORKSPACE.
+void launch_refused(const char* what);
+
 // ---- launchers (each only enqueues on `st`) -------------------------------------------------------
 void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_t st);
 void launch_plan_sentrows(const Layout& ly, const Ptrs& p, hipStream_t st);
@@ -125,7 +129,8 @@ struct NtArgs {
   float* gL; float* gR; int64_t ldg; int col0, Np, Nvalid, accumulate;
   // work sharing across workgroups: scratch for partial tiles and per-tile arrival counters (zero between launches)
   float* partial; int32_t* counters; int max_wgs;
-  // Grouped mode (one grammar per sentence; fp32 only): the rows of the launch are the spans of one width, sentence
+  int n_counters;  // capacity of `counters`: a launch with more output tiles is refused (see launch_refused)
+  // Grouped mode (one grammar per sentence): the rows of the launch are the spans of one width, sentence
   // after sentence; sentence b owns rows [grp_rowbase[b] - grp_row_first, + max(0, grp_lens[b] - grp_w + 1)) and
   // multiplies them with its own operand Bm + b * grp_b_stride.  Row tiles never straddle two sentences.
   int grouped, ngroups, grp_w;
@@ -151,6 +156,7 @@ struct TnArgs {
   float* gL; float* gR; int64_t ldg; int col0;  // destination column offset (0 or N)
   int accumulate;
   float* partial; int32_t* counters; int max_wgs;  // work sharing scratch, as in NtArgs
+  int n_counters;
   // Grouped mode (one grammar per sentence): sentence b reduces over its own rows only and writes gL / gR + b * grp_gstride;
   // A, Bm, sc are then the whole arrays, indexed by span row.
   //   grp_mode 1: rows rowlist[grp_off[b] + s], s < n_b (n_b - 1) / 2  (spans of width >= 2; the Bm row is row - brow0)

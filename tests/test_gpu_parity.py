@@ -272,6 +272,8 @@ def test_bf16_scaled_full_size_sampled():
     (5, 1, [4, 2]),                    # a single preterminal
     (33, 17, [2, 2, 2, 2]),            # every sentence has the minimum length: width 2 is all root spans
     (40, 24, [3] * 37),                # many short sentences
+    (12, 155, [2] * 10),               # far more preterminals than nonterminals: the leaf reverse product has more
+    (22, 162, [9, 6, 2, 2, 4, 9, 5, 2]),  # column tiles than any projection (regression: arrival counters ran short)
 ])
 def test_degenerate_sizes(N, P, lens):
     d = synth.make_inputs("tiny", seed=900 + N + len(lens), pad_value=np.nan, N=N, P=P, B=len(lens), lengths=lens, V=50)

@@ -42,6 +42,8 @@ def check_against_oracle(d, got, grad_logZ=None, sentences=None):
     dict(N=70, P=45, B=7, lengths=[2, 3, 9, 17, 5, 2, 12]),          # sizes that are no multiples of the padding
     dict(N=40, P=24, B=4, lengths=[40, 33, 2, 65]),                  # sentences spanning two row tiles; 64-row tiles
     dict(N=20, P=12, B=3, lengths=[70, 140, 9]),                     # 128-row tiles for the longest sentence
+    dict(N=12, P=155, B=10, lengths=[2] * 10),                       # P > 2N, one row tile per sentence (regression:
+    dict(N=47, P=135, B=3, lengths=[5, 4, 2]),                       # arrival counters ran short for the leaf product)
 ])
 def test_per_sentence_grammars_match_oracle(kw):
     d = synth.make_inputs_per_sentence("tiny", pad_value=np.nan, **kw)
