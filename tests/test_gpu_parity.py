@@ -381,3 +381,45 @@ def test_seeded_random_shapes(seed):
             check_grad(f"grad_log_emit[{b}]", got["grad_log_emit"][b, :n], ge)
     else:
         check_all(got, oracle_run(d, g))
+
+
+def test_maximum_length_sentence_against_closed_form():
+    """One sentence of 1024 words (the length limit; 1023 widths, half a million spans) with a uniform grammar:
+    L = R = 1/M, root = 1/N, every emission weight c gives Z = C_{n-1} N^{n-2} P^n c^n / M^{2(n-1)} (C = Catalan
+    number), and by symmetry uniform root and preterminal posteriors."""
+    import math
+    n, N, P, c = 1024, 4, 7, 0.3
+    M = N + P
+    d = dict(name="uniform", B=1, N=N, P=P, n_max=n, lengths=np.array([n], dtype=np.int32),
+             log_root=np.full(N, -math.log(N), dtype=np.float32), L=np.full((N, M), 1.0 / M, dtype=np.float32),
+             R=np.full((N, M), 1.0 / M, dtype=np.float32), log_emit=np.full((1, n, P), math.log(c), dtype=np.float32))
+    print("case n=1024 closed form", flush=True)
+    got, _ = gpu_run(d, fused=True)
+    log_catalan = math.lgamma(2 * (n - 1) + 1) - 2 * math.lgamma(n) - math.log(n)
+    expect = log_catalan - 2 * (n - 1) * math.log(M) + (n - 2) * math.log(N) + n * math.log(P * c)
+    assert got["logZ"][0] == pytest.approx(expect, rel=1e-5)
+    assert np.allclose(got["grad_log_root"], 1.0 / N, rtol=1e-3)
+    assert np.allclose(got["grad_log_emit"][0], 1.0 / P, rtol=1e-3)
+    # expected rule counts: n - 1 binary rules per tree, through the left and through the right factor
+    assert (d["L"] * got["grad_L"]).sum() == pytest.approx(n - 1, rel=1e-3)
+    assert (d["R"] * got["grad_R"]).sum() == pytest.approx(n - 1, rel=1e-3)
+
+
+@pytest.mark.parametrize("per_sentence", [False, True])
+def test_maximum_batch_size(per_sentence):
+    """960 sentences (the batch limit: the lengths travel as one kernel argument)."""
+    rng = np.random.default_rng(960)
+    lens = rng.integers(2, 6, size=960).tolist()
+    make = synth.make_inputs_per_sentence if per_sentence else synth.make_inputs
+    d = make("tiny", seed=960, pad_value=np.nan, N=5, P=6, B=960, lengths=lens, V=30)
+    print("case B=960", per_sentence, flush=True)
+    got, _ = gpu_run(d)
+    if not per_sentence:
+        check_all(got, oracle_run(d))
+        return
+    for b in range(0, 960, 37):
+        n = lens[b]
+        lz, gL, gR, gr, ge = O.inside_backward_sentence(d["log_root"][b], d["L"][b], d["R"][b], d["log_emit"][b, :n])
+        check_logZ(got["logZ"][b:b + 1], np.array([lz]))
+        check_grad(f"grad_L[{b}]", got["grad_L"][b], gL)
+        check_grad(f"grad_log_emit[{b}]", got["grad_log_emit"][b, :n], ge)
