@@ -99,3 +99,16 @@ def test_decode_argument_checks_run_before_any_launch():
     cfg = bd.make_config(8, 8, 2, 6)
     assert lib.spcfg_span_marginals(C.byref(cfg), lens.ctypes.data, 2, 6, fake, 1 << 30, None, None, None) == -1
     assert lib.spcfg_span_marginals(C.byref(cfg), lens.ctypes.data, 2, 6, C.c_void_p(4096), 16, fake, None, None) == -4
+
+
+def test_header_is_valid_c99_and_cpp():
+    """The boundary is a C ABI: the header must compile as plain C (and as C++) on its own."""
+    import subprocess
+    import tempfile
+    hdr = os.path.join(ROOT, "include", "spcfg.h")
+    with tempfile.TemporaryDirectory() as tmp:
+        src = os.path.join(tmp, "t.c")
+        with open(src, "w") as f:
+            f.write(f'#include "{hdr}"\nint main(void) {{ spcfg_config c; c.struct_size = sizeof c; return (int)c.struct_size == 0; }}\n')
+        subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only", src])
+        subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Werror", "-x", "c++", "-fsyntax-only", src])
