@@ -9,6 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspcfg.so")
+CLIENT = os.path.join(HERE, "abi_client.bin")  # plain C program that uses the library through its C ABI only
 SOURCES = ["spcfg_api.hip", "kernels_elem.hip", "gemm_nt.hip", "gemm_nt16.hip", "gemm_tn.hip", "rules_frontend.hip", "decode.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
          # packed fp32 ops are kept off for all device code on the test machines
@@ -27,6 +28,14 @@ def build(verbose=True):
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+    # the C client: compiled as C (host only), linked against the library and the HIP runtime
+    rocm = os.path.dirname(os.path.dirname(find_hipcc()))
+    cc = ["gcc", "-std=c99", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+          os.path.join(CSRC, "abi_client.c"), "-o", CLIENT, "-L", HERE, "-lspcfg", "-L", os.path.join(rocm, "lib"),
+          "-lamdhip64", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cc), flush=True)
+    subprocess.check_call(cc)
     return LIB
 
 
