@@ -18,6 +18,17 @@ constexpr int TM = 128, TN = 128, TK = 32;
 constexpr int kStageT = (TM + TN) * TK + TK;  // A tile, B tile, scales
 constexpr size_t kLdsBytesT = 2 * kStageT * sizeof(float);
 
+// 16 bytes per lane straight from global memory into LDS (lane l lands at lds_base + 16 l; the LDS base is
+// uniform over the wavefront).  The builtin exists in the device pass only.
+__device__ __forceinline__ void dma16(const float* gptr, float* lds_base) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  typedef __attribute__((address_space(3))) float lds_float;
+  __builtin_amdgcn_global_load_lds(gptr, (lds_float*)lds_base, 16, 0, 0);
+#else
+  (void)gptr; (void)lds_base;
+#endif
+}
+
 // MODE 0: one reduction over the contiguous rows [0, S).  MODE 1, 2: one reduction per sentence (grouped mode of
 // TnArgs); every workgroup share is a whole number of output tiles, so no partial tiles are exchanged.
 template <int MODE>
@@ -62,41 +73,26 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
   const bool bcol_ok = (b0 + lc4 * 4) < (int)g.ldb;  // ldb is the padded column count of X
   const float* gA = g.A + a0 + lc4 * 4;
   const float* gB = g.Bm + (bcol_ok ? b0 + lc4 * 4 : 0);
-  // staging registers as named scalars (arrays end up in scratch memory next to the scheduling barriers)
-  floatx4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;
+  // Tiles go straight from global memory into LDS (16 bytes per lane, lane l of a wavefront lands at base +
+  // 16 l): thread (lr, lc4) moves columns 4 lc4 .. +3 of tile row lr + 8 q, and a wavefront's two rows are
+  // contiguous in the [row][128] LDS tile.  Rows past the end are read from the last valid row (always in
+  // bounds, finite) and contribute nothing because their scale is staged as 0; columns past the padded width
+  // of X are read from column 0 and only feed output columns that the epilogue drops.
   float rsc = 0.0f;
-  const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
-  // rows past the end are read from the last valid row (always in bounds) and replaced by zeros when the
-  // registers are stored to LDS (not earlier: a select right after the load would wait for the load)
-#define SPCFG_TN_LOAD1(RA, RB, Q, S0)                                              \
-  {                                                                                \
-    const int64_t s = (S0) + lr + 8 * (Q);                                         \
-    const bool ok = s < S;                                                         \
-    const int64_t sc = ok ? s : S - 1;                                             \
-    const int64_t sr = MODE == 1 ? (int64_t)rl[sc] : rbase + sc;                   \
-    RA = *reinterpret_cast<const floatx4*>(gA + sr * g.lda);                        \
-    RB = *reinterpret_cast<const floatx4*>(gB + (MODE == 1 ? sr - g.brow0 : sr) * g.ldb); \
+  const int uw = __builtin_amdgcn_readfirstlane(wave);
+#define SPCFG_TN_DMA1(Q, BUF, S0)                                                                        \
+  {                                                                                                      \
+    const int64_t s = (S0) + lr + 8 * (Q);                                                               \
+    const int64_t sc = s < S ? s : S - 1;                                                                \
+    const int64_t sr = MODE == 1 ? (int64_t)rl[sc] : rbase + sc;                                         \
+    dma16(gA + sr * g.lda, lds + (BUF)*kStageT + (8 * (Q) + 2 * uw) * TM);                               \
+    dma16(gB + (MODE == 1 ? sr - g.brow0 : sr) * g.ldb, lds + (BUF)*kStageT + TM * TK + (8 * (Q) + 2 * uw) * TN); \
   }
-#define SPCFG_TN_LOAD(S0)                                                          \
-  SPCFG_TN_LOAD1(ra0, rb0, 0, S0) SPCFG_TN_LOAD1(ra1, rb1, 1, S0)                  \
-  SPCFG_TN_LOAD1(ra2, rb2, 2, S0) SPCFG_TN_LOAD1(ra3, rb3, 3, S0)                  \
+#define SPCFG_TN_DMA(BUF, S0)                                                                            \
+  SPCFG_TN_DMA1(0, BUF, S0) SPCFG_TN_DMA1(1, BUF, S0) SPCFG_TN_DMA1(2, BUF, S0) SPCFG_TN_DMA1(3, BUF, S0) \
   if (tid < TK) rsc = ((S0) + tid < S) ? g.sc[MODE == 1 ? (int64_t)rl[(S0) + tid] : rbase + (S0) + tid] : 0.0f;
-#define SPCFG_TN_STORE(BUF, S0)                                                    \
-  {                                                                                \
-    float* as_ = lds + (BUF)*kStageT + lr * TM + lc4 * 4;                          \
-    float* bs_ = lds + (BUF)*kStageT + TM * TK + lr * TN + lc4 * 4;                \
-    const bool k0_ = (S0) + lr < S, k1_ = (S0) + lr + 8 < S;                       \
-    const bool k2_ = (S0) + lr + 16 < S, k3_ = (S0) + lr + 24 < S;                 \
-    *reinterpret_cast<floatx4*>(as_) = k0_ ? ra0 : zero4;                           \
-    *reinterpret_cast<floatx4*>(as_ + 8 * TM) = k1_ ? ra1 : zero4;                  \
-    *reinterpret_cast<floatx4*>(as_ + 16 * TM) = k2_ ? ra2 : zero4;                 \
-    *reinterpret_cast<floatx4*>(as_ + 24 * TM) = k3_ ? ra3 : zero4;                 \
-    *reinterpret_cast<floatx4*>(bs_) = (k0_ && bcol_ok) ? rb0 : zero4;              \
-    *reinterpret_cast<floatx4*>(bs_ + 8 * TN) = (k1_ && bcol_ok) ? rb1 : zero4;     \
-    *reinterpret_cast<floatx4*>(bs_ + 16 * TN) = (k2_ && bcol_ok) ? rb2 : zero4;    \
-    *reinterpret_cast<floatx4*>(bs_ + 24 * TN) = (k3_ && bcol_ok) ? rb3 : zero4;    \
-    if (tid < TK) lds[(BUF)*kStageT + (TM + TN) * TK + tid] = rsc;                 \
-  }
+#define SPCFG_TN_STORE_SC(BUF) \
+  if (tid < TK) lds[(BUF)*kStageT + (TM + TN) * TK + tid] = rsc;
 
   floatx16 acc[2][2];
 #pragma unroll
@@ -106,8 +102,9 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
-  SPCFG_TN_LOAD((int64_t)k0 * TK)
-  SPCFG_TN_STORE(0, (int64_t)k0 * TK)
+  SPCFG_TN_DMA(0, (int64_t)k0 * TK)
+  SPCFG_TN_STORE_SC(0)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
   const int fcol = lane & 31, fk = lane >> 5;
@@ -142,8 +139,8 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
   for (int kt = k0; kt < k1; ++kt) {
     const int buf = (kt - k0) & 1;
     const int64_t sn = (int64_t)(kt + 1 < k1 ? kt + 1 : kt) * TK;  // the last step re-reads itself (never used)
-    SPCFG_TN_LOAD(sn)
-    __builtin_amdgcn_sched_barrier(0);  // keep the prefetch loads at the top of the step
+    SPCFG_TN_DMA(buf ^ 1, sn)  // the other stage: everybody left it at the last barrier
+    __builtin_amdgcn_sched_barrier(0);  // keep the loads at the top of the step
     const float* as = lds + buf * kStageT + wm * 64 + fcol;
     const float* bs = lds + buf * kStageT + TM * TK + wn * 64 + fcol;
     const float* ss = lds + buf * kStageT + (TM + TN) * TK;
@@ -156,8 +153,8 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
       SPCFG_TN_FRAGS(x, as, bs, ss, kk + 4)
       SPCFG_TN_MFMA(y)
       __builtin_amdgcn_sched_barrier(0);
-      if (kk == 20) {  // LDS stores of the prefetched tile, behind three quarters of the MFMA work
-        SPCFG_TN_STORE(buf ^ 1, sn)
+      if (kk == 20) {  // the next step's scales, behind three quarters of the MFMA work
+        SPCFG_TN_STORE_SC(buf ^ 1)
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -166,6 +163,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
     SPCFG_TN_FRAGS(y, as, bs, ss, TK - 2)
     SPCFG_TN_MFMA(x)
     __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my part of the next tile has landed in LDS
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
     {
@@ -180,9 +178,9 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
   __syncthreads();  // all operands fetched before the LDS tiles are reused by the next tile segment
 #undef SPCFG_TN_FRAGS
 #undef SPCFG_TN_MFMA
-#undef SPCFG_TN_LOAD
-#undef SPCFG_TN_LOAD1
-#undef SPCFG_TN_STORE
+#undef SPCFG_TN_DMA
+#undef SPCFG_TN_DMA1
+#undef SPCFG_TN_STORE_SC
 
   nt::finish_tile<128>(g.partial, g.counters, acc, tile, k0, k1, KTg, ipw, wg, it, wg_begin, tid, &s_last,
                        [&](floatx16(&t)[2][2]) {
