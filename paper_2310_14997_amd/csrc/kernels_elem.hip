@@ -80,11 +80,27 @@ __device__ __forceinline__ float norm_scale(uint32_t maxbits) {
 }
 
 // ------------------------------------------------------------------------------------------ span plan
-// Width-synchronous schedule (Sec. 3.2, span-level parallelism): rows are ordered by width, sentence, start.
-__global__ void k_plan_rowbase(LenArg la, int B, int n_max, int32_t* __restrict__ lens,
-                               int32_t* __restrict__ rowbase, int32_t* __restrict__ rootrow,
+// Width-synchronous schedule (Sec. 3.2, span-level parallelism): rows are ordered by width.  Within a width the
+// order is: the prefix spans (i = 0) of all sentences, then the other spans that do not end the sentence
+// (sentence by sentence, by start), then the suffix spans (j = n, i > 0).  A prefix span is never a right
+// child and a suffix span never a left child, so the first two blocks are exactly the rows whose left projection
+// (eta) is used and the last two blocks those whose right projection (zeta) is used: each is one contiguous row
+// range for the projection products.  Width 1, and every width when each sentence has its own grammar, keep the
+// plain (sentence, start) order; the three tables then describe that order.
+//   rowtab[0 * stride + w * B + b]  row of span (0, w) of sentence b (-1 if the sentence is shorter)
+//   rowtab[1 * stride + w * B + b]  row of span (1, 1 + w) (the spans 1 .. n-w-1 follow each other)
+//   rowtab[2 * stride + w * B + b]  row of span (n - w, n)
+__device__ __forceinline__ int row_of(const int32_t* __restrict__ rowtab, int stride, int B, int w, int b, int i,
+                                      int n) {
+  const int which = i == 0 ? 0 : (i == n - w ? 2 : 1);
+  return rowtab[which * stride + w * B + b] + (which == 1 ? i - 1 : 0);
+}
+
+__global__ void k_plan_rowbase(LenArg la, int B, int n_max, int by_sentence, int32_t* __restrict__ lens,
+                               int32_t* __restrict__ rowtab, int32_t* __restrict__ rootrow,
                                int32_t* __restrict__ counters, int n_counters) {
   __shared__ int s_w[kMaxLen + 2];
+  const int stride = (n_max + 1) * B;
   for (int t = threadIdx.x; t < n_counters; t += blockDim.x) counters[t] = 0;  // GEMM arrival counters
   for (int b = threadIdx.x; b < B; b += blockDim.x) lens[b] = la.v[b];
   for (int w = 1 + threadIdx.x; w <= n_max; w += blockDim.x) {
@@ -103,37 +119,65 @@ __global__ void k_plan_rowbase(LenArg la, int B, int n_max, int32_t* __restrict_
   }
   __syncthreads();
   for (int w = 1 + threadIdx.x; w <= n_max; w += blockDim.x) {
-    int run = s_w[w];
-    for (int b = 0; b < B; ++b) {
-      const int n = la.v[b];
-      rowbase[w * B + b] = (n >= w) ? run : -1;
-      if (n == w) rootrow[b] = run;
-      run += max(0, n - w + 1);
+    const int base = s_w[w];
+    int* tp = rowtab + w * B;
+    int* tm = rowtab + stride + w * B;
+    int* ts = rowtab + 2 * stride + w * B;
+    if (by_sentence || w == 1) {
+      int run = base;
+      for (int b = 0; b < B; ++b) {
+        const int cnt = la.v[b] - w + 1;
+        tp[b] = cnt > 0 ? run : -1;
+        tm[b] = cnt > 0 ? run + 1 : -1;
+        ts[b] = cnt > 0 ? run + cnt - 1 : -1;
+        if (cnt == 1) rootrow[b] = run;
+        run += max(0, cnt);
+      }
+    } else {
+      int n_pre = 0, n_mid = 0;
+      for (int b = 0; b < B; ++b) {
+        const int cnt = la.v[b] - w + 1;
+        n_pre += cnt > 0 ? 1 : 0;
+        n_mid += max(0, cnt - 2);
+      }
+      int rp = base, rm = base + n_pre, rs = base + n_pre + n_mid;
+      for (int b = 0; b < B; ++b) {
+        const int cnt = la.v[b] - w + 1;
+        if (cnt <= 0) { tp[b] = tm[b] = ts[b] = -1; continue; }
+        tp[b] = rp;
+        tm[b] = rm;
+        ts[b] = cnt >= 2 ? rs : rp;  // a span that is the whole sentence is both: it sits in the prefix block
+        if (cnt == 1) rootrow[b] = rp;
+        rp += 1;
+        rm += max(0, cnt - 2);
+        rs += cnt >= 2 ? 1 : 0;
+      }
     }
   }
 }
 
-__global__ void k_plan_rows(int B, const int32_t* __restrict__ lens, const int32_t* __restrict__ rowbase,
+__global__ void k_plan_rows(int B, int stride, const int32_t* __restrict__ lens, const int32_t* __restrict__ rowtab,
                             int32_t* __restrict__ row_b, int32_t* __restrict__ row_i,
                             int32_t* __restrict__ rootmask, uint32_t* __restrict__ tmaxb,
                             uint32_t* __restrict__ umaxb) {
   const int w = blockIdx.x + 1, b = blockIdx.y;
   const int n = lens[b];
   if (w > n) return;
-  const int base = rowbase[w * B + b];
   for (int i = threadIdx.x; i <= n - w; i += blockDim.x) {
-    row_b[base + i] = b;
-    row_i[base + i] = i;
-    rootmask[base + i] = (w == n) ? 1 : 0;
-    tmaxb[base + i] = 0u;
-    umaxb[base + i] = 0u;
+    const int r = row_of(rowtab, stride, B, w, b, i, n);
+    row_b[r] = b;
+    row_i[r] = i;
+    rootmask[r] = (w == n) ? 1 : 0;
+    tmaxb[r] = 0u;
+    umaxb[r] = 0u;
   }
 }
 
 // Rows of width >= 2 listed sentence by sentence (width, then start): the reduction order of the per-sentence
 // rule gradients.  Sentence b owns entries [sum_{b'<b} n_b'(n_b'-1)/2, + n_b(n_b-1)/2).
-__global__ void k_plan_sentrows(int B, const int32_t* __restrict__ lens, const int32_t* __restrict__ rowbase,
-                                int32_t* __restrict__ sentrows, int32_t* __restrict__ sentoff) {
+__global__ void k_plan_sentrows(int B, int stride, const int32_t* __restrict__ lens,
+                                const int32_t* __restrict__ rowtab, int32_t* __restrict__ sentrows,
+                                int32_t* __restrict__ sentoff) {
   const int w = blockIdx.x + 2, b = blockIdx.y;
   const int n = lens[b];
   if (w > n) return;
@@ -142,8 +186,7 @@ __global__ void k_plan_sentrows(int B, const int32_t* __restrict__ lens, const i
   if (w == 2 && threadIdx.x == 0) sentoff[b] = (int32_t)off;
   // spans of widths 2..w-1 of this sentence: sum_{v=2}^{w-1} (n - v + 1)
   off += (int64_t)(w - 2) * (n + 1) - ((int64_t)w * (w - 1) / 2 - 1);
-  const int base = rowbase[w * B + b];
-  for (int i = threadIdx.x; i <= n - w; i += blockDim.x) sentrows[off + i] = base + i;
+  for (int i = threadIdx.x; i <= n - w; i += blockDim.x) sentrows[off + i] = row_of(rowtab, stride, B, w, b, i, n);
 }
 
 // ------------------------------------------------------------------------------------------ weights
@@ -247,8 +290,9 @@ constexpr int kChunk = 256;  // nonterminals per wavefront (4 per lane) when KG 
 
 template <int KG>
 __global__ void __launch_bounds__(64)
-k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __restrict__ rowbase,
-            const int32_t* __restrict__ row_b, const int32_t* __restrict__ row_i, const float* __restrict__ HZ,
+k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const int32_t* __restrict__ lens,
+            const int32_t* __restrict__ rowtab, const int32_t* __restrict__ row_b,
+            const int32_t* __restrict__ row_i, const float* __restrict__ HZ,
             float* __restrict__ T, int32_t* __restrict__ mexp, uint32_t* __restrict__ tmaxb, void* __restrict__ Tb) {
   extern __shared__ __align__(16) unsigned char smem[];
   float* s_c = reinterpret_cast<float*>(smem);                 // [w-1]
@@ -257,10 +301,11 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __res
   const int lane = threadIdx.x;
   const int64_t r = row0 + blockIdx.x;
   const int b = row_b[r], i = row_i[r];
+  const int n = lens[b];
   int dmax = kExpZero;
   for (int k = 1 + lane; k < w; k += 64) {
-    const int lr = rowbase[k * B + b] + i;            // span (i, i+k)
-    const int rr = rowbase[(w - k) * B + b] + i + k;  // span (i+k, i+w)
+    const int lr = row_of(rowtab, stride, B, k, b, i, n);          // span (i, i+k)
+    const int rr = row_of(rowtab, stride, B, w - k, b, i + k, n);  // span (i+k, i+w)
     s_l[k - 1] = lr;
     s_r[k - 1] = rr;
     const int d = add_exp(norm_exp(mexp[lr], tmaxb[lr]), norm_exp(mexp[rr], tmaxb[rr]));
@@ -367,7 +412,7 @@ __global__ void k_root_fwd(int B, int N, int Np, int64_t S1, const int32_t* __re
   z = block_sum_d(z, redd);
   double sx = 0.0;
   const int n = lens[b];
-  const int leaf0 = rowbase[1 * B + b];
+  const int leaf0 = rowbase[1 * B + b];  // width 1 keeps the (sentence, start) order
   for (int i = threadIdx.x; i < n; i += blockDim.x) sx += (double)xs[leaf0 + i];
   sx = block_sum_d(sx, redd);
   if (threadIdx.x == 0) {
@@ -449,8 +494,8 @@ __global__ void k_grad_log_root(int B, int N, int Np, int64_t S1, const int32_t*
 // as in the forward pass one wavefront handles (span, 256 nonterminals) and the normalisation by the
 // largest magnitude is left to the GEMM epilogue.
 __global__ void __launch_bounds__(64)
-k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __restrict__ lens,
-            const int32_t* __restrict__ rowbase, const int32_t* __restrict__ row_b,
+k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const int32_t* __restrict__ lens,
+            const int32_t* __restrict__ rowtab, const int32_t* __restrict__ row_b,
             const int32_t* __restrict__ row_i, const int32_t* __restrict__ rootmask,
             const float* __restrict__ HZ, const float* __restrict__ BH, const int32_t* __restrict__ mexp,
             const uint32_t* __restrict__ tmaxb, float* __restrict__ UV, int32_t* __restrict__ uexp,
@@ -474,12 +519,12 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, const int32_t* __res
     int pr, sr;
     if (t < nl) {
       const int jp = j + 1 + t;
-      pr = rowbase[(jp - i) * B + b] + i;   // parent (i, j')
-      sr = rowbase[(jp - j) * B + b] + j;   // sibling (j, j'), used through its zeta
+      pr = row_of(rowtab, stride, B, jp - i, b, i, n);   // parent (i, j')
+      sr = row_of(rowtab, stride, B, jp - j, b, j, n);   // sibling (j, j'), used through its zeta
     } else {
       const int ip = t - nl;
-      pr = rowbase[(j - ip) * B + b] + ip;  // parent (i', j)
-      sr = rowbase[(i - ip) * B + b] + ip;  // sibling (i', i), used through its eta
+      pr = row_of(rowtab, stride, B, j - ip, b, ip, n);  // parent (i', j)
+      sr = row_of(rowtab, stride, B, i - ip, b, ip, n);  // sibling (i', i), used through its eta
     }
     s_p[t] = pr - (int)S1;
     s_s[t] = sr;
@@ -578,7 +623,7 @@ __global__ void k_zero_pad_emit(int P, int n_max, const int32_t* __restrict__ le
 // root span (both are in every tree), so they read the root row.  label = first arg-max nonterminal.
 __global__ void __launch_bounds__(64)
 k_span_marginals(int B, int N, int Np, int n_max, int64_t S1, const int32_t* __restrict__ lens,
-                 const int32_t* __restrict__ rowbase, const float* __restrict__ T, const float* __restrict__ BH,
+                 const int32_t* __restrict__ rowtab, const float* __restrict__ T, const float* __restrict__ BH,
                  const int32_t* __restrict__ mexp, const int32_t* __restrict__ uexp,
                  const uint32_t* __restrict__ umaxb, float* __restrict__ mu, int32_t* __restrict__ label) {
   const int lane = threadIdx.x;
@@ -594,7 +639,8 @@ k_span_marginals(int B, int N, int Np, int n_max, int64_t S1, const int32_t* __r
     return;
   }
   const int w = j - i;
-  const int64_t r = (w == 1) ? rowbase[n * B + b] : rowbase[w * B + b] + i;
+  const int stride = (n_max + 1) * B;
+  const int64_t r = (w == 1) ? rowtab[n * B + b] : row_of(rowtab, stride, B, w, b, i, n);
   const float* t = T + (r - S1) * Np;
   const float* h = BH + (r - S1) * Np;
   float sum = 0.0f, best = 0.0f;
@@ -627,15 +673,16 @@ k_span_marginals(int B, int N, int Np, int n_max, int64_t S1, const int32_t* __r
 }  // namespace
 
 void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_t st) {
-  launch_k(k_plan_rowbase, dim3(1), dim3(256), 0, st, lens, ly.B, ly.n_max, p.lens, p.rowbase, p.rootrow,
+  launch_k(k_plan_rowbase, dim3(1), dim3(256), 0, st, lens, ly.B, ly.n_max, ly.G > 1 ? 1 : 0, p.lens, p.rowbase,
+           p.rootrow,
                      p.counters, ly.n_counters);
-  launch_k(k_plan_rows, dim3(ly.n_max, ly.B), dim3(64), 0, st, ly.B, p.lens, p.rowbase, p.row_b, p.row_i,
+  launch_k(k_plan_rows, dim3(ly.n_max, ly.B), dim3(64), 0, st, ly.B, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b, p.row_i,
                      p.rootmask, p.tmaxb, p.umaxb);
 }
 
 void launch_plan_sentrows(const Layout& ly, const Ptrs& p, hipStream_t st) {
   if (ly.n_max < 2) return;
-  launch_k(k_plan_sentrows, dim3(ly.n_max - 1, ly.B), dim3(64), 0, st, ly.B, p.lens, p.rowbase, p.sentrows,
+  launch_k(k_plan_sentrows, dim3(ly.n_max - 1, ly.B), dim3(64), 0, st, ly.B, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.sentrows,
                      p.sentoff);
 }
 
@@ -665,12 +712,12 @@ void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int6
   const int chunks = (ly.Np + kChunk - 1) / kChunk;
   if (rows * chunks < 1024 && w - 1 >= 64) {  // fewer than one wavefront per SIMD, long chains of split points
     const dim3 grid((unsigned)rows, (unsigned)(ly.Np / 64));
-    launch_k(k_split_fwd<4>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.rowbase, p.row_b, p.row_i, p.HZ,
+    launch_k(k_split_fwd<4>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b, p.row_i, p.HZ,
              p.T, p.mexp, p.tmaxb, p.Tb);
     return;
   }
   const dim3 grid((unsigned)rows, (unsigned)chunks);
-  launch_k(k_split_fwd<1>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.rowbase, p.row_b, p.row_i, p.HZ,
+  launch_k(k_split_fwd<1>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b, p.row_i, p.HZ,
            p.T, p.mexp, p.tmaxb, p.Tb);
 }
 
@@ -693,7 +740,7 @@ void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, con
 void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
   const size_t sh = (size_t)ly.n_max * 12;
   const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
-  launch_k(k_split_bwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, p.lens, p.rowbase, p.row_b,
+  launch_k(k_split_bwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b,
                      p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc, p.UVb);
 }
 

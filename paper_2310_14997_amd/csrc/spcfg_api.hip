@@ -44,7 +44,7 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   const size_t i4 = sizeof(int32_t), f4 = sizeof(float);
   ly.lens = take(i4 * B);
-  ly.rowbase = take(i4 * (size_t)(n_max + 1) * B);
+  ly.rowbase = take(i4 * 3 * (size_t)(n_max + 1) * B);  // three tables, see the span plan kernel
   ly.rootrow = take(i4 * B);
   ly.ztil = take(f4 * B);
   ly.rmax = take(f4 * B);
