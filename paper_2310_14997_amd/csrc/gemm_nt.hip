@@ -16,8 +16,11 @@ namespace {
 using namespace nt;
 constexpr int BK = 32;
 
-template <int EPI, int BM, bool GROUPED>
+// MODE 0: one product; 1: grouped (one grammar per sentence); 2: parts (several row ranges with their own
+// column block and K range in one launch, see NtArgs).
+template <int EPI, int BM, int MODE>
 __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total_iters) {
+  constexpr bool GROUPED = MODE == 1, PARTS = MODE == 2;
   using G = Geo<BM>;
   extern __shared__ __align__(16) float lds[];
   __shared__ int s_last;
@@ -41,20 +44,49 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
   const int wg_end = min(wg_begin + ipw, total_iters);
   int it = wg_begin;
   while (it < wg_end) {
-    const int tile = it / KT;
-    const int k0 = it - tile * KT;
-    const int k1 = min(KT, k0 + (wg_end - it));
-    const int tile_m = tile % tiles_m, tile_n = tile / tiles_m;
-    int row0 = tile_m * BM, row_end = g.rows;
+    int tile, ustart, KTt = KT, k0, tile_m, tile_n, row0, row_end = g.rows, c_shift = 0, kbeg = 0;
+    if (PARTS) {
+      // which part does unit `it` belong to?  (at most three parts; each is tiles * K-steps units long)
+      const int tiles_n = (g.cols + BN - 1) / BN;
+      int p = 0, ubase = 0, tbase = 0;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        if (p == q && q + 1 < g.parts) {
+          const int tq = ((g.prt_rows[q] + BM - 1) / BM) * tiles_n;
+          if (it >= ubase + tq * g.prt_kt[q]) { ubase += tq * g.prt_kt[q]; tbase += tq; p = q + 1; }
+        }
+      }
+      const int tm = (g.prt_rows[p] + BM - 1) / BM;
+      KTt = g.prt_kt[p];
+      const int u = it - ubase;
+      const int tl = u / KTt;
+      k0 = u - tl * KTt;
+      tile = tbase + tl;
+      ustart = ubase + tl * KTt;
+      tile_m = tl % tm; tile_n = tl / tm;
+      row0 = g.prt_row0[p] + tile_m * BM;
+      row_end = g.prt_row0[p] + g.prt_rows[p];
+      c_shift = g.prt_c0[p];
+      kbeg = g.prt_kbeg[p];
+    } else {
+      tile = it / KT;
+      k0 = it - tile * KT;
+      ustart = tile * KT;
+      tile_m = tile % tiles_m; tile_n = tile / tiles_m;
+      row0 = tile_m * BM;
+    }
+    const int k1 = min(KTt, k0 + (wg_end - it));
     const int col0 = tile_n * BN;
-    const float* bmat = static_cast<const float*>(g.Bm);
+    // parts: the part's column block of Bm (rows of the K-contiguous panel) and its K range
+    const float* bmat = static_cast<const float*>(g.Bm) + (int64_t)c_shift * g.ldb + (int64_t)kbeg * BK;
+    const float* amat = static_cast<const float*>(g.A) + (int64_t)kbeg * BK;
     if (GROUPED) bmat += (int64_t)find_group<BM>(g, s_tile0, s_row0, s_cnt, tile_m, &row0, &row_end) * g.grp_b_stride;
 
     const float* ga[G::QA];
     const float* gb[4];
 #pragma unroll
     for (int q = 0; q < G::QA; ++q)
-      ga[q] = static_cast<const float*>(g.A) + (int64_t)min(row0 + lr + 32 * q, row_end - 1) * g.lda + lc4 * 4;
+      ga[q] = amat + (int64_t)min(row0 + lr + 32 * q, row_end - 1) * g.lda + lc4 * 4;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
       gb[q] = bmat + (int64_t)min(col0 + lr + 32 * q, g.cols - 1) * g.ldb + lc4 * 4;
@@ -140,38 +172,48 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
 #undef SPCFG_MFMA1
 #undef SPCFG_MFMA4
 
-    finish_tile<BM>(g.partial, g.counters, acc, tile, k0, k1, KT, ipw, wg, it, wg_begin, tid, &s_last,
-                    [&](floatx16(&t)[G::MI][G::NI]) { epilogue<EPI, BM>(g, t, row0, col0, wm, wn, lane, row_end); });
+    finish_tile<BM>(g.partial, g.counters, acc, tile, ustart, k0, k1, KTt, ipw, wg, it, wg_begin, tid, &s_last,
+                    [&](floatx16(&t)[G::MI][G::NI]) {
+                      epilogue<EPI, BM>(g, t, row0, col0, wm, wn, lane, row_end, c_shift);
+                    });
     it += k1 - k0;
   }
 }
 
-template <int EPI, int BM, bool GROUPED>
+template <int EPI, int BM, int MODE>
 void launch(const NtArgs& a, hipStream_t st) {
   using G = Geo<BM>;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI, BM, GROUPED>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI, BM, MODE>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::kLdsBytes);
     attr_set = true;
   }
-  launch_shared(k_gemm_nt<EPI, BM, GROUPED>, a, BM, BK, G::kLdsBytes, st);
+  launch_shared(k_gemm_nt<EPI, BM, MODE>, a, BM, BK, G::kLdsBytes, st);
 }
 
 template <int EPI>
 void launch_bm(const NtArgs& a, hipStream_t st) {
   if (a.grouped) {
     switch (chosen_bm(a)) {
-      case 32: launch<EPI, 32, true>(a, st); break;
-      case 64: launch<EPI, 64, true>(a, st); break;
-      default: launch<EPI, 128, true>(a, st); break;
+      case 32: launch<EPI, 32, 1>(a, st); break;
+      case 64: launch<EPI, 64, 1>(a, st); break;
+      default: launch<EPI, 128, 1>(a, st); break;
+    }
+    return;
+  }
+  if (a.parts > 0) {
+    switch (chosen_bm(a)) {
+      case 32: launch<EPI, 32, 2>(a, st); break;
+      case 64: launch<EPI, 64, 2>(a, st); break;
+      default: launch<EPI, 128, 2>(a, st); break;
     }
     return;
   }
   switch (chosen_bm(a)) {
-    case 32: launch<EPI, 32, false>(a, st); break;
-    case 64: launch<EPI, 64, false>(a, st); break;
-    default: launch<EPI, 128, false>(a, st); break;
+    case 32: launch<EPI, 32, 0>(a, st); break;
+    case 64: launch<EPI, 64, 0>(a, st); break;
+    default: launch<EPI, 128, 0>(a, st); break;
   }
 }
 

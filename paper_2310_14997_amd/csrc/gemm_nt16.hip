@@ -131,7 +131,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt16(NtArgs g, int ipw, int tot
 #undef SPCFG_STA
 #undef SPCFG_STORE_TILE
 
-    finish_tile<BM>(g.partial, g.counters, acc, tile, k0, k1, KT, ipw, wg, it, wg_begin, tid, &s_last,
+    finish_tile<BM>(g.partial, g.counters, acc, tile, tile * KT, k0, k1, KT, ipw, wg, it, wg_begin, tid, &s_last,
                     [&](floatx16(&t)[G::MI][G::NI]) { epilogue<EPI, BM>(g, t, row0, col0, wm, wn, lane, row_end); });
     it += k1 - k0;
   }

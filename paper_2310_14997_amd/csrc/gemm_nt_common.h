@@ -53,7 +53,7 @@ template <int BM> struct Geo {
 
 template <int EPI, int BM>
 __device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[Geo<BM>::MI][Geo<BM>::NI], int row0, int col0,
-                                         int wm, int wn, int lane, int row_end) {
+                                         int wm, int wn, int lane, int row_end, int c_shift = 0) {
   using G = Geo<BM>;
   // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
 #pragma unroll
@@ -97,7 +97,7 @@ __device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[Geo<BM
         if (c >= g.cols) continue;
         float val = acc[mi][ni][v] * scale;
         if (EPI == NT_EPI_LEAF_EMIT) val *= g.E[(int64_t)r * g.lde + c];
-        g.C[drow * g.ldc + c] = val;
+        g.C[drow * g.ldc + c + c_shift] = val;  // c_shift: column block of this part of the launch
       }
     }
   }
@@ -173,16 +173,17 @@ __device__ __forceinline__ int find_group(const NtArgs& g, const int* s_tile0, c
 // publish the partial tile, count the arrival, and let the last arriver reduce in fixed order.
 template <int BM, typename Epi>
 __device__ __forceinline__ void finish_tile(float* partial, int32_t* counters, floatx16 (&acc)[Geo<BM>::MI][Geo<BM>::NI],
-                                            int tile, int k0, int k1, int KT, int ipw, int wg, int it, int wg_begin,
-                                            int tid, int* s_last_ptr, Epi&& run_epilogue) {
+                                            int tile, int ustart, int k0, int k1, int KT, int ipw, int wg, int it,
+                                            int wg_begin, int tid, int* s_last_ptr, Epi&& run_epilogue) {
   using G = Geo<BM>;
   int& s_last = *s_last_ptr;
   if (k0 == 0 && k1 == KT) {
     run_epilogue(acc);
   } else {
     // partial tile: publish, count arrivals, last arriver reduces in fixed order
-    const int first_g = (tile * KT) / ipw;
-    const int last_g = (tile * KT + KT - 1) / ipw;
+    // ustart = index of the tile's first K-step in the launch's unit space; shares are ipw units long
+    const int first_g = ustart / ipw;
+    const int last_g = (ustart + KT - 1) / ipw;
     const int parts = last_g - first_g + 1;
     float* slot = partial + (size_t)(2 * wg + (it != wg_begin ? 1 : 0)) * G::kSlotFloats;
 #pragma unroll
@@ -200,7 +201,7 @@ __device__ __forceinline__ void finish_tile(float* partial, int32_t* counters, f
     __syncthreads();
     if (s_last) {
       // one 32x32 accumulator tile at a time (8 loads in flight per lane), parts in ascending order
-      const int odd0 = (tile * KT != first_g * ipw) ? 1 : 0;
+      const int odd0 = (ustart != first_g * ipw) ? 1 : 0;
 #pragma unroll
       for (int mi = 0; mi < G::MI; ++mi)
 #pragma unroll
@@ -241,14 +242,18 @@ __device__ __forceinline__ void finish_tile(float* partial, int32_t* counters, f
 // of work relative to the machine, so the thresholds are in multiply-accumulates (rows * cols * K).  Small
 // launches want short tiles (finer shares, less padding) and one workgroup per CU; large ones tall tiles
 // (less LDS and L2 traffic per flop) and two workgroups per CU.
-inline int pick_bm(int rows, int cols, int K) {
-  const double work = (double)rows * cols * K;
+inline double work_of(const NtArgs& a) {
+  if (a.parts == 0) return (double)(a.grouped ? a.grp_max_rows : a.rows) * a.cols * a.K;
+  double w = 0;
+  for (int p = 0; p < a.parts; ++p) w += (double)a.prt_rows[p] * a.cols * a.prt_kt[p] * 32;
+  return w;
+}
+inline int pick_bm(int rows, double work) {
   if (rows <= 32 || work <= 2.7e9) return 32;
   if (rows <= 64 || work <= 7.6e9) return 64;
   return 128;
 }
-inline int pick_wgs(int rows, int cols, int K) {
-  const double work = (double)rows * cols * K;
+inline int pick_wgs(double work) {
   return work <= 8e7 ? 128 : (work <= 1.25e9 ? 256 : 512);
 }
 
@@ -257,11 +262,20 @@ inline int pick_wgs(int rows, int cols, int K) {
 template <typename Kernel>
 void launch_shared(Kernel kernel, const NtArgs& a, int BM, int BKelems, size_t lds_bytes, hipStream_t st) {
   const int tiles_m = a.grouped ? a.grp_tiles_m[BM == 32 ? 0 : (BM == 64 ? 1 : 2)] : (a.rows + BM - 1) / BM;
-  const int tiles = tiles_m * ((a.cols + BN - 1) / BN);
+  int tiles = tiles_m * ((a.cols + BN - 1) / BN);
   const int KT = a.K / BKelems;
-  const int total = tiles * KT;
+  int total = tiles * KT;
+  if (a.parts > 0) {  // several products in one launch: each part has its own rows and K range
+    tiles = 0; total = 0;
+    for (int p = 0; p < a.parts; ++p) {
+      const int tp = ((a.prt_rows[p] + BM - 1) / BM) * ((a.cols + BN - 1) / BN);
+      tiles += tp;
+      total += tp * a.prt_kt[p];
+    }
+    if (total == 0) return;
+  }
   if (tiles > a.n_counters) { launch_refused("projection product: more output tiles than arrival counters"); return; }
-  int Gn = pick_wgs(a.rows, a.cols, a.K);
+  int Gn = pick_wgs(a.parts ? work_of(a) : (double)a.rows * a.cols * a.K);
   const int cap = a.max_wgs * (128 / BM);  // the partial-tile scratch holds 2 * max_wgs slots of 128 x 128
   if (Gn > cap) Gn = cap;
   if (Gn > total / 2) Gn = total / 2 > 0 ? total / 2 : 1;  // at least two K-steps per share
@@ -276,7 +290,7 @@ void launch_shared(Kernel kernel, const NtArgs& a, int BM, int BKelems, size_t l
 }
 
 inline int chosen_bm(const NtArgs& a) {
-  int bm = pick_bm(a.grouped ? a.grp_max_rows : a.rows, a.cols, a.K);
+  int bm = pick_bm(a.grouped ? a.grp_max_rows : a.rows, work_of(a));
 #ifdef SPCFG_TUNING
   if (getenv("SPCFG_NT_BM")) bm = atoi(getenv("SPCFG_NT_BM"));
 #endif

@@ -182,7 +182,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
 #undef SPCFG_TN_DMA1
 #undef SPCFG_TN_STORE_SC
 
-  nt::finish_tile<128>(g.partial, g.counters, acc, tile, k0, k1, KTg, ipw, wg, it, wg_begin, tid, &s_last,
+  nt::finish_tile<128>(g.partial, g.counters, acc, tile, tile * KT, k0, k1, KTg, ipw, wg, it, wg_begin, tid, &s_last,
                        [&](floatx16(&t)[2][2]) {
     // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
 #pragma unroll

@@ -59,8 +59,9 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   ly.xs = take(f4 * S1);
   // One arrival counter per output tile of the largest launch: at most max(S1, S2) rows (one width; grouped
   // launches round every sentence's rows up to whole row tiles, at most one extra tile per sentence) and
-  // max(2Np, Pp) columns (the projections write 2Np columns, the leaf reverse product P of them).
-  ly.n_counters = gemm_nt_tiles((int)(S1 > S2 ? S1 : S2) + (per_sentence ? 32 * B : 0),
+  // max(2Np, Pp) columns (the projections write 2Np columns, the leaf reverse product P of them).  A launch cut
+  // into up to three row ranges rounds each of them up to whole row tiles: two extra tiles of 32 rows.
+  ly.n_counters = gemm_nt_tiles((int)(S1 > S2 ? S1 : S2) + (per_sentence ? 32 * B : 64),
                                 2 * ly.Np > ly.Pp ? 2 * ly.Np : ly.Pp);
   {  // the bf16 rule-gradient product has 2Np rows and up to max(Np, Pp) columns
     const int g = (2 * ly.Np / 128 + 1) * ((ly.Np > ly.Pp ? ly.Np : ly.Pp) / 128 + 1);
@@ -207,6 +208,26 @@ int check_ws(const Layout& ly, void* ws, size_t bytes) {
   return SPCFG_OK;
 }
 
+// Shared grammar, fp32, width >= 2: the rows of a width are ordered [prefix spans | middle spans | suffix spans]
+// (a span that is both, i.e. a root, counts as prefix).  A prefix span is never a right child and a suffix span
+// never a left child, so one of their two projections (forward) resp. one half of their adjoint (reverse, it
+// is zero) takes no part: the launch is cut into parts that leave those products out.
+struct WidthBlocks { int nP, nM, nS; };
+WidthBlocks width_blocks(const Plan& plan, const Layout& ly, int w) {
+  WidthBlocks k{0, 0, 0};
+  for (int b = 0; b < ly.B; ++b) {
+    const int cnt = plan.lens.v[b] - w + 1;
+    if (cnt >= 1) ++k.nP;
+    if (cnt >= 2) ++k.nS;
+    if (cnt >= 3) k.nM += cnt - 2;
+  }
+  return k;
+}
+bool use_parts(const Layout& ly, int w) { return ly.G == 1 && !ly.bf16 && w >= 2; }
+void set_part(NtArgs& a, int i, int row0, int rows, int c0, int kbeg, int kt) {
+  a.prt_row0[i] = row0; a.prt_rows[i] = rows; a.prt_c0[i] = c0; a.prt_kbeg[i] = kbeg; a.prt_kt[i] = kt;
+}
+
 // One grammar per sentence: the launch for width w multiplies each sentence's rows with that sentence's panel.
 void set_groups(NtArgs& a, const Plan& plan, const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t b_stride) {
   if (ly.G == 1) return;
@@ -260,6 +281,15 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
     a.rows = (int)rows; a.cols = (int)(2 * Np); a.K = (int)Np;
     a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb + row0;
+    // eta for the prefix and middle rows, zeta for the middle and suffix rows (when Np is not a whole number of
+    // 128-column tiles the two column blocks would each pad their last tile: one product of 2Np columns then)
+    if (use_parts(ly, w) && Np % 128 == 0) {
+      const WidthBlocks k = width_blocks(plan, ly, w);
+      const int kt = (int)(Np / 32);
+      a.parts = 2; a.cols = (int)Np;
+      set_part(a, 0, 0, k.nP + k.nM, 0, 0, kt);
+      set_part(a, 1, k.nP, k.nM + k.nS, (int)Np, 0, kt);
+    }
     set_groups(a, plan, ly, p, w, row0, 2 * Np * Np);
     launch_gemm_nt(a, st);
   }
@@ -303,6 +333,14 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.N * rows);
       a.Bm = p.Wtn; a.ldb = 2 * Np; a.C = p.BH + (row0 - ly.S1) * Np; a.ldc = Np; a.cols = (int)Np;
       a.epilogue = NT_EPI_MASKROWS; a.rowmask = p.rootmask + row0; a.rowmaxb = p.umaxb + row0;
+      if (use_parts(ly, w)) {  // prefix rows: only the eta adjoint (first half of K); suffix rows: only zeta's
+        const WidthBlocks k = width_blocks(plan, ly, w);
+        const int kt = (int)(Np / 32);
+        a.parts = 3;
+        set_part(a, 0, 0, k.nP, 0, 0, kt);
+        set_part(a, 1, k.nP, k.nM, 0, 0, 2 * kt);
+        set_part(a, 2, k.nP + k.nM, k.nS, 0, kt, kt);
+      }
       set_groups(a, plan, ly, p, w, row0, 2 * Np * Np);
       launch_gemm_nt(a, st);
     } else {

@@ -137,6 +137,14 @@ struct NtArgs {
   const int32_t* grp_lens; const int32_t* grp_rowbase; int64_t grp_row_first; int64_t grp_b_stride;
   int grp_tiles_m[3];  // host: number of row tiles for tile heights 32, 64, 128
   int grp_max_rows;    // host: largest row count of one sentence
+  // Parts mode (fp32, shared grammar, width >= 2): `parts` products in one launch.  Part p multiplies the rows
+  // [prt_row0[p], + prt_rows[p]) with the columns [prt_c0[p], + cols) of Bm / C over the K-steps
+  // [prt_kbeg[p], + prt_kt[p]) (steps of 32 values).  The span plan puts the prefix spans first and the suffix
+  // spans last within a width, so "rows whose eta is used", "rows whose zeta is used" (forward: two parts, one
+  // column block each) and "prefix / middle / suffix rows" (reverse: the adjoint of zeta resp. eta is zero, half
+  // of K is skipped) are contiguous ranges.
+  int parts;
+  int prt_row0[3], prt_rows[3], prt_c0[3], prt_kbeg[3], prt_kt[3];
 };
 void launch_gemm_nt(const NtArgs& a, hipStream_t st);
 void launch_gemm_nt16(const NtArgs& a, hipStream_t st);  // bf16-operand variant (called through launch_gemm_nt)

@@ -274,6 +274,12 @@ def test_bf16_scaled_full_size_sampled():
     (40, 24, [3] * 37),                # many short sentences
     (12, 155, [2] * 10),               # far more preterminals than nonterminals: the leaf reverse product has more
     (22, 162, [9, 6, 2, 2, 4, 9, 5, 2]),  # column tiles than any projection (regression: arrival counters ran short)
+    # prefix / middle / suffix row blocks of a width, projected as separate parts of one launch: blocks with no
+    # middle spans, with only prefix spans, with more than one row tile per block; N padded to one and to one and
+    # a half column tiles (the second keeps the forward product in one piece)
+    (128, 40, [2, 3, 3, 4, 2, 5, 3] * 11),
+    (150, 40, [4, 3, 5, 3, 2, 4] * 9),
+    (64, 30, [3, 3, 3, 4] * 40),
 ])
 def test_degenerate_sizes(N, P, lens):
     d = synth.make_inputs("tiny", seed=900 + N + len(lens), pad_value=np.nan, N=N, P=P, B=len(lens), lengths=lens, V=50)
