@@ -140,6 +140,8 @@ def main():
                          "at the workload's shape; reported under \"frontend\", not part of the step")
     ap.add_argument("--per-sentence", action="store_true",
                     help="one grammar per sentence (grouped projection products) at the workload's shape")
+    ap.add_argument("--fp32-mfma", action="store_true",
+                    help="fp32 matrix instructions instead of the split-bf16 products (SPCFG_FLAG_FP32_MFMA)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step into a HIP graph once and time its replays instead of eager launches")
     ap.add_argument("--decode", action="store_true",
@@ -171,7 +173,8 @@ def main():
     d = synth.make_inputs_per_sentence(args.workload) if args.per_sentence else synth.make_inputs(args.workload)
     precision = args.precision or d["precision"]
     bf16 = precision == "bf16"
-    wl = bd.Workload(d, precision=bd.PRECISION_BF16 if bf16 else bd.PRECISION_FP32)
+    wl = bd.Workload(d, precision=bd.PRECISION_BF16 if bf16 else bd.PRECISION_FP32,
+                     flags=bd.FLAG_FP32_MFMA if args.fp32_mfma else 0)
     peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_FP32_MFMA_TFLOPS
     wc = synth.work_counts(d["lengths"], d["N"], d["P"])
     stream = torch.cuda.current_stream()

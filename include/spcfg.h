@@ -53,7 +53,12 @@ enum {
      become grouped products: each sentence's spans meet that sentence's [L;R] panel.  With
      SPCFG_PRECISION_BF16 the projections round their operands to bf16 as usual; the per-sentence rule
      gradients are then reduced with fp32 operands. */
-  SPCFG_FLAG_PER_SENTENCE_GRAMMAR = 2u
+  SPCFG_FLAG_PER_SENTENCE_GRAMMAR = 2u,
+  /* SPCFG_PRECISION_FP32 forms its matrix products from bf16 matrix instructions by default: every fp32
+     operand is cut exactly into three bf16 pieces and six piece products are accumulated in fp32, which keeps
+     the accuracy of an fp32 product (the dropped terms are below 2^-23 of it) at a fraction of the cost of
+     fp32 matrix instructions.  This flag selects fp32 matrix instructions instead. */
+  SPCFG_FLAG_FP32_MFMA = 4u
 };
 
 /* Plain-old-data configuration; set struct_size = sizeof(spcfg_config). */

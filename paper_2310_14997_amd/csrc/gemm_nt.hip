@@ -18,7 +18,8 @@ constexpr int BK = 32;
 
 // MODE 0: one product; 1: grouped (one grammar per sentence); 2: parts (several row ranges with their own
 // column block and K range in one launch, see NtArgs).
-template <int EPI, int BM, int MODE>
+// X3: fp32 products from bf16 matrix instructions (Split3) instead of fp32 ones.
+template <int EPI, int BM, int MODE, bool X3>
 __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total_iters) {
   constexpr bool GROUPED = MODE == 1, PARTS = MODE == 2;
   using G = Geo<BM>;
@@ -136,6 +137,54 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
 #define SPCFG_MFMA4(A0, A1, B0, B1) \
   SPCFG_MFMA1(A0, A1, B0, B1, x) SPCFG_MFMA1(A0, A1, B0, B1, y) SPCFG_MFMA1(A0, A1, B0, B1, z) SPCFG_MFMA1(A0, A1, B0, B1, w)
 
+    if constexpr (X3) {
+    // fp32 product from bf16 matrix instructions: every operand is cut into three bf16 pieces (8 + 8 + 8
+    // significant bits, by truncation, so hi + mid + lo is the fp32 value exactly) and the six largest of the
+    // nine piece products are accumulated in fp32; the three dropped ones are below 2^-23 of the product.
+    // One 32x32x16 instruction takes 8 K values per lane: the two 4-value reads of chunks 2c and 2c + 1.
+    float4 pa0, pa1, pb0, pb1;  // chunk 0 of the current K-step, fetched one step ahead (behind the barrier)
+    float4 qa0, qa1, qb0, qb1, ra_0, ra_1, rb_0, rb_1, sa0, sa1, sb0, sb1;  // chunks 1, 2, 3
+    SPCFG_FRAGS(pa0, pa1, pb0, pb1, lds + a_off, lds + b_off, 0)
+#define SPCFG_SPLIT(P, U, V) Split3 P; P.cut(U, V);
+#define SPCFG_MFMA_T(X, Y)                                                                                    \
+  acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A0.X(), B0.Y(), acc[0][0], 0, 0, 0);                      \
+  if (G::NI > 1) acc[0][G::NI - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A0.X(), B1.Y(), acc[0][G::NI - 1], 0, 0, 0); \
+  if (G::MI > 1) acc[G::MI - 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1.X(), B0.Y(), acc[G::MI - 1][0], 0, 0, 0); \
+  if (G::MI > 1 && G::NI > 1)                                                                                  \
+    acc[G::MI - 1][G::NI - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1.X(), B1.Y(), acc[G::MI - 1][G::NI - 1], 0, 0, 0);
+#define SPCFG_GROUP(UA0, UA1, UB0, UB1, VA0, VA1, VB0, VB1)                                    \
+  {                                                                                            \
+    SPCFG_SPLIT(A0, UA0, VA0) SPCFG_SPLIT(B0, UB0, VB0)                                        \
+    Split3 A1, B1;                                                                             \
+    if (G::MI > 1) A1.cut(UA1, VA1);                                                           \
+    if (G::NI > 1) B1.cut(UB1, VB1);                                                           \
+    SPCFG_MFMA_T(l, h) SPCFG_MFMA_T(h, l) SPCFG_MFMA_T(m, m) SPCFG_MFMA_T(m, h) SPCFG_MFMA_T(h, m) SPCFG_MFMA_T(h, h) \
+  }
+
+    for (int kt = k0; kt < k1; ++kt) {
+      const int buf = (kt - k0) & 1;
+      const int kn = min(kt + 1, k1 - 1) * BK;
+      SPCFG_LOAD_TILE(kn)
+      __builtin_amdgcn_sched_barrier(0);
+      const float* as = lds + buf * G::kStage + a_off;
+      const float* bs = lds + buf * G::kStage + b_off;
+      SPCFG_FRAGS(qa0, qa1, qb0, qb1, as, bs, 1)
+      SPCFG_FRAGS(ra_0, ra_1, rb_0, rb_1, as, bs, 2)
+      SPCFG_FRAGS(sa0, sa1, sb0, sb1, as, bs, 3)
+      SPCFG_GROUP(pa0, pa1, pb0, pb1, qa0, qa1, qb0, qb1)
+      __builtin_amdgcn_sched_barrier(0);
+      SPCFG_STORE_TILE(lds + (buf ^ 1) * G::kStage + lds_st)
+      __builtin_amdgcn_sched_barrier(0);
+      __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+      SPCFG_FRAGS(pa0, pa1, pb0, pb1, lds + (buf ^ 1) * G::kStage + a_off, lds + (buf ^ 1) * G::kStage + b_off, 0)
+      __builtin_amdgcn_sched_barrier(0);
+      SPCFG_GROUP(ra_0, ra_1, rb_0, rb_1, sa0, sa1, sb0, sb1)
+    }
+#undef SPCFG_SPLIT
+#undef SPCFG_MFMA_T
+#undef SPCFG_GROUP
+    } else {
     float4 pa0, pa1, pb0, pb1;  // chunk 0 of the current K-step, fetched one step ahead (behind the barrier)
     float4 qa0, qa1, qb0, qb1;  // chunks 1..3
     SPCFG_FRAGS(pa0, pa1, pb0, pb1, lds + a_off, lds + b_off, 0)
@@ -167,6 +216,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
       __builtin_amdgcn_sched_barrier(0);
       SPCFG_MFMA4(qa0, qa1, qb0, qb1)
     }
+    }
     __syncthreads();  // every wavefront has fetched its last operands before the LDS tiles are reused
 #undef SPCFG_FRAGS
 #undef SPCFG_MFMA1
@@ -180,16 +230,21 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
   }
 }
 
-template <int EPI, int BM, int MODE>
-void launch(const NtArgs& a, hipStream_t st) {
+template <int EPI, int BM, int MODE, bool X3>
+void launch_x(const NtArgs& a, hipStream_t st) {
   using G = Geo<BM>;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI, BM, MODE>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI, BM, MODE, X3>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::kLdsBytes);
     attr_set = true;
   }
-  launch_shared(k_gemm_nt<EPI, BM, MODE>, a, BM, BK, G::kLdsBytes, st);
+  launch_shared(k_gemm_nt<EPI, BM, MODE, X3>, a, BM, BK, G::kLdsBytes, st);
+}
+
+template <int EPI, int BM, int MODE>
+void launch(const NtArgs& a, hipStream_t st) {
+  if (a.fp32_mfma) launch_x<EPI, BM, MODE, false>(a, st); else launch_x<EPI, BM, MODE, true>(a, st);
 }
 
 template <int EPI>

@@ -11,7 +11,6 @@ namespace spcfg {
 namespace {
 
 using namespace nt;
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int BK = 64;  // bf16 values per K-step
 
 template <int EPI, int BM, bool GROUPED>

@@ -33,6 +33,40 @@ __device__ __forceinline__ F2 ld_agent(const float* p) {
                                                   __HIP_MEMORY_SCOPE_AGENT));
 }
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+// fp32 products from bf16 matrix instructions (the bf16 rate of the matrix cores is 16 times the fp32 rate):
+// every operand is cut into three bf16 pieces of 8 + 8 + 8 significant bits by truncation, so hi + mid + lo
+// is the fp32 value exactly, and the six largest of the nine piece products are accumulated in fp32
+// (hi*hi, hi*mid, mid*hi, mid*mid, hi*lo, lo*hi).  The three dropped ones are below 2^-23 of the product,
+// the size of an fp32 rounding error.  Pieces of 8 values are packed as one MFMA operand.
+struct Split3 {
+  uintx4 hi, mid, lo;
+  __device__ __forceinline__ static void cut2(float x0, float x1, unsigned& h, unsigned& m, unsigned& l) {
+    const unsigned b0 = __float_as_uint(x0), b1 = __float_as_uint(x1);
+    h = __builtin_amdgcn_perm(b1, b0, 0x07060302u);  // upper halves of (x1, x0)
+    const float r0 = x0 - __uint_as_float(b0 & 0xffff0000u), r1 = x1 - __uint_as_float(b1 & 0xffff0000u);
+    const unsigned c0 = __float_as_uint(r0), c1 = __float_as_uint(r1);
+    m = __builtin_amdgcn_perm(c1, c0, 0x07060302u);
+    const float s0 = r0 - __uint_as_float(c0 & 0xffff0000u), s1 = r1 - __uint_as_float(c1 & 0xffff0000u);
+    l = __builtin_amdgcn_perm(__float_as_uint(s1), __float_as_uint(s0), 0x07060302u);
+  }
+  __device__ __forceinline__ void cut(const float4& u, const float4& v) {
+    unsigned h0, h1, h2, h3, m0, m1, m2, m3, l0, l1, l2, l3;
+    cut2(u.x, u.y, h0, m0, l0);
+    cut2(u.z, u.w, h1, m1, l1);
+    cut2(v.x, v.y, h2, m2, l2);
+    cut2(v.z, v.w, h3, m3, l3);
+    hi = uintx4{h0, h1, h2, h3};
+    mid = uintx4{m0, m1, m2, m3};
+    lo = uintx4{l0, l1, l2, l3};
+  }
+  __device__ __forceinline__ bf16x8 h() const { return __builtin_bit_cast(bf16x8, hi); }
+  __device__ __forceinline__ bf16x8 m() const { return __builtin_bit_cast(bf16x8, mid); }
+  __device__ __forceinline__ bf16x8 l() const { return __builtin_bit_cast(bf16x8, lo); }
+};
+
+
 constexpr int BN = 128;
 // One K-step is 128 bytes of every tile row (32 fp32 or 64 bf16 values); LDS rows are 144 bytes apart
 // (16-byte aligned, and 16-byte reads of 8 consecutive rows touch all banks once).

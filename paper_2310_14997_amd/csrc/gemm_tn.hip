@@ -13,6 +13,7 @@ namespace {
 
 using nt::floatx16;
 using nt::floatx4;
+typedef float floatx8 __attribute__((ext_vector_type(8)));
 
 constexpr int TM = 128, TN = 128, TK = 32;
 constexpr int kStageT = (TM + TN) * TK + TK;  // A tile, B tile, scales
@@ -31,7 +32,8 @@ __device__ __forceinline__ void dma16(const float* gptr, float* lds_base) {
 
 // MODE 0: one reduction over the contiguous rows [0, S).  MODE 1, 2: one reduction per sentence (grouped mode of
 // TnArgs); every workgroup share is a whole number of output tiles, so no partial tiles are exchanged.
-template <int MODE>
+// X3: fp32 products from bf16 matrix instructions (nt::Split3) instead of fp32 ones.
+template <int MODE, bool X3>
 __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total_iters) {
   extern __shared__ __align__(16) float lds[];
   __shared__ int s_last;
@@ -108,6 +110,74 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
   __syncthreads();
 
   const int fcol = lane & 31, fk = lane >> 5;
+  if constexpr (X3) {
+  // One 32x32x16 instruction takes 8 reduction rows per lane: rows 16 c + 8 (lane / 32) .. + 7 of chunk c of
+  // the step, read as 4-byte LDS words (the tile lies [row][column]).  The span scale (a power of two) goes
+  // into the A values before they are cut into bf16 pieces.
+#define SPCFG_TN_RAW(P, AS, BS, SS, C)                                          \
+  {                                                                             \
+    const int kb_ = 16 * (C) + 8 * fk;                                          \
+    P##s0 = *reinterpret_cast<const float4*>((SS) + kb_);                       \
+    P##s1 = *reinterpret_cast<const float4*>((SS) + kb_ + 4);                   \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j) {                             \
+      P##a0[j] = (AS)[(kb_ + j) * TM];                                          \
+      P##a1[j] = (AS)[(kb_ + j) * TM + 32];                                     \
+      P##b0[j] = (BS)[(kb_ + j) * TN];                                          \
+      P##b1[j] = (BS)[(kb_ + j) * TN + 32];                                     \
+    }                                                                           \
+  }
+#define SPCFG_TN_T(X, Y)                                                                             \
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A0.X(), B0.Y(), acc[0][0], 0, 0, 0);           \
+    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A0.X(), B1.Y(), acc[0][1], 0, 0, 0);           \
+    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1.X(), B0.Y(), acc[1][0], 0, 0, 0);           \
+    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1.X(), B1.Y(), acc[1][1], 0, 0, 0);
+#define SPCFG_TN_GROUP(P)                                                                            \
+  {                                                                                                  \
+    nt::Split3 A0, A1, B0, B1;                                                                       \
+    A0.cut(float4{P##a0[0] * P##s0.x, P##a0[1] * P##s0.y, P##a0[2] * P##s0.z, P##a0[3] * P##s0.w},   \
+           float4{P##a0[4] * P##s1.x, P##a0[5] * P##s1.y, P##a0[6] * P##s1.z, P##a0[7] * P##s1.w});  \
+    A1.cut(float4{P##a1[0] * P##s0.x, P##a1[1] * P##s0.y, P##a1[2] * P##s0.z, P##a1[3] * P##s0.w},   \
+           float4{P##a1[4] * P##s1.x, P##a1[5] * P##s1.y, P##a1[6] * P##s1.z, P##a1[7] * P##s1.w});  \
+    B0.cut(float4{P##b0[0], P##b0[1], P##b0[2], P##b0[3]}, float4{P##b0[4], P##b0[5], P##b0[6], P##b0[7]}); \
+    B1.cut(float4{P##b1[0], P##b1[1], P##b1[2], P##b1[3]}, float4{P##b1[4], P##b1[5], P##b1[6], P##b1[7]}); \
+    SPCFG_TN_T(l, h) SPCFG_TN_T(h, l) SPCFG_TN_T(m, m) SPCFG_TN_T(m, h) SPCFG_TN_T(h, m) SPCFG_TN_T(h, h) \
+  }
+  floatx8 xa0, xa1, xb0, xb1, ya0, ya1, yb0, yb1;
+  float4 xs0, xs1, ys0, ys1;
+  {
+    const float* as = lds + wm * 64 + fcol;
+    const float* bs = lds + TM * TK + wn * 64 + fcol;
+    const float* ss = lds + (TM + TN) * TK;
+    SPCFG_TN_RAW(x, as, bs, ss, 0)
+  }
+  for (int kt = k0; kt < k1; ++kt) {
+    const int buf = (kt - k0) & 1;
+    const int64_t sn = (int64_t)(kt + 1 < k1 ? kt + 1 : kt) * TK;  // the last step re-reads itself (never used)
+    SPCFG_TN_DMA(buf ^ 1, sn)  // the other stage: everybody left it at the last barrier
+    __builtin_amdgcn_sched_barrier(0);  // keep the loads at the top of the step
+    const float* as = lds + buf * kStageT + wm * 64 + fcol;
+    const float* bs = lds + buf * kStageT + TM * TK + wn * 64 + fcol;
+    const float* ss = lds + buf * kStageT + (TM + TN) * TK;
+    SPCFG_TN_RAW(y, as, bs, ss, 1)
+    SPCFG_TN_GROUP(x)
+    __builtin_amdgcn_sched_barrier(0);
+    SPCFG_TN_STORE_SC(buf ^ 1)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my part of the next tile has landed in LDS
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    {
+      const float* as2 = lds + (buf ^ 1) * kStageT + wm * 64 + fcol;
+      const float* bs2 = lds + (buf ^ 1) * kStageT + TM * TK + wn * 64 + fcol;
+      const float* ss2 = lds + (buf ^ 1) * kStageT + (TM + TN) * TK;
+      SPCFG_TN_RAW(x, as2, bs2, ss2, 0)
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    SPCFG_TN_GROUP(y)
+  }
+#undef SPCFG_TN_RAW
+#undef SPCFG_TN_T
+#undef SPCFG_TN_GROUP
+  } else {
   // operands of one K pair: named scalars, double-buffered by hand so that the LDS reads of pair kk+2 are in
   // flight while the MFMAs of pair kk execute
   // (the span scale is multiplied in when the pair is used, not when it is fetched: a use right behind
@@ -175,6 +245,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
     __builtin_amdgcn_sched_barrier(0);
     SPCFG_TN_MFMA(y)
   }
+  }
   __syncthreads();  // all operands fetched before the LDS tiles are reused by the next tile segment
 #undef SPCFG_TN_FRAGS
 #undef SPCFG_TN_MFMA
@@ -213,12 +284,12 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
 void launch_gemm_tn(const TnArgs& a, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_tn<0>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)kLdsBytesT);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_tn<1>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)kLdsBytesT);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_tn<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)kLdsBytesT);
+    const void* kernels[6] = {
+        reinterpret_cast<const void*>(&k_gemm_tn<0, false>), reinterpret_cast<const void*>(&k_gemm_tn<1, false>),
+        reinterpret_cast<const void*>(&k_gemm_tn<2, false>), reinterpret_cast<const void*>(&k_gemm_tn<0, true>),
+        reinterpret_cast<const void*>(&k_gemm_tn<1, true>),  reinterpret_cast<const void*>(&k_gemm_tn<2, true>)};
+    for (const void* k : kernels)
+      (void)hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytesT);
     attr_set = true;
   }
   const int tiles = ((2 * a.Np) / TM) * ((a.cols + TN - 1) / TN);
@@ -228,10 +299,9 @@ void launch_gemm_tn(const TnArgs& a, hipStream_t st) {
     const int64_t tiles_total = (int64_t)a.ngroups * tiles;
     const int64_t total64 = tiles_total * a.grp_kt_max;
     if (total64 >= ((int64_t)1 << 31)) return;  // guarded by the row-count limit of the layout
-    if (a.grp_mode == 1)
-      launch_k(k_gemm_tn<1>, dim3((unsigned)tiles_total), dim3(256), kLdsBytesT, st, a, a.grp_kt_max, (int)total64);
-    else
-      launch_k(k_gemm_tn<2>, dim3((unsigned)tiles_total), dim3(256), kLdsBytesT, st, a, a.grp_kt_max, (int)total64);
+    auto kernel = a.grp_mode == 1 ? (a.fp32_mfma ? k_gemm_tn<1, false> : k_gemm_tn<1, true>)
+                                  : (a.fp32_mfma ? k_gemm_tn<2, false> : k_gemm_tn<2, true>);
+    launch_k(kernel, dim3((unsigned)tiles_total), dim3(256), kLdsBytesT, st, a, a.grp_kt_max, (int)total64);
     return;
   }
   if (a.S <= 0) return;
@@ -244,7 +314,7 @@ void launch_gemm_tn(const TnArgs& a, hipStream_t st) {
   if (Gn > total / 2) Gn = total / 2 > 0 ? total / 2 : 1;
   int ipw = (total + Gn - 1) / Gn;
   Gn = (total + ipw - 1) / ipw;
-  launch_k(k_gemm_tn<0>, dim3(Gn), dim3(256), kLdsBytesT, st, a, ipw, total);
+  launch_k(a.fp32_mfma ? k_gemm_tn<0, false> : k_gemm_tn<0, true>, dim3(Gn), dim3(256), kLdsBytesT, st, a, ipw, total);
 }
 
 }  // namespace spcfg

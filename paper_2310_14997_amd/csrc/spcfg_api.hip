@@ -27,7 +27,7 @@ int check_cfg(const spcfg_config* c) {
   if (c->N < 1 || c->P < 1 || c->N > (1 << 16) || c->P > (1 << 16)) return SPCFG_ERR_SHAPE;
   if (c->max_B < 1 || c->max_B > kMaxB || c->max_n < 2 || c->max_n > kMaxLen) return SPCFG_ERR_SHAPE;
   if (c->precision != SPCFG_PRECISION_FP32 && c->precision != SPCFG_PRECISION_BF16) return SPCFG_ERR_UNSUPPORTED;
-  if (c->flags & ~(uint32_t)(SPCFG_FLAG_ACCUMULATE_GRADS | SPCFG_FLAG_PER_SENTENCE_GRAMMAR)) return SPCFG_ERR_UNSUPPORTED;
+  if (c->flags & ~(uint32_t)(SPCFG_FLAG_ACCUMULATE_GRADS | SPCFG_FLAG_PER_SENTENCE_GRAMMAR | SPCFG_FLAG_FP32_MFMA)) return SPCFG_ERR_UNSUPPORTED;
   return SPCFG_OK;
 }
 
@@ -247,6 +247,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
             const float* L, const float* R, const float* log_emit, float* logZ, hipStream_t st) {
   const int n_max = ly.n_max;
   const int64_t Np = ly.Np, Pp = ly.Pp;
+  const int fp32_mfma = (cfg->flags & SPCFG_FLAG_FP32_MFMA) ? 1 : 0;
   {
     Scope s(st, SPCFG_PROF_SETUP, 4.0 * 2 * (double)ly.N * (ly.N + ly.P) * 3 + 8.0 * ly.S1 * ly.P, 4);
     launch_plan(ly, p, plan.lens, st);
@@ -257,7 +258,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
   {  // width 1: [eta | zeta] = [L_P ; R_P] * emission vector
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.P * ly.S1);
     NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.leafE; a.lda = Pp; a.Bm = p.Wp; a.ldb = Pp; a.C = p.HZ; a.ldc = 2 * Np;
     if (ly.bf16) { a.A = p.leafEb; a.a_bf16 = 1; }
     a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
@@ -275,7 +276,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     if (w == n_max) break;  // every span of the largest width is a root span: never a child, not projected
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.N * rows);
     NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.a_bf16 = 1; }
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
@@ -306,6 +307,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
              hipStream_t st) {
   const int n_max = ly.n_max;
   const int64_t Np = ly.Np, Pp = ly.Pp;
+  const int fp32_mfma = (cfg->flags & SPCFG_FLAG_FP32_MFMA) ? 1 : 0;
   const int acc = (cfg->flags & SPCFG_FLAG_ACCUMULATE_GRADS) ? 1 : 0;
   {
     Scope s(st, SPCFG_PROF_ROOT, 16.0 * ly.N * ly.B, 3);
@@ -326,7 +328,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       launch_split_bwd(ly, p, w, row0, rows, st);
     }
     NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.UV + row0 * 2 * Np; a.lda = 2 * Np; a.K = (int)(2 * Np); a.rows = (int)rows;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np; a.a_bf16 = 1; }
     if (w >= 2) {
@@ -359,6 +361,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       int n_longest = 2;
       for (int b = 0; b < ly.B; ++b) n_longest = plan.lens.v[b] > n_longest ? plan.lens.v[b] : n_longest;
       TnArgs t{};
+      t.fp32_mfma = fp32_mfma;
       t.Np = (int)Np; t.N = ly.N; t.gL = grad_L; t.gR = grad_R; t.ldg = ly.N + ly.P; t.accumulate = acc;
       t.ngroups = ly.B; t.grp_lens = p.lens; t.grp_gstride = (int64_t)ly.N * (ly.N + ly.P);
       t.A = p.UV; t.lda = 2 * Np; t.sc = p.gsc;
@@ -372,6 +375,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       launch_gemm_tn(t, st);
     } else if (!ly.bf16) {
       TnArgs t{};
+      t.fp32_mfma = fp32_mfma;
       t.partial = p.partial; t.counters = p.counters; t.max_wgs = kGemmWgs; t.n_counters = ly.n_counters;
       t.Np = (int)Np; t.N = ly.N; t.gL = grad_L; t.gR = grad_R; t.ldg = ly.N + ly.P; t.accumulate = acc;
       t.A = p.UV + ly.S1 * 2 * Np; t.lda = 2 * Np; t.Bm = p.T; t.ldb = Np; t.sc = p.gsc + ly.S1; t.S = ly.S2;

@@ -143,6 +143,7 @@ struct NtArgs {
   // spans last within a width, so "rows whose eta is used", "rows whose zeta is used" (forward: two parts, one
   // column block each) and "prefix / middle / suffix rows" (reverse: the adjoint of zeta resp. eta is zero, half
   // of K is skipped) are contiguous ranges.
+  int fp32_mfma;  // 1: fp32 matrix instructions instead of the split-bf16 scheme (fp32 operands only)
   int parts;
   int prt_row0[3], prt_rows[3], prt_c0[3], prt_kbeg[3], prt_kt[3];
 };
@@ -154,6 +155,7 @@ constexpr int kGemmWgs = 512;                    // workgroups per projection la
 
 // C[a][b] (+)= sum_s sc[s] * A[s][a] * Bm[s][b]   (both operands reduction-major), written into grad_L / grad_R.
 struct TnArgs {
+  int fp32_mfma;                    // 1: fp32 matrix instructions instead of the split-bf16 scheme
   const float* A; int64_t lda;     // UV rows [S x 2Np]
   const float* Bm; int64_t ldb;    // T rows [S x Np] or leafE rows [S x Pp]
   const float* sc;                 // [S]

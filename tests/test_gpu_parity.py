@@ -288,6 +288,22 @@ def test_degenerate_sizes(N, P, lens):
     check_all(got, oracle_run(d))
 
 
+@pytest.mark.parametrize("kw", [
+    dict(),
+    dict(N=150, P=70, B=9, lengths=[2, 9, 17, 5, 12, 3, 3, 30, 4], V=300),
+])
+def test_fp32_matrix_instruction_path(kw):
+    """SPCFG_FLAG_FP32_MFMA: the products run on fp32 matrix instructions instead of the split-bf16 scheme; both
+    meet the fp32 tolerances against the oracle."""
+    d = synth.make_inputs("tiny", seed=515, pad_value=np.nan, **kw)
+    print("case fp32 mfma", kw, flush=True)
+    ref = oracle_run(d)
+    got, _ = gpu_run(d, flags=bd.FLAG_FP32_MFMA)
+    check_all(got, ref)
+    got3, _ = gpu_run(d)
+    check_all(got3, ref)
+
+
 def test_long_single_sentence_many_widths():
     """One sentence of 260 words (259 widths, late widths with a single span, LDS tables of 259 entries)."""
     d = synth.make_inputs("long", seed=31, pad_value=np.nan, N=24, P=20, B=2, lengths=[260, 7], V=200)
