@@ -3,8 +3,9 @@
 
 A step is one spcfg_inside_forward_backward call (every kernel of the hot path) on one synthetic
 PTB-shaped batch (N = P = 2048, B = 64, lengths <= 40) whose inputs are already resident in HBM.
-Prints ONE JSON line: sentences/s, plus `roofline` for the dominant kernel (the fp32 MFMA projection GEMM,
-timed with HIP events inside the library on the launch stream) and `cpu_baseline` (the CPU oracle timed on
+Prints ONE JSON line: sentences/s, plus `roofline` for the dominant kernel (the stacked projection GEMM, whose
+fp32 products are formed from six bf16 MFMA piece products each, timed with HIP events inside the library on
+the launch stream) and `cpu_baseline` (the CPU oracle timed on
 a bounded sample of the same batch on this machine's host cores).
 """
 from __future__ import annotations
@@ -22,6 +23,11 @@ import numpy as np  # noqa: E402
 
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
 PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+# fp32 operands, default path: every fp32 product costs six bf16 matrix-instruction products (three exact bf16
+# pieces per operand, the six largest of the nine piece products), so the matrix cores can deliver at most
+# a sixth of their bf16 rate in fp32-equivalent flop
+SPLIT_PRODUCTS = 6
+PEAK_SPLIT_TFLOPS = PEAK_BF16_MFMA_TFLOPS / SPLIT_PRODUCTS
 PEAK_HBM_GBS = 8000.0
 
 
@@ -175,7 +181,13 @@ def main():
     bf16 = precision == "bf16"
     wl = bd.Workload(d, precision=bd.PRECISION_BF16 if bf16 else bd.PRECISION_FP32,
                      flags=bd.FLAG_FP32_MFMA if args.fp32_mfma else 0)
-    peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_FP32_MFMA_TFLOPS
+    peak = PEAK_BF16_MFMA_TFLOPS if bf16 else (PEAK_FP32_MFMA_TFLOPS if args.fp32_mfma else PEAK_SPLIT_TFLOPS)
+    if bf16:
+        kernel_name, mfma = "k_gemm_nt16 (bf16 operands, bf16 MFMA", "bf16"
+    elif args.fp32_mfma:
+        kernel_name, mfma = "k_gemm_nt (fp32 MFMA", "f32"
+    else:
+        kernel_name, mfma = "k_gemm_nt (fp32 operands cut into 3 bf16 pieces, 6 bf16 MFMA products per fp32 product", "bf16 x6"
     wc = synth.work_counts(d["lengths"], d["N"], d["P"])
     stream = torch.cuda.current_stream()
 
@@ -242,8 +254,7 @@ def main():
                                f"split_terms={wc['split_terms']}, seed={d['seed']}",
                    "flop_fwd_bwd": wc["flop_fwd_bwd"], "tflops_fwd_bwd": wc["flop_fwd_bwd"] / (dt / args.steps) / 1e12},
         "roofline": {"bound": "mfma",
-                     "kernel": ("k_gemm_nt16 (bf16 MFMA" if bf16 else "k_gemm_nt (fp32 MFMA")
-                               + " stacked projection, forward + reverse)",
+                     "kernel": kernel_name + "; stacked projection, forward + reverse)", "mfma": mfma,
                      "achieved": achieved_tflops, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved_tflops / peak, "traffic": traffic,
                      "launches_per_step": proj_launches, "avg_launch_us": proj_ms * 1e3 / max(proj_launches, 1),

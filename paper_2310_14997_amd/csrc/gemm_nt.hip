@@ -138,9 +138,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
   SPCFG_MFMA1(A0, A1, B0, B1, x) SPCFG_MFMA1(A0, A1, B0, B1, y) SPCFG_MFMA1(A0, A1, B0, B1, z) SPCFG_MFMA1(A0, A1, B0, B1, w)
 
     if constexpr (X3) {
-    // fp32 product from bf16 matrix instructions: every operand is cut into three bf16 pieces (8 + 8 + 8
-    // significant bits, by truncation, so hi + mid + lo is the fp32 value exactly) and the six largest of the
-    // nine piece products are accumulated in fp32; the three dropped ones are below 2^-23 of the product.
+    // fp32 products from bf16 matrix instructions (nt::Split3).
     // One 32x32x16 instruction takes 8 K values per lane: the two 4-value reads of chunks 2c and 2c + 1.
     float4 pa0, pa1, pb0, pb1;  // chunk 0 of the current K-step, fetched one step ahead (behind the barrier)
     float4 qa0, qa1, qb0, qb1, ra_0, ra_1, rb_0, rb_1, sa0, sa1, sb0, sb1;  // chunks 1, 2, 3

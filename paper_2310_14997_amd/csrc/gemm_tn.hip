@@ -68,7 +68,17 @@ __global__ void __launch_bounds__(256, 2) k_gemm_tn(TnArgs g, int ipw, int total
     gL += grp * g.grp_gstride;
     gR += grp * g.grp_gstride;
   }
-  const int tile_a = tile_l % tiles_a, tile_b = tile_l / tiles_a;
+  int tile_a = tile_l % tiles_a, tile_b = tile_l / tiles_a;
+  if (MODE == 0) {
+    // 64 consecutive tiles (the tiles one XCD works on at a time: workgroups are renumbered into contiguous runs
+    // per XCD) form an 8 x 8 block of the output, so that XCD's L2 fetches 16 operand panels for them and not 34
+    const int tiles_bb = (g.cols + TN - 1) / TN;
+    if ((tiles_a & 7) == 0 && (tiles_bb & 7) == 0) {
+      const int blk = tile_l >> 6, l = tile_l & 63, blocks_a = tiles_a >> 3;
+      tile_a = (blk % blocks_a) * 8 + (l & 7);
+      tile_b = (blk / blocks_a) * 8 + (l >> 3);
+    }
+  }
   const int a0 = tile_a * TM, b0 = tile_b * TN;
 
   const int lc4 = tid & 31, lr = tid >> 5;  // 32 float4 per tile row, 8 rows per pass
