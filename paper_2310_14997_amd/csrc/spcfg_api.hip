@@ -60,8 +60,9 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   // One arrival counter per output tile of the largest launch: at most max(S1, S2) rows (one width; grouped
   // launches round every sentence's rows up to whole row tiles, at most one extra tile per sentence) and
   // max(2Np, Pp) columns (the projections write 2Np columns, the leaf reverse product P of them).  A launch cut
-  // into up to three row ranges rounds each of them up to whole row tiles: two extra tiles of 32 rows.
-  ly.n_counters = gemm_nt_tiles((int)(S1 > S2 ? S1 : S2) + (per_sentence ? 32 * B : 64),
+  // into up to three row ranges rounds each of them up to whole row tiles: two extra tiles of 32 rows (also with
+  // the per-sentence flag when the batch is a single sentence: that runs as a shared grammar).
+  ly.n_counters = gemm_nt_tiles((int)(S1 > S2 ? S1 : S2) + 64 + (per_sentence ? 32 * B : 0),
                                 2 * ly.Np > ly.Pp ? 2 * ly.Np : ly.Pp);
   {  // the bf16 rule-gradient product has 2Np rows and up to max(Np, Pp) columns
     const int g = (2 * ly.Np / 128 + 1) * ((ly.Np > ly.Pp ? ly.Np : ly.Pp) / 128 + 1);

@@ -44,6 +44,8 @@ def check_against_oracle(d, got, grad_logZ=None, sentences=None):
     dict(N=20, P=12, B=3, lengths=[70, 140, 9]),                     # 128-row tiles for the longest sentence
     dict(N=12, P=155, B=10, lengths=[2] * 10),                       # P > 2N, one row tile per sentence (regression:
     dict(N=47, P=135, B=3, lengths=[5, 4, 2]),                       # arrival counters ran short for the leaf product)
+    dict(N=1, P=63, B=1, lengths=[4]),                               # a batch of one sentence runs as a shared grammar
+    dict(N=33, P=20, B=1, lengths=[9]),                              # (regression: counters of the three-part launch)
 ])
 def test_per_sentence_grammars_match_oracle(kw):
     d = synth.make_inputs_per_sentence("tiny", pad_value=np.nan, **kw)
