@@ -288,6 +288,8 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     if (use_parts(ly, w) && Np % 128 == 0) {
       const WidthBlocks k = width_blocks(plan, ly, w);
       const int kt = (int)(Np / 32);
+      // the profile counts the executed flop: one of the two projections is left out for k.nP + k.nS rows
+      if (g_prof.on) g_prof.work[SPCFG_PROF_GEMM_FWD] -= 2.0 * ly.N * (double)ly.N * (k.nP + k.nS);
       a.parts = 2; a.cols = (int)Np;
       set_part(a, 0, 0, k.nP + k.nM, 0, 0, kt);
       set_part(a, 1, k.nP, k.nM + k.nS, (int)Np, 0, kt);
@@ -339,6 +341,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       if (use_parts(ly, w)) {  // prefix rows: only the eta adjoint (first half of K); suffix rows: only zeta's
         const WidthBlocks k = width_blocks(plan, ly, w);
         const int kt = (int)(Np / 32);
+        if (g_prof.on) g_prof.work[SPCFG_PROF_GEMM_BWD] -= 2.0 * ly.N * (double)ly.N * (k.nP + k.nS);
         a.parts = 3;
         set_part(a, 0, 0, k.nP, 0, 0, kt);
         set_part(a, 1, k.nP, k.nM, 0, 0, 2 * kt);
