@@ -147,6 +147,26 @@ def test_runtime_errors_do_not_launch():
     assert e.value.code == -4
 
 
+def check_flow_identities(d, got):
+    """Identities of expected rule counts that hold at any size: every tree has n - 1 binary rules, a nonterminal
+    occurs as a parent as often as it occurs as the root or as somebody's child, preterminal children are the
+    emission posteriors."""
+    lens = d["lengths"]
+    nm1 = float((lens.astype(np.float64) - 1).sum())
+    L64, R64 = d["L"].astype(np.float64), d["R"].astype(np.float64)
+    EL, ER = L64 * got["grad_L"], R64 * got["grad_R"]
+    N = d["N"]
+    assert EL.sum() == pytest.approx(nm1, rel=1e-4) and ER.sum() == pytest.approx(nm1, rel=1e-4)
+    check_grad("parent counts L vs R", EL.sum(axis=1), ER.sum(axis=1))
+    tok = np.zeros(d["P"])
+    for b in range(d["B"]):
+        tok += got["grad_log_emit"][b, : int(lens[b])].sum(axis=0)
+    check_grad("preterminal child counts vs emission posteriors", (EL + ER)[:, N:].sum(axis=0), tok)
+    assert got["grad_log_root"].sum() == pytest.approx(d["B"], rel=1e-4)
+    # nonterminal occurrences: as a parent = as the root + as somebody's child
+    check_grad("nonterminal flow", EL.sum(axis=1), got["grad_log_root"] + (EL + ER)[:, :N].sum(axis=0), 2e-4)
+
+
 def test_long_sentences_scaled_down():
     """Long-sentence shape (hundreds of widths, late widths with one or two spans) at a size the oracle finishes."""
     d = synth.make_inputs("long", pad_value=np.nan, N=192, P=160, B=3, lengths=[131, 64, 97], V=2000)
@@ -178,19 +198,29 @@ def test_ptb_full_size_sampled_against_oracle_and_invariants():
         check_logZ(got["logZ"][b:b + 1], np.array([lz]))
         check_grad(f"grad_log_emit[{b}]", got["grad_log_emit"][b, :n], ge)
         assert np.all(got["grad_log_emit"][b, n:] == 0.0)
-    nm1 = float((lens.astype(np.float64) - 1).sum())
-    L64, R64 = d["L"].astype(np.float64), d["R"].astype(np.float64)
-    EL, ER = L64 * got["grad_L"], R64 * got["grad_R"]
-    N = d["N"]
-    assert EL.sum() == pytest.approx(nm1, rel=1e-4) and ER.sum() == pytest.approx(nm1, rel=1e-4)
-    check_grad("parent counts L vs R", EL.sum(axis=1), ER.sum(axis=1))
-    tok = np.zeros(d["P"])
-    for b in range(d["B"]):
-        tok += got["grad_log_emit"][b, : int(lens[b])].sum(axis=0)
-    check_grad("preterminal child counts vs emission posteriors", (EL + ER)[:, N:].sum(axis=0), tok)
-    assert got["grad_log_root"].sum() == pytest.approx(d["B"], rel=1e-4)
-    # nonterminal occurrences: as a parent = as the root + as somebody's child
-    check_grad("nonterminal flow", EL.sum(axis=1), got["grad_log_root"] + (EL + ER)[:, :N].sum(axis=0), 2e-4)
+    check_flow_identities(d, got)
+
+
+def test_long_full_size_sampled_against_oracle_and_invariants():
+    """Long-sentence configuration as bench.py launches it (B=4, n up to 169, N=P=1024): the shortest sentence
+    against the oracle, every sentence through the identities that hold at any size."""
+    d = synth.make_inputs("long", pad_value=np.nan)
+    print("case long full size", flush=True)
+    wl = bd.Workload(d)
+    wl.forward_backward()
+    got = wl.results()
+    lens = d["lengths"]
+    b = int(np.argmin(lens))
+    n = int(lens[b])
+    print("  oracle sentence", b, "length", n, flush=True)
+    lz, gL, gR, gr, ge = O.inside_backward_sentence(d["log_root"], d["L"], d["R"], d["log_emit"][b, :n])
+    check_logZ(got["logZ"][b:b + 1], np.array([lz]))
+    check_grad(f"grad_log_emit[{b}]", got["grad_log_emit"][b, :n], ge)
+    for c in range(d["B"]):
+        m = int(lens[c])
+        assert np.allclose(got["grad_log_emit"][c, :m].sum(axis=1), 1.0, rtol=2e-4)
+        assert np.all(got["grad_log_emit"][c, m:] == 0.0)
+    check_flow_identities(d, got)
 
 
 # ---------------------------------------------------------------------------------------------- bf16 operands
