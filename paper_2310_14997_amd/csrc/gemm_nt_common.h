@@ -289,9 +289,15 @@ inline double work_of(const NtArgs& a) {
   for (int p = 0; p < a.parts; ++p) w += (double)a.prt_rows[p] * a.cols * a.prt_kt[p] * 32;
   return w;
 }
-inline int pick_bm(int rows, double work) {
-  if (rows <= 32 || work <= 2.7e9) return 32;
-  if (rows <= 64 || work <= 7.6e9) return 64;
+// fp32 operands (split products): repeated sweeps at N = 2048 put the changes at 190 rows (32 -> 64 for both
+// shapes) and at 380 rows (64 -> 128) for the forward shape (2N columns, K = N; 128 is 20 % faster at 500-900
+// rows) resp. 520 rows for the reverse shape (N columns, K = 2N; equal from there on); at N = 1024 the short tile
+// wins at every row count that occurs, which the same amounts of work reproduce.  bf16 operands keep the
+// thresholds of their own sweep.
+inline int pick_bm(int rows, double work, bool bf16, bool wide) {
+  const double t64 = bf16 ? 2.7e9 : 1.6e9, t128 = bf16 ? 7.6e9 : (wide ? 3.2e9 : 4.3e9);
+  if (rows <= 32 || work <= t64) return 32;
+  if (rows <= 64 || work <= t128) return 64;
   return 128;
 }
 inline int pick_wgs(double work) {
@@ -331,7 +337,8 @@ void launch_shared(Kernel kernel, const NtArgs& a, int BM, int BKelems, size_t l
 }
 
 inline int chosen_bm(const NtArgs& a) {
-  int bm = pick_bm(a.grouped ? a.grp_max_rows : a.rows, work_of(a));
+  // wide = more columns than K (the forward projection; a two-part launch is one)
+  int bm = pick_bm(a.grouped ? a.grp_max_rows : a.rows, work_of(a), a.a_bf16 != 0, a.parts == 2 || a.cols > a.K);
 #ifdef SPCFG_TUNING
   if (getenv("SPCFG_NT_BM")) bm = atoi(getenv("SPCFG_NT_BM"));
 #endif
