@@ -57,7 +57,8 @@ enum {
   /* SPCFG_PRECISION_FP32 forms its matrix products from bf16 matrix instructions by default: every fp32
      operand is cut exactly into three bf16 pieces and six piece products are accumulated in fp32, which keeps
      the accuracy of an fp32 product (the dropped terms are below 2^-23 of it) at a fraction of the cost of
-     fp32 matrix instructions.  This flag selects fp32 matrix instructions instead. */
+     fp32 matrix instructions.  This flag selects fp32 matrix instructions instead.  It has no effect on products
+     whose operands are bf16 (SPCFG_PRECISION_BF16). */
   SPCFG_FLAG_FP32_MFMA = 4u
 };
 
