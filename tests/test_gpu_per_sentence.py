@@ -57,6 +57,14 @@ def test_per_sentence_grammars_match_oracle(kw):
         assert np.array_equal(got[k], again[k], equal_nan=True), f"{k}: fused and split calls differ"
 
 
+def test_per_sentence_grammars_on_fp32_matrix_instructions():
+    """The grouped kernels also exist with fp32 matrix instructions (SPCFG_FLAG_FP32_MFMA)."""
+    d = synth.make_inputs_per_sentence("tiny", pad_value=np.nan, N=70, P=45, B=5, lengths=[2, 9, 17, 5, 12])
+    print("case per-sentence fp32 mfma", flush=True)
+    got, _ = run(d, flags=bd.FLAG_FP32_MFMA)
+    check_against_oracle(d, got)
+
+
 def test_per_sentence_upstream_weights_and_accumulate():
     d = synth.make_inputs_per_sentence("tiny", pad_value=np.nan, N=33, P=21, B=5, lengths=[4, 11, 2, 8, 15])
     g = np.array([0.5, 2.0, 1.0, 0.0, 3.0])
