@@ -15,6 +15,13 @@ namespace {
 
 using namespace nt;
 constexpr int BK = 32;
+// Split-product path: the tile lies in LDS already cut into its three bf16 planes (each thread cuts the 32
+// values it stages, so every value is cut once per workgroup and not once per wavefront that multiplies it).
+// One K-step of a row is 32 bf16 = 64 bytes per plane; rows are 80 bytes apart (16-byte aligned, and 16-byte
+// reads of 8 consecutive rows touch every bank once).  One stage: three planes of BM + 128 rows.
+constexpr int PRS = 20;  // plane row stride in 4-byte words
+template <int BM> constexpr int kPlaneWords = (BM + BN) * PRS;
+template <int BM, bool X3> constexpr size_t kLdsBytesNT = X3 ? (size_t)3 * kPlaneWords<BM> * 4 : Geo<BM>::kLdsBytes;
 
 // MODE 0: one product; 1: grouped (one grammar per sentence); 2: parts (several row ranges with their own
 // column block and K range in one launch, see NtArgs).
@@ -119,8 +126,10 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
   *reinterpret_cast<float4*>((DST) + BM * LDT + 64 * LDT) = rb2;                  \
   *reinterpret_cast<float4*>((DST) + BM * LDT + 96 * LDT) = rb3;
     SPCFG_LOAD_TILE(k0 * BK)
-    SPCFG_STORE_TILE(lds + lds_st)
-    __syncthreads();
+    if constexpr (!X3) {
+      SPCFG_STORE_TILE(lds + lds_st)
+      __syncthreads();
+    }
 
     // MFMA operands of one 8-wide K chunk: named scalars (arrays next to scheduling barriers go to scratch)
 #define SPCFG_FRAGS(A0, A1, B0, B1, AS, BS, KC)                                         \
@@ -138,50 +147,73 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
   SPCFG_MFMA1(A0, A1, B0, B1, x) SPCFG_MFMA1(A0, A1, B0, B1, y) SPCFG_MFMA1(A0, A1, B0, B1, z) SPCFG_MFMA1(A0, A1, B0, B1, w)
 
     if constexpr (X3) {
-    // fp32 products from bf16 matrix instructions (nt::Split3).
-    // One 32x32x16 instruction takes 8 K values per lane: the two 4-value reads of chunks 2c and 2c + 1.
-    float4 pa0, pa1, pb0, pb1;  // chunk 0 of the current K-step, fetched one step ahead (behind the barrier)
-    float4 qa0, qa1, qb0, qb1, ra_0, ra_1, rb_0, rb_1, sa0, sa1, sb0, sb1;  // chunks 1, 2, 3
-    SPCFG_FRAGS(pa0, pa1, pb0, pb1, lds + a_off, lds + b_off, 0)
-#define SPCFG_SPLIT(P, U, V) Split3 P; P.cut(U, V);
-#define SPCFG_MFMA_T(X, Y)                                                                                    \
-  acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A0.X(), B0.Y(), acc[0][0], 0, 0, 0);                      \
-  if (G::NI > 1) acc[0][G::NI - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A0.X(), B1.Y(), acc[0][G::NI - 1], 0, 0, 0); \
-  if (G::MI > 1) acc[G::MI - 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1.X(), B0.Y(), acc[G::MI - 1][0], 0, 0, 0); \
-  if (G::MI > 1 && G::NI > 1)                                                                                  \
-    acc[G::MI - 1][G::NI - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1.X(), B1.Y(), acc[G::MI - 1][G::NI - 1], 0, 0, 0);
-#define SPCFG_GROUP(UA0, UA1, UB0, UB1, VA0, VA1, VB0, VB1)                                    \
+    // fp32 products from bf16 matrix instructions (nt::Split3 describes the cut).  Single LDS stage: matrix phase
+    // on the stage (24 16-byte operand reads and 48 matrix instructions per wavefront, no vector work), barrier,
+    // cut the staged registers of the next step into the stage, barrier.  The two phases of the two workgroups
+    // of a CU interleave.
+    uint32_t* ldsu = reinterpret_cast<uint32_t*>(lds);
+    constexpr int PL = kPlaneWords<BM>;
+    const int st_off = lr * PRS + lc4 * 2;                         // this thread's 4 values of row lr (+ 32 q)
+    const int fa_off = (wm * G::MI * 32 + frag_row) * PRS + (lane >> 5) * 4;   // 8 values of chunk c: + 8 c words
+    const int fb_off = (BM + wn * G::NI * 32 + frag_row) * PRS + (lane >> 5) * 4;
+#define SPCFG_CUT_STORE1(V, ROWOFF)                                                            \
   {                                                                                            \
-    SPCFG_SPLIT(A0, UA0, VA0) SPCFG_SPLIT(B0, UB0, VB0)                                        \
-    Split3 A1, B1;                                                                             \
-    if (G::MI > 1) A1.cut(UA1, VA1);                                                           \
-    if (G::NI > 1) B1.cut(UB1, VB1);                                                           \
+    unsigned h0_, m0_, l0_, h1_, m1_, l1_;                                                     \
+    Split3::cut2(V.x, V.y, h0_, m0_, l0_);                                                     \
+    Split3::cut2(V.z, V.w, h1_, m1_, l1_);                                                     \
+    *reinterpret_cast<uint2*>(ldsu + st_off + (ROWOFF)*PRS) = uint2{h0_, h1_};                 \
+    *reinterpret_cast<uint2*>(ldsu + PL + st_off + (ROWOFF)*PRS) = uint2{m0_, m1_};            \
+    *reinterpret_cast<uint2*>(ldsu + 2 * PL + st_off + (ROWOFF)*PRS) = uint2{l0_, l1_};        \
+  }
+#define SPCFG_CUT_STORE                                             \
+  SPCFG_CUT_STORE1(ra0, 0)                                          \
+  if (G::QA > 1) SPCFG_CUT_STORE1(ra1, 32)                          \
+  if (G::QA > 2) SPCFG_CUT_STORE1(ra2, 64)                          \
+  if (G::QA > 2) SPCFG_CUT_STORE1(ra3, 96)                          \
+  SPCFG_CUT_STORE1(rb0, BM) SPCFG_CUT_STORE1(rb1, BM + 32) SPCFG_CUT_STORE1(rb2, BM + 64) SPCFG_CUT_STORE1(rb3, BM + 96)
+#define SPCFG_OPER(PLANE, OFF, C) \
+  __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(ldsu + (PLANE)*PL + (OFF) + 8 * (C)))
+#define SPCFG_MFMA_T(X, Y)                                                                                    \
+  acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0##X, b0##Y, acc[0][0], 0, 0, 0);                        \
+  if (G::NI > 1) acc[0][G::NI - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0##X, b1##Y, acc[0][G::NI - 1], 0, 0, 0); \
+  if (G::MI > 1) acc[G::MI - 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1##X, b0##Y, acc[G::MI - 1][0], 0, 0, 0); \
+  if (G::MI > 1 && G::NI > 1)                                                                                  \
+    acc[G::MI - 1][G::NI - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1##X, b1##Y, acc[G::MI - 1][G::NI - 1], 0, 0, 0);
+#define SPCFG_CHUNK(C)                                                                             \
+  {                                                                                                \
+    const bf16x8 a0h = SPCFG_OPER(0, fa_off, C), a0m = SPCFG_OPER(1, fa_off, C), a0l = SPCFG_OPER(2, fa_off, C); \
+    const bf16x8 b0h = SPCFG_OPER(0, fb_off, C), b0m = SPCFG_OPER(1, fb_off, C), b0l = SPCFG_OPER(2, fb_off, C); \
+    bf16x8 a1h = a0h, a1m = a0m, a1l = a0l, b1h = b0h, b1m = b0m, b1l = b0l;                       \
+    if (G::MI > 1) {                                                                               \
+      a1h = SPCFG_OPER(0, fa_off + 32 * PRS, C); a1m = SPCFG_OPER(1, fa_off + 32 * PRS, C);        \
+      a1l = SPCFG_OPER(2, fa_off + 32 * PRS, C);                                                   \
+    }                                                                                              \
+    if (G::NI > 1) {                                                                               \
+      b1h = SPCFG_OPER(0, fb_off + 32 * PRS, C); b1m = SPCFG_OPER(1, fb_off + 32 * PRS, C);        \
+      b1l = SPCFG_OPER(2, fb_off + 32 * PRS, C);                                                   \
+    }                                                                                              \
     SPCFG_MFMA_T(l, h) SPCFG_MFMA_T(h, l) SPCFG_MFMA_T(m, m) SPCFG_MFMA_T(m, h) SPCFG_MFMA_T(h, m) SPCFG_MFMA_T(h, h) \
   }
-
+    SPCFG_CUT_STORE  // the first step (the stage is free: the previous tile segment ended with a barrier)
+    __syncthreads();
     for (int kt = k0; kt < k1; ++kt) {
-      const int buf = (kt - k0) & 1;
-      const int kn = min(kt + 1, k1 - 1) * BK;
-      SPCFG_LOAD_TILE(kn)
+      const bool more = kt + 1 < k1;  // uniform over the workgroup
+      if (more) { SPCFG_LOAD_TILE((kt + 1) * BK) }
+      __builtin_amdgcn_sched_barrier(0);  // keep the prefetch loads at the top of the step
+      SPCFG_CHUNK(0)
+      SPCFG_CHUNK(1)
       __builtin_amdgcn_sched_barrier(0);
-      const float* as = lds + buf * G::kStage + a_off;
-      const float* bs = lds + buf * G::kStage + b_off;
-      SPCFG_FRAGS(qa0, qa1, qb0, qb1, as, bs, 1)
-      SPCFG_FRAGS(ra_0, ra_1, rb_0, rb_1, as, bs, 2)
-      SPCFG_FRAGS(sa0, sa1, sb0, sb1, as, bs, 3)
-      SPCFG_GROUP(pa0, pa1, pb0, pb1, qa0, qa1, qb0, qb1)
-      __builtin_amdgcn_sched_barrier(0);
-      SPCFG_STORE_TILE(lds + (buf ^ 1) * G::kStage + lds_st)
-      __builtin_amdgcn_sched_barrier(0);
-      __syncthreads();
-      __builtin_amdgcn_sched_barrier(0);
-      SPCFG_FRAGS(pa0, pa1, pb0, pb1, lds + (buf ^ 1) * G::kStage + a_off, lds + (buf ^ 1) * G::kStage + b_off, 0)
-      __builtin_amdgcn_sched_barrier(0);
-      SPCFG_GROUP(ra_0, ra_1, rb_0, rb_1, sa0, sa1, sb0, sb1)
+      if (more) {
+        __syncthreads();  // every wavefront has read its operands of this step
+        SPCFG_CUT_STORE
+        __syncthreads();
+      }
     }
-#undef SPCFG_SPLIT
+#undef SPCFG_CUT_STORE1
+#undef SPCFG_CUT_STORE
+#undef SPCFG_OPER
 #undef SPCFG_MFMA_T
-#undef SPCFG_GROUP
+#undef SPCFG_CHUNK
     } else {
     float4 pa0, pa1, pb0, pb1;  // chunk 0 of the current K-step, fetched one step ahead (behind the barrier)
     float4 qa0, qa1, qb0, qb1;  // chunks 1..3
@@ -234,10 +266,10 @@ void launch_x(const NtArgs& a, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI, BM, MODE, X3>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::kLdsBytes);
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytesNT<BM, X3>);
     attr_set = true;
   }
-  launch_shared(k_gemm_nt<EPI, BM, MODE, X3>, a, BM, BK, G::kLdsBytes, st);
+  launch_shared(k_gemm_nt<EPI, BM, MODE, X3>, a, BM, BK, kLdsBytesNT<BM, X3>, st);
 }
 
 template <int EPI, int BM, int MODE>
