@@ -308,6 +308,23 @@ void launch_bm(const NtArgs& a, hipStream_t st) {
 int gemm_nt_tiles(int rows, int cols) { return ((rows + 31) / 32) * ((cols + nt::BN - 1) / nt::BN); }
 size_t gemm_nt_partial_bytes(int max_wgs) { return (size_t)2 * max_wgs * nt::Geo<128>::kSlotFloats * sizeof(float); }
 
+// Parts that cover all columns over different K ranges of the same rows (the reverse product: the adjoint half
+// they leave out is zero) can also run as one plain product.  Each part rounds its rows up to whole tiles, so with
+// few prefix / suffix rows per width and tall tiles the plain product has fewer (tile, K-step) units: then the parts
+// are dropped.  Returns whether the launch keeps its parts.
+bool gemm_nt_keep_parts(NtArgs& a) {
+  if (a.parts == 0) return false;
+  const int bm = nt::chosen_bm(a);
+  int units_parts = 0;
+  for (int p = 0; p < a.parts; ++p) {
+    if (a.prt_c0[p] != 0) return true;  // parts with their own column blocks (the forward product) stay
+    units_parts += ((a.prt_rows[p] + bm - 1) / bm) * a.prt_kt[p];
+  }
+  if (((a.rows + bm - 1) / bm) * (a.K / BK) > units_parts) return true;
+  a.parts = 0;
+  return false;
+}
+
 void launch_gemm_nt(const NtArgs& a, hipStream_t st) {
   if (a.rows <= 0 || a.cols <= 0) return;
   if (a.b_bf16) { launch_gemm_nt16(a, st); return; }

@@ -341,11 +341,12 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       if (use_parts(ly, w)) {  // prefix rows: only the eta adjoint (first half of K); suffix rows: only zeta's
         const WidthBlocks k = width_blocks(plan, ly, w);
         const int kt = (int)(Np / 32);
-        if (g_prof.on) g_prof.work[SPCFG_PROF_GEMM_BWD] -= 2.0 * ly.N * (double)ly.N * (k.nP + k.nS);
         a.parts = 3;
         set_part(a, 0, 0, k.nP, 0, 0, kt);
         set_part(a, 1, k.nP, k.nM, 0, 0, 2 * kt);
         set_part(a, 2, k.nP + k.nM, k.nS, 0, kt, kt);
+        // (the profile counts the executed flop)
+        if (gemm_nt_keep_parts(a) && g_prof.on) g_prof.work[SPCFG_PROF_GEMM_BWD] -= 2.0 * ly.N * (double)ly.N * (k.nP + k.nS);
       }
       set_groups(a, plan, ly, p, w, row0, 2 * Np * Np);
       launch_gemm_nt(a, st);

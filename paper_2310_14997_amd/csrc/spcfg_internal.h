@@ -149,6 +149,7 @@ struct NtArgs {
 };
 void launch_gemm_nt(const NtArgs& a, hipStream_t st);
 void launch_gemm_nt16(const NtArgs& a, hipStream_t st);  // bf16-operand variant (called through launch_gemm_nt)
+bool gemm_nt_keep_parts(NtArgs& a);             // drops the parts of a launch that would not save work
 int gemm_nt_tiles(int rows, int cols);           // number of output tiles (= arrival counters needed)
 size_t gemm_nt_partial_bytes(int max_wgs);       // scratch needed for partial tiles
 constexpr int kGemmWgs = 512;                    // workgroups per projection launch: 2 per CU on 256 CUs
