@@ -1,12 +1,16 @@
-// fp32 MFMA GEMM for the stacked projections (Sec. 3.2: [eta | zeta] = [L;R] * beta for all spans of one
+// fp32-operand MFMA GEMM for the stacked projections (Sec. 3.2: [eta | zeta] = [L;R] * beta for all spans of one
 // width at once) and for their reverse:  C[r][c] = sum_k A[r][k] * Bm[c][k], both operands K-contiguous.
 //
-// gfx950 mapping: 128x128x32 tile per 256-thread workgroup (4 wavefronts, 2x2, 64x64 each = 2x2 tiles of
-// v_mfma_f32_32x32x2_f32; shorter tiles for widths with few spans).  Global -> registers -> LDS with two LDS
-// stages and one barrier per K-step.  Each lane fetches its MFMA operands as one 16-byte LDS read covering
-// four K values; the K order inside an 8-wide chunk is permuted identically for both operands (lanes 0-31
-// take k0..k0+3, lanes 32-63 k0+4..k0+7), which leaves the sum over K unchanged.  Work sharing across
-// workgroups and the epilogues are in gemm_nt_common.h.
+// gfx950 mapping: 128x128x32 tile per 256-thread workgroup (4 wavefronts, 2x2, 64x64 each = 2x2 tiles of 32x32;
+// shorter tiles for widths with few spans), global -> registers -> LDS, one K-step of loads in flight.
+// Two inner loops:
+//  * default: fp32 products from bf16 matrix instructions (nt::Split3): the staged registers are cut into three
+//    bf16 planes on their way into a single LDS stage; per K-step a matrix phase (16-byte operand reads,
+//    v_mfma_f32_32x32x16_bf16), a barrier, the cut of the next step, a barrier;
+//  * SPCFG_FLAG_FP32_MFMA: v_mfma_f32_32x32x2_f32 on fp32 tiles in two LDS stages, one barrier per K-step; each
+//    lane fetches its operands as one 16-byte LDS read covering four K values (the K order inside an 8-wide chunk
+//    is permuted identically for both operands, which leaves the sum over K unchanged).
+// Work sharing across workgroups and the epilogues are in gemm_nt_common.h.
 #include "gemm_nt_common.h"
 
 namespace spcfg {

@@ -1,9 +1,10 @@
-// fp32 MFMA GEMM for the rule gradients:  d/d[L;R][a][b] = sum_s sc[s] * UV[s][a] * X[s][b], where s runs over
+// fp32-operand MFMA GEMM for the rule gradients:  d/d[L;R][a][b] = sum_s sc[s] * UV[s][a] * X[s][b], where s runs over
 // every span row, UV holds the scaled adjoints of [eta | zeta] and X the stored inside vectors (chain rule
 // through the stacked projection of Sec. 3.2).  Both operands are reduction-major, so tiles go to LDS as
 // they lie in memory ([s][a], [s][b]) and every MFMA operand is a conflict-free 4-byte LDS read.
-// 128x128 output tile, 32 span rows per step, 4 wavefronts (2x2) of 2x2 v_mfma_f32_32x32x2_f32 tiles.
-// The per-row power-of-two scale is applied to the A fragments in registers.  The (tile, K-step) space is
+// 128x128 output tile, 32 span rows per step, 4 wavefronts (2x2) of 2x2 tiles of 32x32: by default fp32 products
+// from bf16 matrix instructions (nt::Split3, fragments cut in registers), with SPCFG_FLAG_FP32_MFMA
+// v_mfma_f32_32x32x2_f32.  The per-row power-of-two scale is applied to the A fragments in registers.  The (tile, K-step) space is
 // shared among workgroups as in the projection GEMMs, so grammars with few output tiles still fill the chip.
 #include "gemm_nt_common.h"
 
