@@ -334,6 +334,15 @@ def test_fp32_matrix_instruction_path(kw):
     check_all(got3, ref)
 
 
+def test_large_grammar_short_sentences():
+    """N = 4096 nonterminals in fp32 (32 column tiles of the reverse product, 64 of the forward one, 128 K-steps):
+    twice the headline grammar, on sentences short enough for the oracle."""
+    d = synth.make_inputs("tiny", seed=4096, pad_value=np.nan, N=4096, P=1024, B=3, lengths=[5, 3, 2], V=100)
+    print("case N=4096", flush=True)
+    got, _ = gpu_run(d, fused=True)
+    print(check_all(got, oracle_run(d)))
+
+
 def test_long_single_sentence_many_widths():
     """One sentence of 260 words (259 widths, late widths with a single span, LDS tables of 259 entries)."""
     d = synth.make_inputs("long", seed=31, pad_value=np.nan, N=24, P=20, B=2, lengths=[260, 7], V=200)
