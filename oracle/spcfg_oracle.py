@@ -17,7 +17,8 @@ children in columns [0, N), preterminal children in columns [N, N+P).  Parents a
 spans of width 1 carry preterminal vectors and wider spans nonterminal vectors.
 
 The gradients are the exact partial derivatives of sum_b g_b * log Z_b (Sec. 3.2 "Recomputation" gives
-d o_ij / d a_ik = exp(a_ik + b_kj - o_ij); the rest is the chain rule through the projection identity).
+d o_ij / d a_ik = exp(a_ik + b_kj - o_ij); the rest is the chain rule through the projection identity),
+taken with respect to the probability-space entries of L and R, also where an entry is zero.
 With g = 1:  grad_log_root[A] is the posterior of A at the root, grad_log_emit[b, i, T] the posterior of
 preterminal T over token i, and L * grad_L, R * grad_R are expected rule counts.
 
@@ -96,18 +97,21 @@ def inside(log_root, L, R, log_emit, lengths):
     return out
 
 
-def _safe_exp_diff(x, y):
-    """exp(x - y) with the convention exp(-inf - (-inf)) = 0 (a zero-probability item carries no mass)."""
-    with np.errstate(invalid="ignore"):
-        d = x - y
-    return np.exp(np.where(np.isnan(d), _NEG_INF, d))
+def _log_adjoint_project(W, la):
+    """log(exp(la) @ W) for every row of la with the row maximum as the shift;  W: [N, K], la: [S, N]  ->  [S, K]."""
+    x = la.max(axis=1, keepdims=True)
+    x = np.where(np.isfinite(x), x, 0.0)
+    with np.errstate(divide="ignore"):
+        return x + np.log(np.exp(la - x) @ W)
 
 
-def _ratio(adj, x, logv):
-    """adj * exp(x - logv), i.e. adj / (W p) since logv = x + log(W p); 0 where the adjoint is 0."""
-    with np.errstate(over="ignore", invalid="ignore"):
-        r = adj * _safe_exp_diff(x, logv)
-    return np.where(adj == 0.0, 0.0, r)
+def _outer_sum(la, lo):
+    """sum_s exp(la[s, A] + lo[s, B])  ->  [N, K], each row pair shifted by its own maxima."""
+    x = la.max(axis=1, keepdims=True)
+    y = lo.max(axis=1, keepdims=True)
+    x = np.where(np.isfinite(x), x, 0.0)
+    y = np.where(np.isfinite(y), y, 0.0)
+    return (np.exp(la - x) * np.exp(x + y)).T @ np.exp(lo - y)
 
 
 def inside_backward_sentence(log_root, L, R, e, g=1.0, return_marginals=False):
@@ -116,6 +120,16 @@ def inside_backward_sentence(log_root, L, R, e, g=1.0, return_marginals=False):
     Returns (logZ, grad_L, grad_R, grad_log_root, grad_log_emit) for g * log Z, all float64; with
     return_marginals also the dict of span posteriors obar[(i, j)] (width >= 2).  A sentence with Z = 0
     contributes zero gradients.
+
+    grad_L, grad_R are derivatives with respect to the entries of L and R themselves (probability space),
+    also at entries that are zero.  The reverse pass therefore carries the adjoints of the probability-space
+    quantities beta = exp(o), eta = exp(a), zeta = exp(b), each kept as its logarithm (every adjoint of log Z
+    is a sum of products of non-negative weights, so the logarithm exists or is -inf):
+        lo_ij[A] = log d logZ / d beta_ij[A],   la_ik[A] = log d logZ / d eta_ik[A],   lb_kj likewise.
+    The paper's identity d o_ij / d a_ik = exp(a_ik + b_kj - o_ij) (Sec. 3.2 "Recomputation") is the same
+    statement multiplied through by eta_ik / beta_ij; written for eta, zeta, beta themselves it stays
+    meaningful where a parent's whole block of L or R is zero (eta = 0, a = -inf) and the log-space adjoint
+    d logZ / d a = eta * d logZ / d eta would vanish identically although d logZ / d eta does not.
     """
     log_root = np.asarray(log_root, dtype=np.float64)
     L = np.asarray(L, dtype=np.float64)
@@ -132,51 +146,47 @@ def inside_backward_sentence(log_root, L, R, e, g=1.0, return_marginals=False):
     if not np.isfinite(logZ):
         return (logZ, gL, gR, g_root, g_emit) + ((obar,) if return_marginals else ())
     L_N, L_P, R_N, R_P = L[:, :N], L[:, N:], R[:, :N], R[:, N:]
-    abar = {s: np.zeros(N) for s in a}
-    bbar = {s: np.zeros(N) for s in b}
+    la = {s: np.full(N, _NEG_INF) for s in a}
+    lb = {s: np.full(N, _NEG_INF) for s in b}
+    lo = {}
 
-    # root rule: d logZ / d o_0n[A] = exp(log_root[A] + o_0n[A] - logZ)
-    obar[(0, n)] = g * _safe_exp_diff(log_root + o[(0, n)], logZ)
+    # root rule: Z = sum_A root[A] beta_0n[A]  =>  d logZ / d beta_0n[A] = root[A] / Z
+    lo[(0, n)] = log_root - logZ
+    obar[(0, n)] = np.exp(lo[(0, n)] + o[(0, n)])
     g_root += obar[(0, n)]
 
-    for w in range(n, 1, -1):  # every parent of a span is wider, so its adjoint is final here
+    for w in range(n, 1, -1):  # every parent of a span is wider, so its adjoints are final here
         spans = [(i, i + w) for i in range(n - w + 1)]
         if w < n:
-            # all spans of this width at once (rows = spans):
-            # a = x + log(L_N p), p = exp(o - x):  d a[A] / d L[A,B] = p[B] / (L_N p)[A],
-            #                                    d a[A] / d o[B]   = L[A,B] p[B] / (L_N p)[A]
+            # eta = L_N beta, zeta = R_N beta (all spans of this width at once, rows = spans):
+            #   d logZ / d beta[B] = sum_A adj_eta[A] L[A,B] + adj_zeta[A] R[A,B]
+            #   d logZ / d L[A,B] += adj_eta[A] beta[B],   d logZ / d R[A,B] += adj_zeta[A] beta[B]
             ow = np.stack([o[s] for s in spans])
-            x = ow.max(axis=1, keepdims=True)
-            x = np.where(np.isfinite(x), x, 0.0)
-            p = np.exp(ow - x)
-            ab = np.stack([abar[s] for s in spans])
-            bb = np.stack([bbar[s] for s in spans])
-            u = _ratio(ab, x, np.stack([a[s] for s in spans]))  # abar / (L_N p)
-            v = _ratio(bb, x, np.stack([b[s] for s in spans]))
-            gL[:, :N] += u.T @ p
-            gR[:, :N] += v.T @ p
-            ob = p * (u @ L_N + v @ R_N)
+            las = np.stack([la[s] for s in spans])
+            lbs = np.stack([lb[s] for s in spans])
+            gL[:, :N] += _outer_sum(las, ow)
+            gR[:, :N] += _outer_sum(lbs, ow)
+            low = np.logaddexp(_log_adjoint_project(L_N, las), _log_adjoint_project(R_N, lbs))
             for r, s in enumerate(spans):
-                obar[s] = ob[r]
-        # Eq. 1 backward: d o_ij / d a_ik = d o_ij / d b_kj = exp(a_ik + b_kj - o_ij)
+                lo[s] = low[r]
+                obar[s] = np.exp(low[r] + ow[r])  # beta * d logZ / d beta: the span posterior
+        # beta_ij = sum_k eta_ik * zeta_kj (Eq. 1 in probability space):
+        #   adj_eta_ik += adj_beta_ij * zeta_kj,   adj_zeta_kj += adj_beta_ij * eta_ik
         for (i, j) in spans:
             for k in range(i + 1, j):
-                gamma = obar[(i, j)] * _safe_exp_diff(a[(i, k)] + b[(k, j)], o[(i, j)])
-                abar[(i, k)] += gamma
-                bbar[(k, j)] += gamma
-    # width 1: same projection backward with the preterminal blocks; eps = exp(e - x)
+                la[(i, k)] = np.logaddexp(la[(i, k)], lo[(i, j)] + b[(k, j)])
+                lb[(k, j)] = np.logaddexp(lb[(k, j)], lo[(i, j)] + a[(i, k)])
+    # width 1: the same projection backward with the preterminal blocks; beta_i = exp(e_i)
     leaves = [(i, i + 1) for i in range(n)]
-    x = e.max(axis=1, keepdims=True)
-    eps = np.exp(e - x)
-    ab = np.stack([abar[s] for s in leaves])
-    bb = np.stack([bbar[s] for s in leaves])
-    u = _ratio(ab, x, np.stack([a[s] for s in leaves]))
-    v = _ratio(bb, x, np.stack([b[s] for s in leaves]))
-    gL[:, N:] += u.T @ eps
-    gR[:, N:] += v.T @ eps
-    g_emit[:] = eps * (u @ L_P + v @ R_P)
-    out = (logZ, gL, gR, g_root, g_emit)
-    return out + ((obar,) if return_marginals else ())
+    las = np.stack([la[s] for s in leaves])
+    lbs = np.stack([lb[s] for s in leaves])
+    gL[:, N:] += _outer_sum(las, e)
+    gR[:, N:] += _outer_sum(lbs, e)
+    g_emit[:] = np.exp(np.logaddexp(_log_adjoint_project(L_P, las), _log_adjoint_project(R_P, lbs)) + e)
+    out = (logZ, g * gL, g * gR, g * g_root, g * g_emit)
+    if return_marginals:
+        out += ({s: g * v for s, v in obar.items()},)
+    return out
 
 
 def inside_backward(log_root, L, R, log_emit, lengths, grad_logZ=None):

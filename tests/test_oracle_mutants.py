@@ -19,12 +19,25 @@ MUTANTS = {
     "shift not added back in the projection": ("return x + np.log(np.exp(o - x) @ W.T)",
                                                "return np.log(np.exp(o - x) @ W.T)"),
     "transposed projection operand": ("a1 = _log_project(L_P, e)", "a1 = _log_project(L_P[:, ::-1], e)"),
-    "grad_R accumulates the left adjoint": ("gR[:, :N] += v.T @ p", "gR[:, :N] += u.T @ p"),
-    "right child gets no adjoint": ("                bbar[(k, j)] += gamma\n", "                pass\n"),
+    "grad_R accumulates the left adjoint": ("gR[:, :N] += _outer_sum(lbs, ow)", "gR[:, :N] += _outer_sum(las, ow)"),
+    "right child gets no adjoint": ("                lb[(k, j)] = np.logaddexp(lb[(k, j)], lo[(i, j)] + a[(i, k)])\n",
+                                    "                pass\n"),
     "root posterior not accumulated": ("    g_root += obar[(0, n)]\n", "    pass\n"),
-    "emission gradient misses the right-child term": ("g_emit[:] = eps * (u @ L_P + v @ R_P)",
-                                                      "g_emit[:] = eps * (u @ L_P)"),
-    "span adjoint misses the R term": ("ob = p * (u @ L_N + v @ R_N)", "ob = p * (u @ L_N)"),
+    "emission gradient misses the right-child term": (
+        "g_emit[:] = np.exp(np.logaddexp(_log_adjoint_project(L_P, las), _log_adjoint_project(R_P, lbs)) + e)",
+        "g_emit[:] = np.exp(_log_adjoint_project(L_P, las) + e)"),
+    "span adjoint misses the R term": (
+        "low = np.logaddexp(_log_adjoint_project(L_N, las), _log_adjoint_project(R_N, lbs))",
+        "low = _log_adjoint_project(L_N, las)"),
+    # the log-space chain rule d logZ / d a = eta * d logZ / d eta vanishes where eta = 0: a reverse pass that
+    # divides it by eta afterwards (and takes 0 / 0 = 0) loses the derivative at a parent's dead column block
+    "adjoint of eta carried as eta times itself (0 where eta = 0)": (
+        "                la[(i, k)] = np.logaddexp(la[(i, k)], lo[(i, j)] + b[(k, j)])\n",
+        "                la[(i, k)] = np.logaddexp(la[(i, k)], lo[(i, j)] + b[(k, j)] + np.where(np.isfinite(a[(i, k)]), 0.0, _NEG_INF))\n"),
+    "outer product shifted by one maximum only": ("return (np.exp(la - x) * np.exp(x + y)).T @ np.exp(lo - y)",
+                                                   "return (np.exp(la - x) * np.exp(x)).T @ np.exp(lo - y)"),
+    "adjoint projection multiplies with the transpose": ("return x + np.log(np.exp(la - x) @ W)",
+                                                         "return x + np.log(np.exp(la - x) @ W.T[:, :W.shape[1]])"),
     "root weights ignored": ("logZ = _logsumexp0((log_root + o[(0, n)])[:, None])[0]",
                              "logZ = _logsumexp0((o[(0, n)])[:, None])[0]"),
 }
@@ -40,6 +53,8 @@ PIN_CALLS = [
     lambda: pins.test_gradients_are_expected_counts_from_enumeration(2, 3, 4),
     lambda: pins.test_gradients_match_central_finite_differences(),
     lambda: pins.test_gradient_invariants(),
+    lambda: pins.test_derivative_at_dead_rule_blocks("L", "pre"),
+    lambda: pins.test_derivative_at_dead_rule_blocks("R", "non"),
 ]
 
 

@@ -87,6 +87,40 @@ def brute_force(log_root, L, R, e):
     return Z, cL, cR, c_root, c_emit
 
 
+def brute_force_derivatives(log_root, L, R, e):
+    """dZ/dL[A,B] and dZ/dR[A,C] as polynomial derivatives: for every labelled tree and every use of the factor,
+    the product of all its other factors.  Unlike weighted counts this is defined where the entry is zero."""
+    n, P = e.shape
+    N = L.shape[0]
+    root, emit = np.exp(log_root), np.exp(e)
+    dL, dR = np.zeros_like(L), np.zeros_like(R)
+    for tree in bracketings(0, n):
+        nodes = []
+
+        def walk(t):
+            if isinstance(t, int):
+                return ("l", t)
+            me = len(nodes)
+            nodes.append(None)
+            nodes[me] = (walk(t[0]), walk(t[1]))
+            return ("n", me)
+
+        walk(tree)
+        for nt in itertools.product(range(N), repeat=len(nodes)):
+            for pt in itertools.product(range(P), repeat=n):
+                fixed = root[nt[0]] * math.prod(emit[i, pt[i]] for i in range(n))
+                facs = []  # (matrix, A, child, value)
+                for idx, (lc, rc) in enumerate(nodes):
+                    A = nt[idx]
+                    lsym = nt[lc[1]] if lc[0] == "n" else N + pt[lc[1]]
+                    rsym = nt[rc[1]] if rc[0] == "n" else N + pt[rc[1]]
+                    facs.append((dL, A, lsym, L[A, lsym]))
+                    facs.append((dR, A, rsym, R[A, rsym]))
+                for u, (dst, A, c, _) in enumerate(facs):
+                    dst[A, c] += fixed * math.prod(f[3] for v, f in enumerate(facs) if v != u)
+    return dL, dR
+
+
 def dense_inside(log_root, L, R, e):
     """Inside pass over the full rule tensor T[A,B,C] = L[A,B] R[A,C], probability space, no factoring."""
     n, P = e.shape
@@ -234,6 +268,8 @@ def test_zero_probability_guards():
     assert O.inside_sentence(lr, L1, R, e)[0] == pytest.approx(math.log(Z), rel=1e-12)
     out = O.inside_backward_sentence(lr, L1, R, e)
     assert all(np.all(np.isfinite(x)) for x in out[1:])
+    dL, dR = brute_force_derivatives(lr, L1, R, e)
+    assert np.allclose(out[1], dL / Z, rtol=1e-10, atol=1e-14) and np.allclose(out[2], dR / Z, rtol=1e-10, atol=1e-14)
 
 
 # ----------------------------------------------------------------------------- gradients
@@ -247,6 +283,43 @@ def test_gradients_are_expected_counts_from_enumeration(N, P, n):
     assert np.allclose(R * gR, cR / Z, rtol=1e-11, atol=1e-14)
     assert np.allclose(gr, c_root / Z, rtol=1e-11)
     assert np.allclose(ge, c_emit / Z, rtol=1e-11)
+
+
+@pytest.mark.parametrize("which,block", [("L", "pre"), ("L", "non"), ("R", "pre"), ("R", "non")])
+def test_derivative_at_dead_rule_blocks(which, block):
+    """One parent has a whole column block of L (or R) equal to zero, so its projection eta (zeta) is zero on every
+    span of that kind.  grad_L is still the derivative with respect to the matrix entry: the derivative of the
+    polynomial Z divided by Z (enumeration, the factor left out), which a one-sided difference of log Z reproduces.
+    The chain rule through a = log eta alone would give 0 there."""
+    rng = np.random.default_rng(77)
+    N, P, n = 3, 2, 4
+    lr, L, R, e = random_grammar(rng, N, P, n, normalised=False)
+    Wm = L if which == "L" else R
+    A = 1
+    cols = slice(N, N + P) if block == "pre" else slice(0, N)
+    Wm[A, cols] = 0.0
+    Z = brute_force(lr, L, R, e)[0]
+    assert Z > 0
+    dL, dR = brute_force_derivatives(lr, L, R, e)
+    lz, gL, gR, gr, ge = O.inside_backward_sentence(lr, L, R, e)
+    assert lz == pytest.approx(math.log(Z), rel=1e-12)
+    assert np.allclose(gL, dL / Z, rtol=1e-10, atol=1e-14)
+    assert np.allclose(gR, dR / Z, rtol=1e-10, atol=1e-14)
+    G = gL if which == "L" else gR
+    assert np.all(G[A, cols] > 0), "the dead block's derivative must not vanish"
+    # one-sided (the entry cannot go below zero), second-order difference of the oracle's own forward pass
+    for c in range(cols.start, cols.stop):
+        h = 2e-6
+        f = [lz]
+        for m in (1, 2):
+            Lh, Rh = L.copy(), R.copy()
+            (Lh if which == "L" else Rh)[A, c] += m * h
+            f.append(O.inside_sentence(lr, Lh, Rh, e)[0])
+        num = (-3 * f[0] + 4 * f[1] - f[2]) / (2 * h)
+        assert G[A, c] == pytest.approx(num, rel=2e-5)
+    # upstream weight, also a negative one
+    out = O.inside_backward_sentence(lr, L, R, e, -1.5)
+    assert np.allclose(out[1], -1.5 * gL, rtol=1e-13) and np.allclose(out[4], -1.5 * ge, rtol=1e-13)
 
 
 def test_gradients_match_central_finite_differences():
