@@ -203,7 +203,9 @@ int spcfg_span_marginals(const spcfg_config* cfg, const int32_t* lengths, int32_
  * Minimum-Bayes-risk tree (the parse used to score a grammar as an unsupervised parser, Sec. 4 "Evaluation"):
  * the binary bracketing of each sentence that maximises the sum of span_post over its spans of width >= 2,
  * by CKY over split points; the smallest split point wins ties.
- *   span_post  dev [B x n_max x n_max], layout as written by spcfg_span_marginals (any non-negative scores)
+ *   span_post  dev [B x n_max x n_max], layout as written by spcfg_span_marginals (any non-negative scores; with
+ *              -inf or NaN scores the result is still a valid bracketing - a span whose candidates are all -inf
+ *              or NaN takes its smallest split point - and tree_score is -inf or NaN)
  *   lengths    host [B], 2 <= lengths[b] <= n_max <= 1024;  B <= 960
  *   tree_spans dev [B x (n_max - 1) x 2] int32: the lengths[b] - 1 spans (i, j) of width >= 2 in pre-order
  *              (parent, left subtree, right subtree), then -1 padding

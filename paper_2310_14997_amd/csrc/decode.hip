@@ -50,6 +50,9 @@ k_mbr_decode(LenArg la, int n_max, int use_lds, const float* __restrict__ mu, fl
         const int ok = __shfl_xor(bk, o, 64);
         if (ov > bv || (ov == bv && ok < bk)) { bv = ov; bk = ok; }
       }
+      // No candidate compares greater than -inf when every sum is -inf or NaN (scores are the caller's data): the
+      // split then defaults to the smallest one, so the table only ever holds split points inside the span.
+      if (bk <= i || bk >= j) bk = i + 1;
       if (lane == 0) {
         const float v = m[(int64_t)i * n_max + (j - 1)] + bv;
         byS[(int64_t)i * n_max + (j - 1)] = v;
@@ -67,7 +70,7 @@ k_mbr_decode(LenArg la, int n_max, int use_lds, const float* __restrict__ mu, fl
     tree_score[b] = byS[n - 1];
     int sp = 0, cnt = 0;
     stack[0] = 0; stack[1] = n; sp = 1;
-    while (sp > 0) {
+    while (sp > 0 && cnt < n - 1) {  // a binary tree over n words has n - 1 spans of width >= 2
       --sp;
       const int i = stack[2 * sp], j = stack[2 * sp + 1];
       out[2 * cnt] = i; out[2 * cnt + 1] = j; ++cnt;

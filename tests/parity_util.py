@@ -40,3 +40,48 @@ def check_all(got, ref, logz_rtol=LOGZ_RTOL_FP32, grad_rtol=GRAD_RTOL_FP32):
     for k in ("grad_log_root", "grad_log_emit", "grad_L", "grad_R"):
         stats[k] = check_grad(k, got[k], ref[k], grad_rtol)
     return stats
+
+
+def oracle_batch_parallel(d, grad_logZ=None, workers=4, sentences=None, timeout=900):
+    """oracle.spcfg_oracle.inside_backward over a whole batch (or the listed sentences), the sentences dealt to a
+    few worker processes (tests/oracle_worker.py: fresh interpreters that import numpy and the oracle only and
+    never touch the GPU; inputs and results travel as .npz files in a temporary directory).
+    Same result layout as the oracle's batched call; sentences that were not asked for keep NaN in logZ."""
+    import os
+    import subprocess
+    import sys
+    import tempfile
+    lengths = np.asarray(d["lengths"])
+    B, n_max, P = d["log_emit"].shape
+    N = d["L"].shape[0]
+    todo = list(range(B)) if sentences is None else list(sentences)
+    # longest first, dealt round-robin: the cost of a sentence grows with the cube of its length
+    order = sorted(todo, key=lambda b: -int(lengths[b]))
+    chunks = [order[w::workers] for w in range(workers) if order[w::workers]]
+    out = dict(logZ=np.full(B, np.nan), grad_L=np.zeros((N, N + P)), grad_R=np.zeros((N, N + P)),
+               grad_log_root=np.zeros(N), grad_log_emit=np.zeros((B, n_max, P)))
+    here = os.path.dirname(os.path.abspath(__file__))
+    with tempfile.TemporaryDirectory() as tmp:
+        inp = os.path.join(tmp, "in.npz")
+        np.savez(inp, log_root=d["log_root"], L=d["L"], R=d["R"], log_emit=d["log_emit"], lengths=lengths,
+                 grad_logZ=np.ones(B) if grad_logZ is None else np.asarray(grad_logZ, np.float64))
+        procs = []
+        # the workers share the host's cores: left at the default, every worker's BLAS would start a thread per core
+        threads = str(max(1, min(os.cpu_count() or 1, 16) // len(chunks)))
+        env = dict(os.environ, OMP_NUM_THREADS=threads, OPENBLAS_NUM_THREADS=threads, MKL_NUM_THREADS=threads)
+        for w, c in enumerate(chunks):
+            outp = os.path.join(tmp, f"out{w}.npz")
+            cmd = [sys.executable, os.path.join(here, "oracle_worker.py"), inp, outp] + [str(b) for b in c]
+            procs.append((subprocess.Popen(cmd, env=env), outp, c))
+        for proc, outp, c in procs:
+            rc = proc.wait(timeout=timeout)
+            assert rc == 0, f"oracle worker failed with exit code {rc}"
+            with np.load(outp) as res:
+                for t, b in enumerate(c):
+                    n = int(lengths[b])
+                    out["logZ"][b] = res["logZ"][t]
+                    out["grad_log_emit"][b, :n] = res[f"ge{t}"]
+                out["grad_L"] += res["grad_L"]
+                out["grad_R"] += res["grad_R"]
+                out["grad_log_root"] += res["grad_log_root"]
+    return out

@@ -129,6 +129,38 @@ def test_mbr_decode_is_bit_exact_on_exactly_representable_scores(lengths):
         assert np.all(spans[b, n - 1:] == -1)
 
 
+def test_mbr_decode_stays_in_bounds_on_non_finite_scores():
+    """Scores are caller data: -inf entries (spans ruled out) decode exactly as in the oracle, also where every
+    candidate of a span is -inf; NaN entries still give a valid bracketing and a NaN score.  No split point outside
+    its span is ever stored or followed."""
+    lengths = [9, 2, 17, 40, 95]
+    rng = np.random.default_rng(4321)
+    B, n_max = len(lengths), max(lengths)
+    mu = rng.integers(0, 65, size=(B, n_max, n_max)).astype(np.float64) / 64.0
+    mu[rng.random(mu.shape) < 0.4] = -np.inf
+    mu[3] = -np.inf                                  # every span of sentence 3 ruled out
+    print("case decode -inf", lengths, flush=True)
+    spans, score = decode_on_gpu(mu, lengths)
+    for b, n in enumerate(lengths):
+        ref_score, ref_spans = D.mbr_decode(to_oracle_layout(mu[b], n), n)
+        got = [tuple(x) for x in spans[b, : n - 1]]
+        assert D.is_binary_tree(got, n)
+        assert got == ref_spans, f"sentence {b} (n={n})"
+        assert score[b] == ref_score
+        assert np.all(spans[b, n - 1:] == -1)
+    mu2 = rng.integers(0, 65, size=(B, n_max, n_max)).astype(np.float64) / 64.0
+    mu2[rng.random(mu2.shape) < 0.2] = np.nan
+    mu2[1] = np.nan
+    mu2[4] = np.nan
+    print("case decode NaN", lengths, flush=True)
+    spans, score = decode_on_gpu(mu2, lengths)
+    for b, n in enumerate(lengths):
+        got = [tuple(x) for x in spans[b, : n - 1]]
+        assert D.is_binary_tree(got, n), f"sentence {b} (n={n})"
+        assert np.all(spans[b, n - 1:] == -1)
+    assert np.isnan(score[1]) and np.isnan(score[4])
+
+
 def test_marginals_then_decode_end_to_end():
     d = synth.make_inputs("small", pad_value=np.nan, B=6, N=96, P=80)
     print("case end to end", flush=True)
