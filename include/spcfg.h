@@ -40,7 +40,8 @@ enum {
   SPCFG_ERR_LENGTH = -3,      /* some lengths[b] < 2 or > n_max (a tree needs the rule S -> A, A -> B C) */
   SPCFG_ERR_WORKSPACE = -4,   /* workspace pointer misaligned or workspace_bytes too small            */
   SPCFG_ERR_UNSUPPORTED = -5, /* precision / flag combination not implemented                         */
-  SPCFG_ERR_HIP = -6          /* a HIP runtime call failed (see spcfg_last_hip_error)                 */
+  SPCFG_ERR_HIP = -6,         /* a HIP runtime call failed (see spcfg_last_hip_error)                 */
+  SPCFG_ERR_STATIC_CAPACITY = -7 /* spcfg_inside_static: the batch needs more than SPCFG_STATIC_SCRATCH_BYTES  */
 };
 
 enum { SPCFG_PRECISION_FP32 = 0, SPCFG_PRECISION_BF16 = 1 };
@@ -113,6 +114,25 @@ int spcfg_inside_backward(const spcfg_config* cfg, const float* log_root, const 
                           const float* log_emit, const int32_t* lengths, int32_t B, int32_t n_max,
                           const float* grad_logZ, float* grad_L, float* grad_R, float* grad_log_root,
                           float* grad_log_emit, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * spcfg_inside for callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same kernels, with the whole workspace (chart,
+ * exponents, packed panels, partial tiles and arrival counters of the projection products) in a static device array
+ * of SPCFG_STATIC_SCRATCH_BYTES that lives in the library's code object.  Nothing is allocated or freed, by this
+ * call or by anything it calls.  Arguments as for spcfg_inside.
+ *   - A batch whose workspace need exceeds the array (see spcfg_workspace_bytes_for; the static layout keeps 56 MiB
+ *     less partial-tile scratch than that figure) is refused with SPCFG_ERR_STATIC_CAPACITY before anything is
+ *     launched.  Small grammars fit (N = P = 512 with a few hundred words per batch), the headline one does not.
+ *   - Every GPU holds its own copy of the array until the process ends; the address is looked up on the first call
+ *     on a device (that device current).  All calls on one GPU share it and it keeps the last call's contents
+ *     (whatever has to start at zero is cleared by the call's first kernels): calls that overlap on one GPU, on
+ *     different streams or from different threads, race.  No backward call can follow: the chart is not the caller's.
+ */
+#define SPCFG_STATIC_SCRATCH_BYTES (64u << 20)
+int spcfg_inside_static(const spcfg_config* cfg, const float* log_root, const float* L, const float* R,
+                        const float* log_emit, const int32_t* lengths, int32_t B, int32_t n_max, float* logZ,
+                        void* hip_stream);
 
 /* spcfg_inside followed by spcfg_inside_backward on the same stream (one call for the fwd+bwd step). */
 int spcfg_inside_forward_backward(const spcfg_config* cfg, const float* log_root, const float* L,

@@ -46,6 +46,7 @@ def load():
     lib.spcfg_workspace_bytes.argtypes = [cfgp, C.POINTER(sz)]
     lib.spcfg_workspace_bytes_for.argtypes = [cfgp, vp, i32, i32, C.POINTER(sz)]
     lib.spcfg_inside.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.spcfg_inside_static.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
     lib.spcfg_inside_backward.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.spcfg_inside_forward_backward.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp,
                                                   vp, sz, vp]
@@ -64,7 +65,7 @@ def load():
     lib.spcfg_profile_class_name.argtypes = [C.c_int]
     lib.spcfg_profile_class_name.restype = C.c_char_p
     for name in ("spcfg_workspace_bytes", "spcfg_workspace_bytes_for", "spcfg_inside", "spcfg_inside_backward",
-                 "spcfg_inside_forward_backward", "spcfg_profile_enable", "spcfg_profile_read"):
+                 "spcfg_inside_forward_backward", "spcfg_inside_static", "spcfg_profile_enable", "spcfg_profile_read"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -142,6 +143,19 @@ def spcfg_inside(cfg, log_root, L, R, log_emit, lengths, logZ, workspace):
     _check(load().spcfg_inside(C.byref(cfg), _dev(log_root, "log_root", rs), _dev(L, "L", gs),
                                _dev(R, "R", gs), _dev(log_emit, "log_emit"), lptr, B, n_max,
                                _dev(logZ, "logZ", (B,)), wp, wb, _stream()))
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def spcfg_inside_static(cfg, log_root, L, R, log_emit, lengths, logZ):
+    """spcfg_inside with the workspace in the library's static device array: nothing is allocated (small batches only)."""
+    B, n_max, P = log_emit.shape
+    N, M, rs, gs = _grammar_shapes(cfg, L, B)
+    arr, lptr = _lengths_array(lengths)
+    _check(load().spcfg_inside_static(C.byref(cfg), _dev(log_root, "log_root", rs), _dev(L, "L", gs),
+                                      _dev(R, "R", gs), _dev(log_emit, "log_emit"), lptr, B, n_max,
+                                      _dev(logZ, "logZ", (B,)), _stream()))
 
 
 def spcfg_inside_backward(cfg, log_root, L, R, log_emit, lengths, grad_logZ, grad_L, grad_R, grad_log_root,

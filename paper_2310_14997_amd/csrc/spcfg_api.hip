@@ -3,6 +3,7 @@
 // per-kernel-class timing with HIP events.
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "spcfg_internal.h"
@@ -32,8 +33,10 @@ int check_cfg(const spcfg_config* c) {
 }
 
 // Byte layout of the workspace for a batch with S1 leaf rows and S2 rows of width >= 2.
-Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int bf16, int per_sentence) {
+Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int bf16, int per_sentence,
+                   int gemm_wgs = kGemmWgs) {
   Layout ly{};
+  ly.gemm_wgs = gemm_wgs;
   ly.N = N; ly.P = P; ly.B = B; ly.n_max = n_max; ly.bf16 = bf16;
   ly.G = per_sentence ? B : 1;
   ly.S1pad = (S1 + 63) / 64 * 64; ly.S2pad = (S2 + 63) / 64 * 64;
@@ -69,7 +72,7 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
     if (g > ly.n_counters) ly.n_counters = g;
   }
   ly.counters = take(i4 * (size_t)ly.n_counters);
-  ly.partial = take(gemm_nt_partial_bytes(kGemmWgs));
+  ly.partial = take(gemm_nt_partial_bytes(gemm_wgs));
   const size_t w4 = bf16 ? 2 : 4;  // bytes per packed weight
   ly.Wn = take(w4 * 2 * (size_t)ly.Np * ly.Np * ly.G);
   ly.Wp = take(w4 * 2 * (size_t)ly.Np * ly.Pp * ly.G);
@@ -113,7 +116,8 @@ Ptrs resolve(const Layout& ly, void* ws) {
   return p;
 }
 
-int make_plan(const spcfg_config* cfg, const int32_t* lengths, int B, int n_max, Plan* plan, Layout* ly) {
+int make_plan(const spcfg_config* cfg, const int32_t* lengths, int B, int n_max, Plan* plan, Layout* ly,
+              int gemm_wgs = kGemmWgs) {
   if (!lengths) return SPCFG_ERR_ARG;
   if (B < 1 || B > cfg->max_B || n_max < 2 || n_max > cfg->max_n) return SPCFG_ERR_SHAPE;
   for (int b = 0; b < B; ++b)
@@ -132,7 +136,7 @@ int make_plan(const spcfg_config* cfg, const int32_t* lengths, int B, int n_max,
   const int64_t S1 = plan->cnt[1], Sall = run;
   if (Sall >= (int64_t)1 << 30) return SPCFG_ERR_SHAPE;
   *ly = make_layout(cfg->N, cfg->P, B, n_max, S1, Sall - S1, cfg->precision == SPCFG_PRECISION_BF16,
-                    (cfg->flags & SPCFG_FLAG_PER_SENTENCE_GRAMMAR) != 0);
+                    (cfg->flags & SPCFG_FLAG_PER_SENTENCE_GRAMMAR) != 0, gemm_wgs);
   return SPCFG_OK;
 }
 
@@ -259,7 +263,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
   {  // width 1: [eta | zeta] = [L_P ; R_P] * emission vector
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.P * ly.S1);
     NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.leafE; a.lda = Pp; a.Bm = p.Wp; a.ldb = Pp; a.C = p.HZ; a.ldc = 2 * Np;
     if (ly.bf16) { a.A = p.leafEb; a.a_bf16 = 1; }
     a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
@@ -277,7 +281,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     if (w == n_max) break;  // every span of the largest width is a root span: never a child, not projected
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.N * rows);
     NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.a_bf16 = 1; }
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
@@ -331,7 +335,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       launch_split_bwd(ly, p, w, row0, rows, st);
     }
     NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.UV + row0 * 2 * Np; a.lda = 2 * Np; a.K = (int)(2 * Np); a.rows = (int)rows;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np; a.a_bf16 = 1; }
     if (w >= 2) {
@@ -381,7 +385,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
     } else if (!ly.bf16) {
       TnArgs t{};
       t.fp32_mfma = fp32_mfma;
-      t.partial = p.partial; t.counters = p.counters; t.max_wgs = kGemmWgs; t.n_counters = ly.n_counters;
+      t.partial = p.partial; t.counters = p.counters; t.max_wgs = ly.gemm_wgs; t.n_counters = ly.n_counters;
       t.Np = (int)Np; t.N = ly.N; t.gL = grad_L; t.gR = grad_R; t.ldg = ly.N + ly.P; t.accumulate = acc;
       t.A = p.UV + ly.S1 * 2 * Np; t.lda = 2 * Np; t.Bm = p.T; t.ldb = Np; t.sc = p.gsc + ly.S1; t.S = ly.S2;
       t.cols = ly.N; t.col0 = 0;
@@ -395,7 +399,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       launch_transpose_bf16(p.UV, 2 * Np, (int)(2 * Np), p.gsc, ly.S1, ly.S1pad, p.UVt_p, st);
       launch_transpose_bf16(p.leafE, Pp, (int)Pp, nullptr, ly.S1, ly.S1pad, p.Et, st);
       NtArgs a{};
-      a.partial = p.partial; a.counters = p.counters; a.max_wgs = kGemmWgs; a.n_counters = ly.n_counters; a.a_bf16 = 1; a.b_bf16 = 1;
+      a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.a_bf16 = 1; a.b_bf16 = 1;
       a.epilogue = NT_EPI_GRAD; a.gL = grad_L; a.gR = grad_R; a.ldg = ly.N + ly.P; a.Np = (int)Np; a.Nvalid = ly.N;
       a.accumulate = acc; a.rows = (int)(2 * Np);
       a.A = p.UVt_n; a.lda = ly.S2pad; a.Bm = p.Tt; a.ldb = ly.S2pad; a.K = (int)ly.S2pad; a.cols = ly.N; a.col0 = 0;
@@ -412,7 +416,58 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
 
 using namespace spcfg;
 
+// ---- static device scratch for the entry point that allocates nothing ---------------------------------------
+// One array per GPU (every device that loads the library's code object holds its own copy at its own address).
+// In host code the array's name only stands for the symbol: the device address comes from hipGetSymbolAddress,
+// once per device, and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[SPCFG_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kStaticGemmWgs = 64;   // partial-tile scratch of the static buffer: 2 * 64 slots of 64 KiB = 8 MiB
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+std::mutex g_scratch_mutex;
+
+// Device address of this device's copy of `scratch` (looked up on the first call on a device, with that device
+// current), or nullptr with the HIP error text recorded.
+void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    snprintf(g_hip_err, sizeof(g_hip_err), "no current HIP device below %d", kMaxDevices);
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      snprintf(g_hip_err, sizeof(g_hip_err), "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
 extern "C" {
+
+int spcfg_inside_static(const spcfg_config* cfg, const float* log_root, const float* L, const float* R,
+                        const float* log_emit, const int32_t* lengths, int32_t B, int32_t n_max, float* logZ,
+                        void* hip_stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (!log_root || !L || !R || !log_emit || !logZ) return SPCFG_ERR_ARG;
+  Plan plan; Layout ly;
+  rc = make_plan(cfg, lengths, B, n_max, &plan, &ly, kStaticGemmWgs);
+  if (rc) return rc;
+  if (ly.total > (size_t)SPCFG_STATIC_SCRATCH_BYTES) return SPCFG_ERR_STATIC_CAPACITY;
+  void* ws = static_scratch();
+  if (!ws) return SPCFG_ERR_HIP;
+  return forward(cfg, plan, ly, resolve(ly, ws), log_root, L, R, log_emit, logZ, (hipStream_t)hip_stream);
+}
 
 int spcfg_workspace_bytes(const spcfg_config* cfg, size_t* out_bytes) {
   int rc = check_cfg(cfg);
@@ -515,6 +570,7 @@ const char* spcfg_strerror(int code) {
     case SPCFG_ERR_WORKSPACE: return "workspace misaligned or too small";
     case SPCFG_ERR_UNSUPPORTED: return "precision or flag not supported";
     case SPCFG_ERR_HIP: return "HIP runtime error";
+    case SPCFG_ERR_STATIC_CAPACITY: return "batch needs more scratch than the static device buffer of spcfg_inside_static holds";
     default: return "unknown error code";
   }
 }

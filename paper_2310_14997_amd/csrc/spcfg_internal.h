@@ -46,6 +46,7 @@ struct Layout {
   size_t Tb, UVb, leafEb;       // bf16 mode only: bf16 copies of T, UV, leafE, written by their producers
   size_t sentrows, sentoff;     // per-sentence grammars only: rows of width >= 2 listed sentence by sentence, first entry of each
   int n_counters;
+  int gemm_wgs;          // workgroups the partial-tile scratch is sized for (kGemmWgs, fewer for the static scratch)
   size_t total;
 };
 

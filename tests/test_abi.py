@@ -90,6 +90,21 @@ def test_null_pointers_are_rejected_before_any_launch():
     assert rc == -4  # misaligned
 
 
+def test_static_scratch_entry_point_checks_its_arguments_on_the_host():
+    """spcfg_inside_static refuses bad arguments and batches beyond its static buffer before anything is launched."""
+    lib = bd.load()
+    fake = C.c_void_p(4096)
+    cfg = bd.make_config(8, 8, 2, 6)
+    lens = np.array([3, 4], dtype=np.int32)
+    assert lib.spcfg_inside_static(C.byref(cfg), None, fake, fake, fake, lens.ctypes.data, 2, 6, fake, None) == -1
+    bad = np.array([1, 4], dtype=np.int32)
+    assert lib.spcfg_inside_static(C.byref(cfg), fake, fake, fake, fake, bad.ctypes.data, 2, 6, fake, None) == -3
+    big = bd.make_config(2048, 2048, 64, 40)
+    full = np.full(64, 40, dtype=np.int32)
+    assert lib.spcfg_inside_static(C.byref(big), fake, fake, fake, fake, full.ctypes.data, 64, 40, fake, None) == -7
+    assert b"static" in lib.spcfg_strerror(-7)
+
+
 def test_decode_argument_checks_run_before_any_launch():
     lib = bd.load()
     fake = C.c_void_p(4096)
