@@ -1,6 +1,8 @@
 // Span plan, weight packing, leaf preparation, split-point reductions (forward and reverse) and root
 // reductions for the simple-PCFG inside pass on gfx950.  All kernels are deterministic (no atomics).
-#include "spcfg_internal.h"
+#include <type_traits>
+
+#include "gemm_nt_common.h"
 
 namespace spcfg {
 
@@ -61,6 +63,23 @@ __device__ __forceinline__ void store_bf16x4(void* base, int64_t idx, float4 v) 
   bf16x4_t r;
   r[0] = (__bf16)v.x; r[1] = (__bf16)v.y; r[2] = (__bf16)v.z; r[3] = (__bf16)v.w;
   *reinterpret_cast<bf16x4_t*>(static_cast<__bf16*>(base) + idx) = r;
+}
+
+// Operand planes of four consecutive values for the projection products: with three planes the exact cut
+// x = hi + mid + lo into bf16 pieces (nt::Split3), with one plane the bf16 rounding.  Plane p starts at
+// base + p * plane_stride elements.
+__device__ __forceinline__ void store_planes4(void* base, int planes, int64_t plane_stride, int64_t idx, float4 v) {
+  if (planes == 3) {
+    unsigned h0, m0, l0, h1, m1, l1;
+    nt::Split3::cut2(v.x, v.y, h0, m0, l0);
+    nt::Split3::cut2(v.z, v.w, h1, m1, l1);
+    uint16_t* b = static_cast<uint16_t*>(base) + idx;
+    *reinterpret_cast<uint2*>(b) = uint2{h0, h1};
+    *reinterpret_cast<uint2*>(b + plane_stride) = uint2{m0, m1};
+    *reinterpret_cast<uint2*>(b + 2 * plane_stride) = uint2{l0, l1};
+  } else {
+    store_bf16x4(base, idx, v);
+  }
 }
 
 // 2^d as a float for an integer d (0 below the fp32 range); exact.
@@ -193,16 +212,28 @@ __global__ void k_plan_sentrows(int B, int stride, const int32_t* __restrict__ l
 // Stacks [L;R] (Sec. 3.2, kernel fusion: one matrix product for both projections) into zero-padded,
 // K-contiguous operands: Wn [2Np x Np] / Wp [2Np x Pp] for the forward products and their transposes
 // Wtn [Np x 2Np] / Wtp [Pp x 2Np] for the reverse products.
+// Element store of a packed panel: OutT float or __bf16 writes the value; uint16_t writes the three bf16 pieces of
+// the exact cut (nt::Split3) into three planes `stride` elements apart.
+template <typename OutT> __device__ __forceinline__ void put_w(OutT* w, int64_t, int64_t at, float v) { w[at] = (OutT)v; }
+__device__ __forceinline__ void put_w(uint16_t* w, int64_t stride, int64_t at, float v) {
+  unsigned h, m, l;
+  nt::Split3::cut2(v, 0.0f, h, m, l);
+  w[at] = (uint16_t)h; w[stride + at] = (uint16_t)m; w[2 * stride + at] = (uint16_t)l;
+}
+// OutT = uint16_t: three bf16 planes per panel (plane strides 2Np*Np resp. 2Np*Pp elements; a grammar's panel set
+// is then three times as long)
 template <typename OutT>
 __global__ void k_pack_weights(const float* __restrict__ L, const float* __restrict__ R, int N, int P, int Np,
                                int Pp, OutT* __restrict__ Wn, OutT* __restrict__ Wp, OutT* __restrict__ Wtn,
                                OutT* __restrict__ Wtp) {
+  constexpr int NPL = std::is_same<OutT, uint16_t>::value ? 3 : 1;
+  const int64_t sn = 2 * (int64_t)Np * Np, sp = 2 * (int64_t)Np * Pp;
   __shared__ float tile[32][33];
   const int M = N + P;
   const int gi = blockIdx.z >> 1, lr = blockIdx.z & 1;  // grammar, left / right factor
   const float* src = (lr ? R : L) + (int64_t)gi * N * M;
-  Wn += (int64_t)gi * 2 * Np * Np; Wtn += (int64_t)gi * 2 * Np * Np;
-  Wp += (int64_t)gi * 2 * Np * Pp; Wtp += (int64_t)gi * 2 * Np * Pp;
+  Wn += (int64_t)gi * NPL * sn; Wtn += (int64_t)gi * NPL * sn;
+  Wp += (int64_t)gi * NPL * sp; Wtp += (int64_t)gi * NPL * sp;
   const int half = lr * Np;
   const int c0 = blockIdx.x * 32;  // padded column: [0,Np) nonterminal part, [Np, Np+Pp) preterminal part
   const int a0 = blockIdx.y * 32;
@@ -215,14 +246,14 @@ __global__ void k_pack_weights(const float* __restrict__ L, const float* __restr
     float v = 0.0f;
     if (a < N && c < (ppart ? P : N)) v = src[(int64_t)a * M + (ppart ? N + c : c)];
     tile[ty + 8 * q][tx] = v;
-    if (ppart) Wp[(int64_t)(half + a) * Pp + c] = (OutT)v; else Wn[(int64_t)(half + a) * Np + c] = (OutT)v;
+    if (ppart) put_w(Wp, sp, (int64_t)(half + a) * Pp + c, v); else put_w(Wn, sn, (int64_t)(half + a) * Np + c, v);
   }
   __syncthreads();
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int c = cc0 + ty + 8 * q, a = a0 + tx;
     const float v = tile[tx][ty + 8 * q];
-    if (ppart) Wtp[(int64_t)c * (2 * Np) + half + a] = (OutT)v; else Wtn[(int64_t)c * (2 * Np) + half + a] = (OutT)v;
+    if (ppart) put_w(Wtp, sp, (int64_t)c * (2 * Np) + half + a, v); else put_w(Wtn, sn, (int64_t)c * (2 * Np) + half + a, v);
   }
 }
 
@@ -254,7 +285,8 @@ __global__ void k_transpose_bf16(const float* __restrict__ X, int64_t ldx, const
 __global__ void k_leaf_prep(const float* __restrict__ log_emit, int P, int Pp, int n_max,
                             const int32_t* __restrict__ row_b, const int32_t* __restrict__ row_i,
                             float* __restrict__ leafE, float* __restrict__ xs, int32_t* __restrict__ mexp,
-                            uint32_t* __restrict__ tmaxb, __bf16* __restrict__ leafEb) {
+                            uint32_t* __restrict__ tmaxb, uint16_t* __restrict__ leafEb, int planes,
+                            int64_t plane_stride) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   const float* e = log_emit + ((int64_t)row_b[r] * n_max + row_i[r]) * P;
@@ -267,7 +299,10 @@ __global__ void k_leaf_prep(const float* __restrict__ log_emit, int P, int Pp, i
   for (int t = threadIdx.x; t < Pp; t += blockDim.x) {
     const float v = (t < P && !dead) ? expf(e[t] - x) : 0.0f;
     out[t] = v;
-    if (leafEb) leafEb[(int64_t)r * Pp + t] = (__bf16)v;
+    if (leafEb) {
+      if (planes == 3) put_w(leafEb, plane_stride, (int64_t)r * Pp + t, v);
+      else reinterpret_cast<__bf16*>(leafEb)[(int64_t)r * Pp + t] = (__bf16)v;
+    }
   }
   if (threadIdx.x == 0) {
     xs[r] = x;
@@ -293,7 +328,8 @@ __global__ void __launch_bounds__(64)
 k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const int32_t* __restrict__ lens,
             const int32_t* __restrict__ rowtab, const int32_t* __restrict__ row_b,
             const int32_t* __restrict__ row_i, const float* __restrict__ HZ,
-            float* __restrict__ T, int32_t* __restrict__ mexp, uint32_t* __restrict__ tmaxb, void* __restrict__ Tb) {
+            float* __restrict__ T, int32_t* __restrict__ mexp, uint32_t* __restrict__ tmaxb, void* __restrict__ Tb,
+            int planes, int64_t plane_stride) {
   extern __shared__ __align__(16) unsigned char smem[];
   float* s_c = reinterpret_cast<float*>(smem);                 // [w-1]
   int32_t* s_l = reinterpret_cast<int32_t*>(s_c + (w - 1));    // [w-1] row of the left child
@@ -376,7 +412,7 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
     }
     if (kg == 0) {
       *reinterpret_cast<float4*>(T + (r - S1) * Np + a) = acc;
-      if (Tb) store_bf16x4(Tb, (r - S1) * Np + a, acc);
+      if (Tb) store_planes4(Tb, planes, plane_stride, (r - S1) * Np + a, acc);
     }
     tmax = fmaxf(fmaxf(acc.x, acc.y), fmaxf(acc.z, acc.w));
   }
@@ -431,7 +467,7 @@ __global__ void k_root_bwd(int N, int Np, int64_t S1, const int32_t* __restrict_
                            const int32_t* __restrict__ mexp, const uint32_t* __restrict__ tmaxb,
                            float* __restrict__ BH, float* __restrict__ UV, int32_t* __restrict__ uexp,
                            uint32_t* __restrict__ umaxb, float* __restrict__ gsc, int64_t root_stride,
-                           __bf16* __restrict__ UVb) {
+                           uint16_t* __restrict__ UVb, int planes, int64_t plane_stride) {
   const int b = blockIdx.x;
   log_root += b * root_stride;
   const int64_t r = rootrow[b];
@@ -447,8 +483,10 @@ __global__ void k_root_bwd(int N, int Np, int64_t S1, const int32_t* __restrict_
     uv[a] = 0.0f;
     uv[Np + a] = 0.0f;
     if (UVb) {
-      UVb[r * 2 * (int64_t)Np + a] = (__bf16)0.0f;
-      UVb[r * 2 * (int64_t)Np + Np + a] = (__bf16)0.0f;
+      for (int pl = 0; pl < planes; ++pl) {  // bf16 zero is the all-zero bit pattern
+        UVb[pl * plane_stride + r * 2 * (int64_t)Np + a] = 0;
+        UVb[pl * plane_stride + r * 2 * (int64_t)Np + Np + a] = 0;
+      }
     }
   }
   if (threadIdx.x == 0) {
@@ -499,7 +537,8 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
             const int32_t* __restrict__ row_i, const int32_t* __restrict__ rootmask,
             const float* __restrict__ HZ, const float* __restrict__ BH, const int32_t* __restrict__ mexp,
             const uint32_t* __restrict__ tmaxb, float* __restrict__ UV, int32_t* __restrict__ uexp,
-            uint32_t* __restrict__ umaxb, float* __restrict__ gsc, void* __restrict__ UVb) {
+            uint32_t* __restrict__ umaxb, float* __restrict__ gsc, void* __restrict__ UVb, int planes,
+            int64_t plane_stride) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x;
   const int64_t r = row0 + blockIdx.x;
@@ -588,8 +627,8 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
     *reinterpret_cast<float4*>(out + a) = u;
     *reinterpret_cast<float4*>(out + Np + a) = v;
     if (UVb) {
-      store_bf16x4(UVb, r * ld + a, u);
-      store_bf16x4(UVb, r * ld + Np + a, v);
+      store_planes4(UVb, planes, plane_stride, r * ld + a, u);
+      store_planes4(UVb, planes, plane_stride, r * ld + Np + a, v);
     }
     amax = fmaxf(fmaxf(fmaxf(fabsf(u.x), fabsf(u.y)), fmaxf(fabsf(u.z), fabsf(u.w))),
                  fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
@@ -688,7 +727,10 @@ void launch_plan_sentrows(const Layout& ly, const Ptrs& p, hipStream_t st) {
 
 void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const float* R, hipStream_t st) {
   dim3 grid((ly.Np + ly.Pp) / 32, ly.Np / 32, 2 * ly.G);
-  if (ly.bf16)
+  if (ly.planes == 3)
+    launch_k(k_pack_weights<uint16_t>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
+                       (uint16_t*)p.Wn, (uint16_t*)p.Wp, (uint16_t*)p.Wtn, (uint16_t*)p.Wtp);
+  else if (ly.bf16)
     launch_k(k_pack_weights<__bf16>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
                        (__bf16*)p.Wn, (__bf16*)p.Wp, (__bf16*)p.Wtn, (__bf16*)p.Wtp);
   else
@@ -704,7 +746,8 @@ void launch_transpose_bf16(const float* X, int64_t ldx, int cols, const float* s
 
 void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hipStream_t st) {
   launch_k(k_leaf_prep, dim3((unsigned)ly.S1), dim3(256), 0, st, log_emit, ly.P, ly.Pp, ly.n_max, p.row_b,
-                     p.row_i, p.leafE, p.xs, p.mexp, p.tmaxb, static_cast<__bf16*>(p.leafEb));
+                     p.row_i, p.leafE, p.xs, p.mexp, p.tmaxb, static_cast<uint16_t*>(p.leafEb), ly.planes,
+                     (int64_t)ly.S1 * ly.Pp);
 }
 
 void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
@@ -713,12 +756,12 @@ void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int6
   if (rows * chunks < 1024 && w - 1 >= 64) {  // fewer than one wavefront per SIMD, long chains of split points
     const dim3 grid((unsigned)rows, (unsigned)(ly.Np / 64));
     launch_k(k_split_fwd<4>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b, p.row_i, p.HZ,
-             p.T, p.mexp, p.tmaxb, p.Tb);
+             p.T, p.mexp, p.tmaxb, p.Tb, ly.planes, (int64_t)ly.S2 * ly.Np);
     return;
   }
   const dim3 grid((unsigned)rows, (unsigned)chunks);
   launch_k(k_split_fwd<1>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b, p.row_i, p.HZ,
-           p.T, p.mexp, p.tmaxb, p.Tb);
+           p.T, p.mexp, p.tmaxb, p.Tb, ly.planes, (int64_t)ly.S2 * ly.Np);
 }
 
 void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st) {
@@ -731,7 +774,8 @@ void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, con
                      float* grad_log_root, int accumulate, hipStream_t st) {
   launch_k(k_root_bwd, dim3(ly.B), dim3(256), 0, st, ly.N, ly.Np, ly.S1, p.rootrow, log_root, grad_logZ,
                      p.ztil, p.rmax, p.mexp, p.tmaxb, p.BH, p.UV, p.uexp, p.umaxb, p.gsc,
-                     (int64_t)(ly.G > 1 ? ly.N : 0), static_cast<__bf16*>(p.UVb));
+                     (int64_t)(ly.G > 1 ? ly.N : 0), static_cast<uint16_t*>(p.UVb), ly.planes,
+                     (int64_t)ly.Sall * 2 * ly.Np);
   launch_k(k_grad_log_root, dim3((ly.N + 255) / 256, ly.G > 1 ? ly.B : 1), dim3(256), 0, st, ly.B, ly.N,
                      ly.Np, ly.S1, p.rootrow, log_root, grad_logZ, p.ztil, p.rmax, p.T, p.tmaxb, grad_log_root,
                      accumulate, ly.G > 1 ? 1 : 0);
@@ -741,7 +785,8 @@ void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int6
   const size_t sh = (size_t)ly.n_max * 12;
   const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
   launch_k(k_split_bwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b,
-                     p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc, p.UVb);
+                     p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc, p.UVb, ly.planes,
+                     (int64_t)ly.Sall * 2 * ly.Np);
 }
 
 void launch_zero_pad_emit(const Layout& ly, const Ptrs& p, float* grad_log_emit, hipStream_t st) {

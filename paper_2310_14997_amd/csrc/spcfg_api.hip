@@ -33,10 +33,13 @@ int check_cfg(const spcfg_config* c) {
 }
 
 // Byte layout of the workspace for a batch with S1 leaf rows and S2 rows of width >= 2.
-Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int bf16, int per_sentence,
+Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int bf16, int per_sentence, int fp32_mfma,
                    int gemm_wgs = kGemmWgs) {
   Layout ly{};
   ly.gemm_wgs = gemm_wgs;
+  // operand planes for the projection products: the bf16 rounding in bf16 mode; in fp32 mode with a shared grammar
+  // the exact three-piece cut (the products then never cut operands themselves)
+  ly.planes = bf16 ? 1 : ((per_sentence && B > 1) || fp32_mfma ? 0 : 3);
   ly.N = N; ly.P = P; ly.B = B; ly.n_max = n_max; ly.bf16 = bf16;
   ly.G = per_sentence ? B : 1;
   ly.S1pad = (S1 + 63) / 64 * 64; ly.S2pad = (S2 + 63) / 64 * 64;
@@ -73,7 +76,7 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   }
   ly.counters = take(i4 * (size_t)ly.n_counters);
   ly.partial = take(gemm_nt_partial_bytes(gemm_wgs));
-  const size_t w4 = bf16 ? 2 : 4;  // bytes per packed weight
+  const size_t w4 = bf16 ? 2 : (ly.planes == 3 ? 6 : 4);  // bytes per packed weight
   ly.Wn = take(w4 * 2 * (size_t)ly.Np * ly.Np * ly.G);
   ly.Wp = take(w4 * 2 * (size_t)ly.Np * ly.Pp * ly.G);
   ly.Wtn = take(w4 * 2 * (size_t)ly.Np * ly.Np * ly.G);
@@ -84,9 +87,11 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
     ly.Tt = take(2 * (size_t)ly.Np * ly.S2pad);
     ly.UVt_p = take(2 * 2 * (size_t)ly.Np * ly.S1pad);
     ly.Et = take(2 * (size_t)ly.Pp * ly.S1pad);
-    ly.Tb = take(2 * (size_t)S2 * ly.Np);
-    ly.UVb = take(2 * (size_t)ly.Sall * 2 * ly.Np);
-    ly.leafEb = take(2 * (size_t)S1 * ly.Pp);
+  }
+  if (ly.planes > 0) {
+    ly.Tb = take(2 * (size_t)ly.planes * S2 * ly.Np);
+    ly.UVb = take(2 * (size_t)ly.planes * ly.Sall * 2 * ly.Np);
+    ly.leafEb = take(2 * (size_t)ly.planes * S1 * ly.Pp);
   }
   ly.leafE = take(f4 * (size_t)S1 * ly.Pp);
   ly.T = take(f4 * (size_t)S2 * ly.Np);
@@ -110,7 +115,7 @@ Ptrs resolve(const Layout& ly, void* ws) {
   p.UV = (float*)(b + ly.UV); p.BH = (float*)(b + ly.BH);
   p.partial = (float*)(b + ly.partial); p.counters = (int32_t*)(b + ly.counters);
   p.sentrows = (int32_t*)(b + ly.sentrows); p.sentoff = (int32_t*)(b + ly.sentoff);
-  p.Tb = ly.bf16 ? b + ly.Tb : nullptr; p.UVb = ly.bf16 ? b + ly.UVb : nullptr; p.leafEb = ly.bf16 ? b + ly.leafEb : nullptr;
+  p.Tb = ly.planes ? b + ly.Tb : nullptr; p.UVb = ly.planes ? b + ly.UVb : nullptr; p.leafEb = ly.planes ? b + ly.leafEb : nullptr;
   p.UVt_n = b + ly.UVt_n; p.Tt = b + ly.Tt; p.UVt_p = b + ly.UVt_p; p.Et = b + ly.Et;
   p.Wn = (float*)(b + ly.Wn); p.Wp = (float*)(b + ly.Wp); p.Wtn = (float*)(b + ly.Wtn); p.Wtp = (float*)(b + ly.Wtp);
   return p;
@@ -136,7 +141,8 @@ int make_plan(const spcfg_config* cfg, const int32_t* lengths, int B, int n_max,
   const int64_t S1 = plan->cnt[1], Sall = run;
   if (Sall >= (int64_t)1 << 30) return SPCFG_ERR_SHAPE;
   *ly = make_layout(cfg->N, cfg->P, B, n_max, S1, Sall - S1, cfg->precision == SPCFG_PRECISION_BF16,
-                    (cfg->flags & SPCFG_FLAG_PER_SENTENCE_GRAMMAR) != 0, gemm_wgs);
+                    (cfg->flags & SPCFG_FLAG_PER_SENTENCE_GRAMMAR) != 0, (cfg->flags & SPCFG_FLAG_FP32_MFMA) != 0,
+                    gemm_wgs);
   return SPCFG_OK;
 }
 
@@ -266,6 +272,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.leafE; a.lda = Pp; a.Bm = p.Wp; a.ldb = Pp; a.C = p.HZ; a.ldc = 2 * Np;
     if (ly.bf16) { a.A = p.leafEb; a.a_bf16 = 1; }
+    if (ly.planes == 3) { a.A = p.leafEb; a.planes3 = 1; a.a_plane = ly.S1 * Pp; a.b_plane = 2 * Np * Pp; }
     a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
     a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb;
     set_groups(a, plan, ly, p, 1, 0, 2 * Np * Pp);
@@ -284,6 +291,10 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.a_bf16 = 1; }
+    if (ly.planes == 3) {
+      a.A = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np;
+      a.planes3 = 1; a.a_plane = ly.S2 * Np; a.b_plane = 2 * Np * Np;
+    }
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
     a.rows = (int)rows; a.cols = (int)(2 * Np); a.K = (int)Np;
     a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb + row0;
@@ -338,6 +349,10 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
     a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.UV + row0 * 2 * Np; a.lda = 2 * Np; a.K = (int)(2 * Np); a.rows = (int)rows;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np; a.a_bf16 = 1; }
+    if (ly.planes == 3) {
+      a.A = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np;
+      a.planes3 = 1; a.a_plane = ly.Sall * 2 * Np; a.b_plane = 2 * Np * (w >= 2 ? Np : Pp);
+    }
     if (w >= 2) {
       Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.N * rows);
       a.Bm = p.Wtn; a.ldb = 2 * Np; a.C = p.BH + (row0 - ly.S1) * Np; a.ldc = Np; a.cols = (int)Np;
@@ -478,7 +493,8 @@ int spcfg_workspace_bytes(const spcfg_config* cfg, size_t* out_bytes) {
   if (Sall >= (int64_t)1 << 30) return SPCFG_ERR_SHAPE;
   *out_bytes = make_layout(cfg->N, cfg->P, cfg->max_B, cfg->max_n, S1, Sall - S1,
                            cfg->precision == SPCFG_PRECISION_BF16,
-                           (cfg->flags & SPCFG_FLAG_PER_SENTENCE_GRAMMAR) != 0).total;
+                           (cfg->flags & SPCFG_FLAG_PER_SENTENCE_GRAMMAR) != 0,
+                           (cfg->flags & SPCFG_FLAG_FP32_MFMA) != 0).total;
   return SPCFG_OK;
 }
 

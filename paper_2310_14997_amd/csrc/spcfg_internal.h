@@ -37,13 +37,16 @@ struct Layout {
   int N, P, Np, Pp, B, n_max;
   int G;                 // number of grammars: 1 (shared by the batch) or B (one per sentence)
   int bf16;              // projections with bf16 operands: packed weights are bf16, transposed bf16 copies for the rule gradients
+  int planes;            // bf16 planes that producers write beside every fp32 chart row for the projection products:
+                         // 0 none (fp32 operands are staged and cut in the kernel), 1 the bf16 rounding (bf16 mode),
+                         // 3 the exact cut hi + mid + lo of every fp32 value (fp32 mode, shared grammar)
   int64_t S1pad, S2pad;  // row counts rounded up to 64 (K of the bf16 rule-gradient product)
   int64_t S1, S2, Sall;  // leaf rows, rows of width >= 2, all rows
   // byte offsets into the workspace
   size_t lens, rowbase, row_b, row_i, rootmask, rootrow, mexp, uexp, tmaxb, umaxb, gsc, xs, ztil, rmax;
   size_t leafE, T, HZ, UV, BH, Wn, Wp, Wtn, Wtp, partial, counters;
   size_t UVt_n, Tt, UVt_p, Et;  // bf16 mode only
-  size_t Tb, UVb, leafEb;       // bf16 mode only: bf16 copies of T, UV, leafE, written by their producers
+  size_t Tb, UVb, leafEb;       // planes > 0: bf16 planes of T, UV, leafE ([planes][rows][cols]), written by their producers
   size_t sentrows, sentoff;     // per-sentence grammars only: rows of width >= 2 listed sentence by sentence, first entry of each
   int n_counters;
   int gemm_wgs;          // workgroups the partial-tile scratch is sized for (kGemmWgs, fewer for the static scratch)
@@ -56,7 +59,7 @@ struct Ptrs {  // device pointers resolved from a Layout
   float *gsc, *xs, *ztil, *rmax;
   float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp, *partial;  // W* hold bf16 data in bf16 mode
   void *UVt_n, *Tt, *UVt_p, *Et;
-  void *Tb, *UVb, *leafEb;  // null in fp32 mode
+  void *Tb, *UVb, *leafEb;  // null when the layout has no planes
   int32_t* counters;
   int32_t* sentrows; int32_t* sentoff;
 };
@@ -145,11 +148,16 @@ struct NtArgs {
   // column block each) and "prefix / middle / suffix rows" (reverse: the adjoint of zeta resp. eta is zero, half
   // of K is skipped) are contiguous ranges.
   int fp32_mfma;  // 1: fp32 matrix instructions instead of the split-bf16 scheme (fp32 operands only)
+  // planes3 = 1: both operands are given as three bf16 planes (the exact cut hi + mid + lo of every fp32 value,
+  // nt::Split3), written by their producers: A = [3][..][lda] with planes a_plane elements apart, Bm likewise with
+  // b_plane; A and Bm then point to bf16 data and the product runs in gemm_nt3.hip.
+  int planes3; int64_t a_plane, b_plane;
   int parts;
   int prt_row0[3], prt_rows[3], prt_c0[3], prt_kbeg[3], prt_kt[3];
 };
 void launch_gemm_nt(const NtArgs& a, hipStream_t st);
 void launch_gemm_nt16(const NtArgs& a, hipStream_t st);  // bf16-operand variant (called through launch_gemm_nt)
+void launch_gemm_nt3(const NtArgs& a, hipStream_t st);   // pre-cut three-plane operands (called through launch_gemm_nt)
 bool gemm_nt_keep_parts(NtArgs& a);             // drops the parts of a launch that would not save work
 int gemm_nt_tiles(int rows, int cols);           // number of output tiles (= arrival counters needed)
 size_t gemm_nt_partial_bytes(int max_wgs);       // scratch needed for partial tiles
