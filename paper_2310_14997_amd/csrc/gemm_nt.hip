@@ -332,7 +332,14 @@ bool gemm_nt_keep_parts(NtArgs& a) {
 void launch_gemm_nt(const NtArgs& a, hipStream_t st) {
   if (a.rows <= 0 || a.cols <= 0) return;
   if (a.b_bf16) { launch_gemm_nt16(a, st); return; }
-  if (a.planes3) { launch_gemm_nt3(a, st); return; }
+  if (a.planes3) {
+    // tall row tiles: the kernel on pre-cut operands; short ones keep the fp32 operands (fewer panel bytes)
+    if (nt::chosen_bm(a) == 128) { launch_gemm_nt3(a, st); return; }
+    NtArgs b = a;
+    b.planes3 = 0;
+    launch_gemm_nt(b, st);
+    return;
+  }
   switch (a.epilogue) {
     case NT_EPI_ROWSCALE: launch_bm<NT_EPI_ROWSCALE>(a, st); break;
     case NT_EPI_MASKROWS: launch_bm<NT_EPI_MASKROWS>(a, st); break;

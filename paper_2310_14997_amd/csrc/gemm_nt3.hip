@@ -151,8 +151,8 @@ __global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int tota
     }
     const int k1 = min(KTt, k0 + (wg_end - it));
     const int col0 = tile_n * BN;
-    const uint16_t* amat = static_cast<const uint16_t*>(g.A) + (int64_t)kbeg * BK3;
-    const uint16_t* bmat = static_cast<const uint16_t*>(g.Bm) + (int64_t)c_shift * g.ldb + (int64_t)kbeg * BK3;
+    const uint16_t* amat = static_cast<const uint16_t*>(g.A3) + (int64_t)kbeg * BK3;
+    const uint16_t* bmat = static_cast<const uint16_t*>(g.Bm3) + (int64_t)c_shift * g.ldb + (int64_t)kbeg * BK3;
     // global address of this lane's 16 bytes of every load instruction at K-step 0: row rg * 16 + lane / 4 of the
     // plane tile (clamped into the operand: rows past the end are never stored), chunk (lane % 4) ^ swz(row)
     const unsigned char* gp[ND];

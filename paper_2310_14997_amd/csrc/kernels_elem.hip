@@ -729,8 +729,8 @@ void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const 
   dim3 grid((ly.Np + ly.Pp) / 32, ly.Np / 32, 2 * ly.G);
   if (ly.planes == 3)
     launch_k(k_pack_weights<uint16_t>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
-                       (uint16_t*)p.Wn, (uint16_t*)p.Wp, (uint16_t*)p.Wtn, (uint16_t*)p.Wtp);
-  else if (ly.bf16)
+                       (uint16_t*)p.Wn3, (uint16_t*)p.Wp3, (uint16_t*)p.Wtn3, (uint16_t*)p.Wtp3);
+  if (ly.bf16)
     launch_k(k_pack_weights<__bf16>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
                        (__bf16*)p.Wn, (__bf16*)p.Wp, (__bf16*)p.Wtn, (__bf16*)p.Wtp);
   else

@@ -76,11 +76,15 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   }
   ly.counters = take(i4 * (size_t)ly.n_counters);
   ly.partial = take(gemm_nt_partial_bytes(gemm_wgs));
-  const size_t w4 = bf16 ? 2 : (ly.planes == 3 ? 6 : 4);  // bytes per packed weight
+  const size_t w4 = bf16 ? 2 : 4;  // bytes per packed weight
   ly.Wn = take(w4 * 2 * (size_t)ly.Np * ly.Np * ly.G);
   ly.Wp = take(w4 * 2 * (size_t)ly.Np * ly.Pp * ly.G);
   ly.Wtn = take(w4 * 2 * (size_t)ly.Np * ly.Np * ly.G);
   ly.Wtp = take(w4 * 2 * (size_t)ly.Np * ly.Pp * ly.G);
+  if (ly.planes == 3) {
+    ly.Wn3 = take(6 * 2 * (size_t)ly.Np * ly.Np); ly.Wp3 = take(6 * 2 * (size_t)ly.Np * ly.Pp);
+    ly.Wtn3 = take(6 * 2 * (size_t)ly.Np * ly.Np); ly.Wtp3 = take(6 * 2 * (size_t)ly.Np * ly.Pp);
+  }
   if (per_sentence) { ly.sentrows = take(i4 * (size_t)S2); ly.sentoff = take(i4 * (size_t)B); }
   if (bf16) {
     ly.UVt_n = take(2 * 2 * (size_t)ly.Np * ly.S2pad);
@@ -117,6 +121,7 @@ Ptrs resolve(const Layout& ly, void* ws) {
   p.sentrows = (int32_t*)(b + ly.sentrows); p.sentoff = (int32_t*)(b + ly.sentoff);
   p.Tb = ly.planes ? b + ly.Tb : nullptr; p.UVb = ly.planes ? b + ly.UVb : nullptr; p.leafEb = ly.planes ? b + ly.leafEb : nullptr;
   p.UVt_n = b + ly.UVt_n; p.Tt = b + ly.Tt; p.UVt_p = b + ly.UVt_p; p.Et = b + ly.Et;
+  p.Wn3 = b + ly.Wn3; p.Wp3 = b + ly.Wp3; p.Wtn3 = b + ly.Wtn3; p.Wtp3 = b + ly.Wtp3;
   p.Wn = (float*)(b + ly.Wn); p.Wp = (float*)(b + ly.Wp); p.Wtn = (float*)(b + ly.Wtn); p.Wtp = (float*)(b + ly.Wtp);
   return p;
 }
@@ -272,7 +277,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.leafE; a.lda = Pp; a.Bm = p.Wp; a.ldb = Pp; a.C = p.HZ; a.ldc = 2 * Np;
     if (ly.bf16) { a.A = p.leafEb; a.a_bf16 = 1; }
-    if (ly.planes == 3) { a.A = p.leafEb; a.planes3 = 1; a.a_plane = ly.S1 * Pp; a.b_plane = 2 * Np * Pp; }
+    if (ly.planes == 3) { a.A3 = p.leafEb; a.Bm3 = p.Wp3; a.planes3 = 1; a.a_plane = ly.S1 * Pp; a.b_plane = 2 * Np * Pp; }
     a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
     a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb;
     set_groups(a, plan, ly, p, 1, 0, 2 * Np * Pp);
@@ -292,7 +297,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.a_bf16 = 1; }
     if (ly.planes == 3) {
-      a.A = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np;
+      a.A3 = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.Bm3 = p.Wn3;
       a.planes3 = 1; a.a_plane = ly.S2 * Np; a.b_plane = 2 * Np * Np;
     }
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
@@ -350,7 +355,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
     a.A = p.UV + row0 * 2 * Np; a.lda = 2 * Np; a.K = (int)(2 * Np); a.rows = (int)rows;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np; a.a_bf16 = 1; }
     if (ly.planes == 3) {
-      a.A = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np;
+      a.A3 = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np; a.Bm3 = w >= 2 ? p.Wtn3 : p.Wtp3;
       a.planes3 = 1; a.a_plane = ly.Sall * 2 * Np; a.b_plane = 2 * Np * (w >= 2 ? Np : Pp);
     }
     if (w >= 2) {

@@ -45,6 +45,7 @@ struct Layout {
   // byte offsets into the workspace
   size_t lens, rowbase, row_b, row_i, rootmask, rootrow, mexp, uexp, tmaxb, umaxb, gsc, xs, ztil, rmax;
   size_t leafE, T, HZ, UV, BH, Wn, Wp, Wtn, Wtp, partial, counters;
+  size_t Wn3, Wp3, Wtn3, Wtp3;  // planes == 3: the packed panels once more, cut into three bf16 planes
   size_t UVt_n, Tt, UVt_p, Et;  // bf16 mode only
   size_t Tb, UVb, leafEb;       // planes > 0: bf16 planes of T, UV, leafE ([planes][rows][cols]), written by their producers
   size_t sentrows, sentoff;     // per-sentence grammars only: rows of width >= 2 listed sentence by sentence, first entry of each
@@ -60,6 +61,7 @@ struct Ptrs {  // device pointers resolved from a Layout
   float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp, *partial;  // W* hold bf16 data in bf16 mode
   void *UVt_n, *Tt, *UVt_p, *Et;
   void *Tb, *UVb, *leafEb;  // null when the layout has no planes
+  void *Wn3, *Wp3, *Wtn3, *Wtp3;
   int32_t* counters;
   int32_t* sentrows; int32_t* sentoff;
 };
@@ -151,7 +153,10 @@ struct NtArgs {
   // planes3 = 1: both operands are given as three bf16 planes (the exact cut hi + mid + lo of every fp32 value,
   // nt::Split3), written by their producers: A = [3][..][lda] with planes a_plane elements apart, Bm likewise with
   // b_plane; A and Bm then point to bf16 data and the product runs in gemm_nt3.hip.
+  // A3 / Bm3 are those planes; A / Bm stay the fp32 operands, which the launches with short row tiles use (their time
+  // goes into reading the panel once, and the fp32 panel is a third shorter than its three planes).
   int planes3; int64_t a_plane, b_plane;
+  const void* A3; const void* Bm3;
   int parts;
   int prt_row0[3], prt_rows[3], prt_c0[3], prt_kbeg[3], prt_kt[3];
 };
