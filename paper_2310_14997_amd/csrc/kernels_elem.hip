@@ -98,6 +98,15 @@ __device__ __forceinline__ float norm_scale(uint32_t maxbits) {
   return maxbits == 0u ? 0.0f : ldexpf(1.0f, -norm_shift(maxbits));
 }
 
+// A projected half row (eta or zeta of a span) is stored with the exponent of its inside vector, norm_exp(mexp, tmaxb),
+// and its own largest entry in pmaxb (from the GEMM epilogue).  Its consumers read it as 2^-g * stored with
+// g = norm_shift(pmaxb), largest entry then in [0.5, 1), and the exponent norm_exp(mexp, tmaxb) + g: products of two
+// such values cannot underflow however small the grammar's weights are.
+__device__ __forceinline__ int proj_exp(int m, uint32_t tmaxbits, uint32_t pmaxbits) {
+  const int e = norm_exp(m, tmaxbits);
+  return (e == kExpZero || pmaxbits == 0u) ? kExpZero : e + norm_shift(pmaxbits);
+}
+
 // ------------------------------------------------------------------------------------------ span plan
 // Width-synchronous schedule (Sec. 3.2, span-level parallelism): rows are ordered by width.  Within a width the
 // order is: the prefix spans (i = 0) of all sentences, then the other spans that do not end the sentence
@@ -178,7 +187,8 @@ __global__ void k_plan_rowbase(LenArg la, int B, int n_max, int by_sentence, int
 __global__ void k_plan_rows(int B, int stride, const int32_t* __restrict__ lens, const int32_t* __restrict__ rowtab,
                             int32_t* __restrict__ row_b, int32_t* __restrict__ row_i,
                             int32_t* __restrict__ rootmask, uint32_t* __restrict__ tmaxb,
-                            uint32_t* __restrict__ umaxb) {
+                            uint32_t* __restrict__ umaxb, uint32_t* __restrict__ hmaxb,
+                            uint32_t* __restrict__ zmaxb) {
   const int w = blockIdx.x + 1, b = blockIdx.y;
   const int n = lens[b];
   if (w > n) return;
@@ -189,6 +199,8 @@ __global__ void k_plan_rows(int B, int stride, const int32_t* __restrict__ lens,
     rootmask[r] = (w == n) ? 1 : 0;
     tmaxb[r] = 0u;
     umaxb[r] = 0u;
+    hmaxb[r] = 0u;
+    zmaxb[r] = 0u;
   }
 }
 
@@ -329,10 +341,11 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
             const int32_t* __restrict__ rowtab, const int32_t* __restrict__ row_b,
             const int32_t* __restrict__ row_i, const float* __restrict__ HZ,
             float* __restrict__ T, int32_t* __restrict__ mexp, uint32_t* __restrict__ tmaxb, void* __restrict__ Tb,
-            int planes, int64_t plane_stride) {
+            int planes, int64_t plane_stride, const uint32_t* __restrict__ hmaxb, const uint32_t* __restrict__ zmaxb) {
   extern __shared__ __align__(16) unsigned char smem[];
-  float* s_c = reinterpret_cast<float*>(smem);                 // [w-1]
-  int32_t* s_l = reinterpret_cast<int32_t*>(s_c + (w - 1));    // [w-1] row of the left child
+  float* s_c = reinterpret_cast<float*>(smem);                 // [w-1] coefficient of the left child's eta
+  float* s_cz = s_c + (w - 1);                                 // [w-1] coefficient of the right child's zeta
+  int32_t* s_l = reinterpret_cast<int32_t*>(s_cz + (w - 1));   // [w-1] row of the left child
   int32_t* s_r = s_l + (w - 1);                                // [w-1] row of the right child
   const int lane = threadIdx.x;
   const int64_t r = row0 + blockIdx.x;
@@ -344,15 +357,21 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
     const int rr = row_of(rowtab, stride, B, w - k, b, i + k, n);  // span (i+k, i+w)
     s_l[k - 1] = lr;
     s_r[k - 1] = rr;
-    const int d = add_exp(norm_exp(mexp[lr], tmaxb[lr]), norm_exp(mexp[rr], tmaxb[rr]));
+    const uint32_t hb = hmaxb[lr];
+    const int d = add_exp(proj_exp(mexp[lr], tmaxb[lr], hb), proj_exp(mexp[rr], tmaxb[rr], zmaxb[rr]));
     s_c[k - 1] = __int_as_float(d);
+    s_cz[k - 1] = __int_as_float(d == kExpZero ? 0 : norm_shift(hb));  // eta's shift, used once m is known
     dmax = max(dmax, d);
   }
   const int m = wave_max_i(dmax);
   __syncthreads();
+  // the term of split point k is 2^(d_k - m) * (2^-gh eta) * (2^-gz zeta): the first two factors go with eta
+  // (coefficient 2^(d_k - m - gh)), the last with zeta (coefficient 2^-gz); both products stay at or below 1
   for (int k = lane; k < w - 1; k += 64) {
     const int d = __float_as_int(s_c[k]);
-    s_c[k] = (d == kExpZero) ? 0.0f : pow2i(d - m);
+    const int gh = __float_as_int(s_cz[k]);
+    s_c[k] = (d == kExpZero) ? 0.0f : pow2i(d - m - gh);
+    s_cz[k] = (d == kExpZero) ? 0.0f : norm_scale(zmaxb[s_r[k]]);
   }
   __syncthreads();
 
@@ -375,30 +394,31 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        const float c = s_c[k + u * KG + kg];
-        acc.x = fmaf(c * h[u].x, z[u].x, acc.x);
-        acc.y = fmaf(c * h[u].y, z[u].y, acc.y);
-        acc.z = fmaf(c * h[u].z, z[u].z, acc.z);
-        acc.w = fmaf(c * h[u].w, z[u].w, acc.w);
+        const float c = s_c[k + u * KG + kg], cz = s_cz[k + u * KG + kg];
+        acc.x = fmaf(c * h[u].x, cz * z[u].x, acc.x);
+        acc.y = fmaf(c * h[u].y, cz * z[u].y, acc.y);
+        acc.z = fmaf(c * h[u].z, cz * z[u].z, acc.z);
+        acc.w = fmaf(c * h[u].w, cz * z[u].w, acc.w);
       }
     }
     for (; k < w - 1; k += 4 * KG) {  // remainder in masked groups of four: no serial chain of dependent loads
       float4 h[4], z[4];
-      float c[4];
+      float c[4], cz[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int idx = k + u * KG + kg;
         const int kk = min(idx, w - 2);
         c[u] = (idx < w - 1) ? s_c[kk] : 0.0f;
+        cz[u] = s_cz[kk];
         h[u] = *reinterpret_cast<const float4*>(hz_l + s_l[kk] * ld);
         z[u] = *reinterpret_cast<const float4*>(hz_r + s_r[kk] * ld);
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        acc.x = fmaf(c[u] * h[u].x, z[u].x, acc.x);
-        acc.y = fmaf(c[u] * h[u].y, z[u].y, acc.y);
-        acc.z = fmaf(c[u] * h[u].z, z[u].z, acc.z);
-        acc.w = fmaf(c[u] * h[u].w, z[u].w, acc.w);
+        acc.x = fmaf(c[u] * h[u].x, cz[u] * z[u].x, acc.x);
+        acc.y = fmaf(c[u] * h[u].y, cz[u] * z[u].y, acc.y);
+        acc.z = fmaf(c[u] * h[u].z, cz[u] * z[u].z, acc.z);
+        acc.w = fmaf(c[u] * h[u].w, cz[u] * z[u].w, acc.w);
       }
     }
     if (KG > 1) {  // sum of the groups' partial sums, in a fixed order
@@ -538,7 +558,7 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
             const float* __restrict__ HZ, const float* __restrict__ BH, const int32_t* __restrict__ mexp,
             const uint32_t* __restrict__ tmaxb, float* __restrict__ UV, int32_t* __restrict__ uexp,
             uint32_t* __restrict__ umaxb, float* __restrict__ gsc, void* __restrict__ UVb, int planes,
-            int64_t plane_stride) {
+            int64_t plane_stride, const uint32_t* __restrict__ hmaxb, const uint32_t* __restrict__ zmaxb) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x;
   const int64_t r = row0 + blockIdx.x;
@@ -549,8 +569,9 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
   const int nl = n - j;  // parents (i, j'), j' = j+1..n   (this span is their left child)
   const int nr = i;      // parents (i', j), i' = 0..i-1   (this span is their right child)
   const int nt = nl + nr;
-  float* s_c = reinterpret_cast<float*>(smem);             // [nt]
-  int32_t* s_p = reinterpret_cast<int32_t*>(s_c + nt);     // [nt] parent row (index into BH: row - S1)
+  float* s_c = reinterpret_cast<float*>(smem);             // [nt] coefficient of the parent's adjoint
+  float* s_cs = s_c + nt;                                  // [nt] coefficient of the sibling's projection
+  int32_t* s_p = reinterpret_cast<int32_t*>(s_cs + nt);    // [nt] parent row (index into BH: row - S1)
   int32_t* s_s = s_p + nt;                                 // [nt] sibling row
 
   int dmax = kExpZero;
@@ -567,8 +588,10 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
     }
     s_p[t] = pr - (int)S1;
     s_s[t] = sr;
-    const int d = add_exp(norm_exp(uexp[pr], umaxb[pr]), norm_exp(mexp[sr], tmaxb[sr]));
+    const uint32_t sb = t < nl ? zmaxb[sr] : hmaxb[sr];  // the sibling's zeta (this span is the left child) or eta
+    const int d = add_exp(norm_exp(uexp[pr], umaxb[pr]), proj_exp(mexp[sr], tmaxb[sr], sb));
     s_c[t] = __int_as_float(d);
+    s_cs[t] = norm_scale(sb);
     dmax = max(dmax, d);
   }
   const int m = wave_max_i(dmax);
@@ -576,6 +599,7 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
   for (int t = lane; t < nt; t += 64) {
     const int d = __float_as_int(s_c[t]);
     s_c[t] = (d == kExpZero) ? 0.0f : pow2i(d - m);
+    if (d == kExpZero) s_cs[t] = 0.0f;
   }
   __syncthreads();
 
@@ -596,27 +620,28 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
         sq[q] = *reinterpret_cast<const float4*>(HZ + s_s[t + q] * ld + (HZOFF) + a);           \
       }                                                                                         \
       _Pragma("unroll") for (int q = 0; q < 8; ++q) {                                           \
-        const float c = s_c[t + q];                                                             \
-        ACC.x = fmaf(c * gq[q].x, sq[q].x, ACC.x);                                              \
-        ACC.y = fmaf(c * gq[q].y, sq[q].y, ACC.y);                                              \
-        ACC.z = fmaf(c * gq[q].z, sq[q].z, ACC.z);                                              \
-        ACC.w = fmaf(c * gq[q].w, sq[q].w, ACC.w);                                              \
+        const float c = s_c[t + q], cs = s_cs[t + q];                                           \
+        ACC.x = fmaf(c * gq[q].x, cs * sq[q].x, ACC.x);                                         \
+        ACC.y = fmaf(c * gq[q].y, cs * sq[q].y, ACC.y);                                         \
+        ACC.z = fmaf(c * gq[q].z, cs * sq[q].z, ACC.z);                                         \
+        ACC.w = fmaf(c * gq[q].w, cs * sq[q].w, ACC.w);                                         \
       }                                                                                         \
     }                                                                                           \
     for (; t < (T1); t += 4) {                                                                  \
       float4 gq[4], sq[4];                                                                      \
-      float cq[4];                                                                              \
+      float cq[4], cs[4];                                                                       \
       _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                           \
         const int tt = min(t + q, (T1)-1);                                                      \
         cq[q] = (t + q < (T1)) ? s_c[tt] : 0.0f;                                                \
+        cs[q] = s_cs[tt];                                                                       \
         gq[q] = *reinterpret_cast<const float4*>(bh + (int64_t)s_p[tt] * Np);                   \
         sq[q] = *reinterpret_cast<const float4*>(HZ + s_s[tt] * ld + (HZOFF) + a);              \
       }                                                                                         \
       _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                           \
-        ACC.x = fmaf(cq[q] * gq[q].x, sq[q].x, ACC.x);                                          \
-        ACC.y = fmaf(cq[q] * gq[q].y, sq[q].y, ACC.y);                                          \
-        ACC.z = fmaf(cq[q] * gq[q].z, sq[q].z, ACC.z);                                          \
-        ACC.w = fmaf(cq[q] * gq[q].w, sq[q].w, ACC.w);                                          \
+        ACC.x = fmaf(cq[q] * gq[q].x, cs[q] * sq[q].x, ACC.x);                                  \
+        ACC.y = fmaf(cq[q] * gq[q].y, cs[q] * sq[q].y, ACC.y);                                  \
+        ACC.z = fmaf(cq[q] * gq[q].z, cs[q] * sq[q].z, ACC.z);                                  \
+        ACC.w = fmaf(cq[q] * gq[q].w, cs[q] * sq[q].w, ACC.w);                                  \
       }                                                                                         \
     }                                                                                           \
   }
@@ -716,7 +741,7 @@ void launch_plan(const Layout& ly, const Ptrs& p, const LenArg& lens, hipStream_
            p.rootrow,
                      p.counters, ly.n_counters);
   launch_k(k_plan_rows, dim3(ly.n_max, ly.B), dim3(64), 0, st, ly.B, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b, p.row_i,
-                     p.rootmask, p.tmaxb, p.umaxb);
+                     p.rootmask, p.tmaxb, p.umaxb, p.hmaxb, p.zmaxb);
 }
 
 void launch_plan_sentrows(const Layout& ly, const Ptrs& p, hipStream_t st) {
@@ -751,17 +776,17 @@ void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hi
 }
 
 void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
-  const size_t sh = (size_t)(w - 1) * 12;
+  const size_t sh = (size_t)(w - 1) * 16;
   const int chunks = (ly.Np + kChunk - 1) / kChunk;
   if (rows * chunks < 1024 && w - 1 >= 64) {  // fewer than one wavefront per SIMD, long chains of split points
     const dim3 grid((unsigned)rows, (unsigned)(ly.Np / 64));
     launch_k(k_split_fwd<4>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b, p.row_i, p.HZ,
-             p.T, p.mexp, p.tmaxb, p.Tb, ly.planes, (int64_t)ly.S2 * ly.Np);
+             p.T, p.mexp, p.tmaxb, p.Tb, ly.planes, (int64_t)ly.S2 * ly.Np, p.hmaxb, p.zmaxb);
     return;
   }
   const dim3 grid((unsigned)rows, (unsigned)chunks);
   launch_k(k_split_fwd<1>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b, p.row_i, p.HZ,
-           p.T, p.mexp, p.tmaxb, p.Tb, ly.planes, (int64_t)ly.S2 * ly.Np);
+           p.T, p.mexp, p.tmaxb, p.Tb, ly.planes, (int64_t)ly.S2 * ly.Np, p.hmaxb, p.zmaxb);
 }
 
 void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st) {
@@ -782,11 +807,11 @@ void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, con
 }
 
 void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
-  const size_t sh = (size_t)ly.n_max * 12;
+  const size_t sh = (size_t)ly.n_max * 16;
   const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
   launch_k(k_split_bwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b,
                      p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc, p.UVb, ly.planes,
-                     (int64_t)ly.Sall * 2 * ly.Np);
+                     (int64_t)ly.Sall * 2 * ly.Np, p.hmaxb, p.zmaxb);
 }
 
 void launch_zero_pad_emit(const Layout& ly, const Ptrs& p, float* grad_log_emit, hipStream_t st) {

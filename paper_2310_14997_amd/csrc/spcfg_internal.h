@@ -7,6 +7,9 @@
 //   leaf row r:        leafE[r] = exp(e_i - max e_i)          (exponent 0; the max is added back into logZ)
 //   span row r (w>=2): T[r]     = sum_k 2^(d_k - m) * eta_ik * zeta_kj,  m = max_k d_k   (exponent mexp[r] = m)
 //   every non-root row: HZ[r]   = [eta | zeta] = 2^-f * [L;R] * (leafE[r] or T[r])        (exponent mexp[r] + f)
+//                      eta and zeta each have a normalising shift of their own on top (from hmaxb[r], zmaxb[r], the
+//                      largest entry of each half, recorded by the GEMM epilogue): a grammar whose weights are tiny
+//                      everywhere gives tiny projections, and the split products eta * zeta must not underflow
 //   reverse pass:      UV[r]    = unnormalised adjoints of [eta | zeta]                   (exponent uexp[r])
 //                      BH[r]    = 2^-f' * UV[r] * [L;R]  = scaled adjoint of beta         (exponent uexp[r] + f')
 // f (f') is the shift that brings the largest magnitude of T[r] (UV[r]) into [0.5, 1).  The split kernels
@@ -43,7 +46,7 @@ struct Layout {
   int64_t S1pad, S2pad;  // row counts rounded up to 64 (K of the bf16 rule-gradient product)
   int64_t S1, S2, Sall;  // leaf rows, rows of width >= 2, all rows
   // byte offsets into the workspace
-  size_t lens, rowbase, row_b, row_i, rootmask, rootrow, mexp, uexp, tmaxb, umaxb, gsc, xs, ztil, rmax;
+  size_t lens, rowbase, row_b, row_i, rootmask, rootrow, mexp, uexp, tmaxb, umaxb, hmaxb, zmaxb, gsc, xs, ztil, rmax;
   size_t leafE, T, HZ, UV, BH, Wn, Wp, Wtn, Wtp, partial, counters;
   size_t Wn3, Wp3, Wtn3, Wtp3;  // planes == 3: the packed panels once more, cut into three bf16 planes
   size_t UVt_n, Tt, UVt_p, Et;  // bf16 mode only
@@ -56,7 +59,7 @@ struct Layout {
 
 struct Ptrs {  // device pointers resolved from a Layout
   int32_t *lens, *rowbase, *row_b, *row_i, *rootmask, *rootrow, *mexp, *uexp;
-  uint32_t *tmaxb, *umaxb;
+  uint32_t *tmaxb, *umaxb, *hmaxb, *zmaxb;
   float *gsc, *xs, *ztil, *rmax;
   float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp, *partial;  // W* hold bf16 data in bf16 mode
   void *UVt_n, *Tt, *UVt_p, *Et;
@@ -127,6 +130,9 @@ struct NtArgs {
   int epilogue;
   const uint32_t* rowmaxb;  // ROWSCALE, MASKROWS: C = 2^-f(rowmaxb[r]) * acc (normalising shift of the A row)
   const int32_t* rowmask;   // MASKROWS: rows with rowmask[r] != 0 are left untouched
+  // ROWSCALE with hmaxb != null: the bit pattern of the largest value written to columns [0, Np) of row r is
+  // max-ed into hmaxb[r], that of columns [Np, 2 Np) into zmaxb[r] (integer atomicMax: exact, order-independent)
+  uint32_t* hmaxb; uint32_t* zmaxb;
   // LEAF_EMIT: C[dst[r] * ldc + c] = acc * E[r][c] * 2^rowexp[r], c < cols
   const float* E; int64_t lde;
   const int32_t* rowexp;

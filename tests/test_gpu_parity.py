@@ -119,6 +119,33 @@ def test_derivative_at_dead_rule_blocks():
     print(check_all(got, ref))
 
 
+@pytest.mark.parametrize("per_sentence,seed,N,P,lens", [
+    (True, 7634, 1, 228, [97, 37, 92, 97, 95, 49]),
+    (True, 7177, 1, 371, [3, 16, 20, 10, 3, 24, 25, 32, 7, 33, 2, 10]),
+    (False, 7634, 1, 228, [97, 37, 92, 97, 95, 49]),
+    (False, 7700, 3, 40, [60, 33, 2, 75]),
+])
+def test_weights_that_are_tiny_everywhere_do_not_underflow(per_sentence, seed, N, P, lens):
+    """Peaked rows (logits x 8) with one or a few nonterminals: the nonterminal block of L and R can be ~1e-20
+    everywhere, so every projection eta, zeta is that small and their product leaves the fp32 range unless each is
+    renormalised on its own (a random sweep met these shapes: -inf for a derivable sentence, gradients off by 85 %)."""
+    make = synth.make_inputs_per_sentence if per_sentence else synth.make_inputs
+    d = make("tiny", seed=seed, pad_value=np.nan, N=N, P=P, B=len(lens), lengths=lens, V=60, lr_scale=8.0)
+    small = float(np.max(d["L"][..., :N])) * float(np.max(d["R"][..., :N]))
+    print("case tiny weights", dict(per_sentence=per_sentence, N=N, P=P, lens=lens), "largest L_N * R_N", small, flush=True)
+    got, _ = gpu_run(d, fused=True)
+    if per_sentence:
+        for b in range(len(lens)):
+            n = lens[b]
+            lz, gL, gR, gr, ge = O.inside_backward_sentence(d["log_root"][b], d["L"][b], d["R"][b], d["log_emit"][b, :n])
+            check_logZ(got["logZ"][b:b + 1], np.array([lz]))
+            check_grad(f"grad_L[{b}]", got["grad_L"][b], gL)
+            check_grad(f"grad_R[{b}]", got["grad_R"][b], gR)
+            check_grad(f"grad_log_emit[{b}]", got["grad_log_emit"][b, :n], ge)
+    else:
+        print(check_all(got, oracle_run(d)))
+
+
 def test_underivable_sentence_gives_minus_inf_and_zero_gradients():
     d = synth.make_inputs("tiny", seed=79, pad_value=np.nan, B=3, lengths=[5, 6, 4])
     d["log_emit"][1, 2, :] = -np.inf   # token 2 of sentence 1 cannot be emitted by any preterminal
