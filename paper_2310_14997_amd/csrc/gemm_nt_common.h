@@ -97,34 +97,6 @@ __device__ __forceinline__ void epilogue(const NtArgs& g, floatx16 (&acc)[Geo<BM
                                          int wm, int wn, int lane, int row_end, int c_shift = 0) {
   using G = Geo<BM>;
   // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
-  if (EPI == NT_EPI_ROWSCALE && g.hmaxb != nullptr) {
-    // largest projected value per row and half (eta: columns below Np, zeta: the rest), for the consumers' own
-    // normalising shift.  The 32 lanes of a half-wavefront hold the 32 columns of one row; the wavefront's 64-column
-    // block lies in one half (Np is a multiple of 64).  All lanes take part in the shuffles.
-    const bool zeta_half = col0 + c_shift + wn * G::NI * 32 >= g.Np;
-#pragma unroll
-    for (int mi = 0; mi < G::MI; ++mi) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int r = row0 + (wm * G::MI + mi) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        float m = 0.0f;
-        if (r < row_end) {
-          const uint32_t mb = g.rowmaxb[r];
-          const int f = max((int)((mb >> 23) & 0xffu) - 126, -126);
-          const float scale = mb == 0u ? 0.0f : ldexpf(1.0f, -f);
-#pragma unroll
-          for (int ni = 0; ni < G::NI; ++ni) {
-            const int c = col0 + (wn * G::NI + ni) * 32 + (lane & 31);
-            if (c < g.cols) m = fmaxf(m, acc[mi][ni][v] * scale);
-          }
-        }
-#pragma unroll
-        for (int o = 1; o < 32; o <<= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-        if ((lane & 31) == 0 && r < row_end && m > 0.0f)
-          atomicMax((zeta_half ? g.zmaxb : g.hmaxb) + r, __float_as_uint(m));
-      }
-    }
-  }
 #pragma unroll
   for (int mi = 0; mi < G::MI; ++mi) {
 #pragma unroll

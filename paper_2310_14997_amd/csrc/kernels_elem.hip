@@ -98,13 +98,24 @@ __device__ __forceinline__ float norm_scale(uint32_t maxbits) {
   return maxbits == 0u ? 0.0f : ldexpf(1.0f, -norm_shift(maxbits));
 }
 
-// A projected half row (eta or zeta of a span) is stored with the exponent of its inside vector, norm_exp(mexp, tmaxb),
-// and its own largest entry in pmaxb (from the GEMM epilogue).  Its consumers read it as 2^-g * stored with
-// g = norm_shift(pmaxb), largest entry then in [0.5, 1), and the exponent norm_exp(mexp, tmaxb) + g: products of two
-// such values cannot underflow however small the grammar's weights are.
-__device__ __forceinline__ int proj_exp(int m, uint32_t tmaxbits, uint32_t pmaxbits) {
+// A projected half row (eta or zeta of a span) is stored as 2^-f * [L or R] * (stored inside vector), with the
+// exponent m + f of its inside vector (f = norm_shift(tmaxb)).  Its producer also records
+//   psum = max_B (biased exponent of max_A W[A,B]) + (biased exponent of the stored inside entry B)      (0: all zero)
+// so that the largest entry of W * (stored inside vector) lies in [2^(psum - 254), 4 N 2^(psum - 254)).  The
+// consumers read the half row as 2^-g * stored with g = (psum - 253) - f (clamped to the fp32 exponent range): its
+// largest entry is then in [0.5, 2 N), and products of two such values cannot leave the fp32 range however small
+// (or large) the grammar's weights are.
+__device__ __forceinline__ int bexp(float x) { return (int)((__float_as_uint(x) >> 23) & 0xffu); }
+__device__ __forceinline__ int bexp_sum(float w, float x) {
+  const int a = bexp(w), b = bexp(x);
+  return (a == 0 || b == 0) ? 0 : a + b;
+}
+__device__ __forceinline__ int proj_shift(uint32_t tmaxbits, int psum) {
+  return min(max((psum - 253) - norm_shift(tmaxbits), -126), 126);
+}
+__device__ __forceinline__ int proj_exp(int m, uint32_t tmaxbits, int psum) {
   const int e = norm_exp(m, tmaxbits);
-  return (e == kExpZero || pmaxbits == 0u) ? kExpZero : e + norm_shift(pmaxbits);
+  return (e == kExpZero || psum == 0) ? kExpZero : e + proj_shift(tmaxbits, psum);
 }
 
 // ------------------------------------------------------------------------------------------ span plan
@@ -187,8 +198,8 @@ __global__ void k_plan_rowbase(LenArg la, int B, int n_max, int by_sentence, int
 __global__ void k_plan_rows(int B, int stride, const int32_t* __restrict__ lens, const int32_t* __restrict__ rowtab,
                             int32_t* __restrict__ row_b, int32_t* __restrict__ row_i,
                             int32_t* __restrict__ rootmask, uint32_t* __restrict__ tmaxb,
-                            uint32_t* __restrict__ umaxb, uint32_t* __restrict__ hmaxb,
-                            uint32_t* __restrict__ zmaxb) {
+                            uint32_t* __restrict__ umaxb, int32_t* __restrict__ hmaxb,
+                            int32_t* __restrict__ zmaxb) {
   const int w = blockIdx.x + 1, b = blockIdx.y;
   const int n = lens[b];
   if (w > n) return;
@@ -199,8 +210,8 @@ __global__ void k_plan_rows(int B, int stride, const int32_t* __restrict__ lens,
     rootmask[r] = (w == n) ? 1 : 0;
     tmaxb[r] = 0u;
     umaxb[r] = 0u;
-    hmaxb[r] = 0u;
-    zmaxb[r] = 0u;
+    hmaxb[r] = 0;
+    zmaxb[r] = 0;
   }
 }
 
@@ -237,7 +248,7 @@ __device__ __forceinline__ void put_w(uint16_t* w, int64_t stride, int64_t at, f
 template <typename OutT>
 __global__ void k_pack_weights(const float* __restrict__ L, const float* __restrict__ R, int N, int P, int Np,
                                int Pp, OutT* __restrict__ Wn, OutT* __restrict__ Wp, OutT* __restrict__ Wtn,
-                               OutT* __restrict__ Wtp) {
+                               OutT* __restrict__ Wtp, uint32_t* __restrict__ colmax) {
   constexpr int NPL = std::is_same<OutT, uint16_t>::value ? 3 : 1;
   const int64_t sn = 2 * (int64_t)Np * Np, sp = 2 * (int64_t)Np * Pp;
   __shared__ float tile[32][33];
@@ -261,12 +272,25 @@ __global__ void k_pack_weights(const float* __restrict__ L, const float* __restr
     if (ppart) put_w(Wp, sp, (int64_t)(half + a) * Pp + c, v); else put_w(Wn, sn, (int64_t)(half + a) * Np + c, v);
   }
   __syncthreads();
+  if (colmax != nullptr && ty == 0) {
+    // colmax[(g * 2 + lr) * (Np + Pp) + c] = max_A W[A, c] over the padded columns c (nonterminals [0, Np), then
+    // preterminals): feeds the exponent bounds of the projections (see proj_shift).  Weights are non-negative, so the
+    // maximum of the bit patterns is the maximum of the values; the array is zeroed before this kernel.
+    float m = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 32; ++q) m = fmaxf(m, tile[q][tx]);
+    if (m > 0.0f) atomicMax(colmax + (int64_t)blockIdx.z * (Np + Pp) + c0 + tx, __float_as_uint(m));
+  }
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int c = cc0 + ty + 8 * q, a = a0 + tx;
     const float v = tile[tx][ty + 8 * q];
     if (ppart) put_w(Wtp, sp, (int64_t)c * (2 * Np) + half + a, v); else put_w(Wtn, sn, (int64_t)c * (2 * Np) + half + a, v);
   }
+}
+
+__global__ void k_zero_u32(uint32_t* __restrict__ p, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
 
 // Xt[c][s] = bf16(sc[s] * X[s][c]) for s < S, 0 for S <= s < Spad: the reduction-major operands of the
@@ -298,8 +322,10 @@ __global__ void k_leaf_prep(const float* __restrict__ log_emit, int P, int Pp, i
                             const int32_t* __restrict__ row_b, const int32_t* __restrict__ row_i,
                             float* __restrict__ leafE, float* __restrict__ xs, int32_t* __restrict__ mexp,
                             uint32_t* __restrict__ tmaxb, uint16_t* __restrict__ leafEb, int planes,
-                            int64_t plane_stride) {
+                            int64_t plane_stride, const float* __restrict__ colmax, int Np, int per_sentence,
+                            int32_t* __restrict__ hmaxb, int32_t* __restrict__ zmaxb) {
   __shared__ float red[16];
+  __shared__ int redi[16];
   const int r = blockIdx.x;
   const float* e = log_emit + ((int64_t)row_b[r] * n_max + row_i[r]) * P;
   float mx = -INFINITY;
@@ -308,18 +334,27 @@ __global__ void k_leaf_prep(const float* __restrict__ log_emit, int P, int Pp, i
   const bool dead = !(mx > -INFINITY);
   const float x = dead ? 0.0f : mx;
   float* out = leafE + (int64_t)r * Pp;
+  const float* cmL = colmax + (int64_t)(per_sentence ? row_b[r] : 0) * 2 * (Np + Pp) + Np;  // preterminal columns of L
+  const float* cmR = cmL + (Np + Pp);
+  int hs = 0, zs = 0;
   for (int t = threadIdx.x; t < Pp; t += blockDim.x) {
     const float v = (t < P && !dead) ? expf(e[t] - x) : 0.0f;
     out[t] = v;
+    hs = max(hs, bexp_sum(cmL[t], v));
+    zs = max(zs, bexp_sum(cmR[t], v));
     if (leafEb) {
       if (planes == 3) put_w(leafEb, plane_stride, (int64_t)r * Pp + t, v);
       else reinterpret_cast<__bf16*>(leafEb)[(int64_t)r * Pp + t] = (__bf16)v;
     }
   }
+  hs = block_max_i(hs, redi);
+  zs = block_max_i(zs, redi);
   if (threadIdx.x == 0) {
     xs[r] = x;
     mexp[r] = dead ? kExpZero : 0;
     tmaxb[r] = dead ? 0u : __float_as_uint(1.0f);  // the largest entry is exactly 1
+    hmaxb[r] = hs;
+    zmaxb[r] = zs;
   }
 }
 
@@ -341,7 +376,8 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
             const int32_t* __restrict__ rowtab, const int32_t* __restrict__ row_b,
             const int32_t* __restrict__ row_i, const float* __restrict__ HZ,
             float* __restrict__ T, int32_t* __restrict__ mexp, uint32_t* __restrict__ tmaxb, void* __restrict__ Tb,
-            int planes, int64_t plane_stride, const uint32_t* __restrict__ hmaxb, const uint32_t* __restrict__ zmaxb) {
+            int planes, int64_t plane_stride, int32_t* __restrict__ hmaxb, int32_t* __restrict__ zmaxb,
+            const float* __restrict__ colmax, int Pp, int per_sentence) {
   extern __shared__ __align__(16) unsigned char smem[];
   float* s_c = reinterpret_cast<float*>(smem);                 // [w-1] coefficient of the left child's eta
   float* s_cz = s_c + (w - 1);                                 // [w-1] coefficient of the right child's zeta
@@ -357,10 +393,9 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
     const int rr = row_of(rowtab, stride, B, w - k, b, i + k, n);  // span (i+k, i+w)
     s_l[k - 1] = lr;
     s_r[k - 1] = rr;
-    const uint32_t hb = hmaxb[lr];
-    const int d = add_exp(proj_exp(mexp[lr], tmaxb[lr], hb), proj_exp(mexp[rr], tmaxb[rr], zmaxb[rr]));
+    const int d = add_exp(proj_exp(mexp[lr], tmaxb[lr], hmaxb[lr]), proj_exp(mexp[rr], tmaxb[rr], zmaxb[rr]));
     s_c[k - 1] = __int_as_float(d);
-    s_cz[k - 1] = __int_as_float(d == kExpZero ? 0 : norm_shift(hb));  // eta's shift, used once m is known
+    s_cz[k - 1] = __int_as_float(proj_shift(tmaxb[lr], hmaxb[lr]));  // eta's shift, used once m is known
     dmax = max(dmax, d);
   }
   const int m = wave_max_i(dmax);
@@ -371,7 +406,7 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
     const int d = __float_as_int(s_c[k]);
     const int gh = __float_as_int(s_cz[k]);
     s_c[k] = (d == kExpZero) ? 0.0f : pow2i(d - m - gh);
-    s_cz[k] = (d == kExpZero) ? 0.0f : norm_scale(zmaxb[s_r[k]]);
+    s_cz[k] = (d == kExpZero) ? 0.0f : pow2i(-proj_shift(tmaxb[s_r[k]], zmaxb[s_r[k]]));
   }
   __syncthreads();
 
@@ -380,6 +415,7 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
   const int kg = lane / LG;            // this lane's group: it takes the split points kg, kg + KG, ...
   const int a = blockIdx.y * (LG * 4) + (lane % LG) * 4;
   float tmax = 0.0f;
+  int hsum = 0, zsum = 0;
   if (a < Np) {  // always true for KG > 1 (the padded width is a multiple of 64): the shuffles below see every lane
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     const float* hz_l = HZ + a;
@@ -435,10 +471,19 @@ k_split_fwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
       if (Tb) store_planes4(Tb, planes, plane_stride, (r - S1) * Np + a, acc);
     }
     tmax = fmaxf(fmaxf(acc.x, acc.y), fmaxf(acc.z, acc.w));
+    // exponent bounds of this vector's two projections (see proj_shift)
+    const float* cmL = colmax + (int64_t)(per_sentence ? b : 0) * 2 * (Np + Pp) + a;
+    const float4 wl = *reinterpret_cast<const float4*>(cmL), wr = *reinterpret_cast<const float4*>(cmL + Np + Pp);
+    hsum = max(max(bexp_sum(wl.x, acc.x), bexp_sum(wl.y, acc.y)), max(bexp_sum(wl.z, acc.z), bexp_sum(wl.w, acc.w)));
+    zsum = max(max(bexp_sum(wr.x, acc.x), bexp_sum(wr.y, acc.y)), max(bexp_sum(wr.z, acc.z), bexp_sum(wr.w, acc.w)));
   }
   tmax = wave_max(tmax);
+  hsum = wave_max_i(hsum);
+  zsum = wave_max_i(zsum);
   if (lane == 0) {
     if (tmax > 0.0f && m != kExpZero) atomicMax(&tmaxb[r], __float_as_uint(tmax));
+    if (hsum > 0 && m != kExpZero) atomicMax(&hmaxb[r], hsum);
+    if (zsum > 0 && m != kExpZero) atomicMax(&zmaxb[r], zsum);
     if (blockIdx.y == 0) mexp[r] = m;
   }
 }
@@ -558,7 +603,7 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
             const float* __restrict__ HZ, const float* __restrict__ BH, const int32_t* __restrict__ mexp,
             const uint32_t* __restrict__ tmaxb, float* __restrict__ UV, int32_t* __restrict__ uexp,
             uint32_t* __restrict__ umaxb, float* __restrict__ gsc, void* __restrict__ UVb, int planes,
-            int64_t plane_stride, const uint32_t* __restrict__ hmaxb, const uint32_t* __restrict__ zmaxb) {
+            int64_t plane_stride, const int32_t* __restrict__ hmaxb, const int32_t* __restrict__ zmaxb) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x;
   const int64_t r = row0 + blockIdx.x;
@@ -588,10 +633,10 @@ k_split_bwd(int w, int64_t row0, int B, int Np, int64_t S1, int stride, const in
     }
     s_p[t] = pr - (int)S1;
     s_s[t] = sr;
-    const uint32_t sb = t < nl ? zmaxb[sr] : hmaxb[sr];  // the sibling's zeta (this span is the left child) or eta
+    const int sb = t < nl ? zmaxb[sr] : hmaxb[sr];  // the sibling's zeta (this span is the left child) or eta
     const int d = add_exp(norm_exp(uexp[pr], umaxb[pr]), proj_exp(mexp[sr], tmaxb[sr], sb));
     s_c[t] = __int_as_float(d);
-    s_cs[t] = norm_scale(sb);
+    s_cs[t] = pow2i(-proj_shift(tmaxb[sr], sb));
     dmax = max(dmax, d);
   }
   const int m = wave_max_i(dmax);
@@ -752,15 +797,18 @@ void launch_plan_sentrows(const Layout& ly, const Ptrs& p, hipStream_t st) {
 
 void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const float* R, hipStream_t st) {
   dim3 grid((ly.Np + ly.Pp) / 32, ly.Np / 32, 2 * ly.G);
-  if (ly.planes == 3)
+  uint32_t* cm = reinterpret_cast<uint32_t*>(p.colmax);
+  const int64_t ncm = 2 * (int64_t)(ly.Np + ly.Pp) * ly.G;
+  launch_k(k_zero_u32, dim3((unsigned)((ncm + 255) / 256 < 1024 ? (ncm + 255) / 256 : 1024)), dim3(256), 0, st, cm, ncm);
+  if (ly.planes == 3)  // the panels once more as three bf16 planes
     launch_k(k_pack_weights<uint16_t>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
-                       (uint16_t*)p.Wn3, (uint16_t*)p.Wp3, (uint16_t*)p.Wtn3, (uint16_t*)p.Wtp3);
+                       (uint16_t*)p.Wn3, (uint16_t*)p.Wp3, (uint16_t*)p.Wtn3, (uint16_t*)p.Wtp3, (uint32_t*)nullptr);
   if (ly.bf16)
     launch_k(k_pack_weights<__bf16>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
-                       (__bf16*)p.Wn, (__bf16*)p.Wp, (__bf16*)p.Wtn, (__bf16*)p.Wtp);
+                       (__bf16*)p.Wn, (__bf16*)p.Wp, (__bf16*)p.Wtn, (__bf16*)p.Wtp, cm);
   else
     launch_k(k_pack_weights<float>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp, p.Wn, p.Wp,
-                       p.Wtn, p.Wtp);
+                       p.Wtn, p.Wtp, cm);
 }
 
 void launch_transpose_bf16(const float* X, int64_t ldx, int cols, const float* sc, int64_t S, int64_t Spad, void* Xt,
@@ -772,7 +820,7 @@ void launch_transpose_bf16(const float* X, int64_t ldx, int cols, const float* s
 void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hipStream_t st) {
   launch_k(k_leaf_prep, dim3((unsigned)ly.S1), dim3(256), 0, st, log_emit, ly.P, ly.Pp, ly.n_max, p.row_b,
                      p.row_i, p.leafE, p.xs, p.mexp, p.tmaxb, static_cast<uint16_t*>(p.leafEb), ly.planes,
-                     (int64_t)ly.S1 * ly.Pp);
+                     (int64_t)ly.S1 * ly.Pp, p.colmax, ly.Np, ly.G > 1 ? 1 : 0, p.hmaxb, p.zmaxb);
 }
 
 void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
@@ -781,12 +829,14 @@ void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int6
   if (rows * chunks < 1024 && w - 1 >= 64) {  // fewer than one wavefront per SIMD, long chains of split points
     const dim3 grid((unsigned)rows, (unsigned)(ly.Np / 64));
     launch_k(k_split_fwd<4>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b, p.row_i, p.HZ,
-             p.T, p.mexp, p.tmaxb, p.Tb, ly.planes, (int64_t)ly.S2 * ly.Np, p.hmaxb, p.zmaxb);
+             p.T, p.mexp, p.tmaxb, p.Tb, ly.planes, (int64_t)ly.S2 * ly.Np, p.hmaxb, p.zmaxb, p.colmax, ly.Pp,
+             ly.G > 1 ? 1 : 0);
     return;
   }
   const dim3 grid((unsigned)rows, (unsigned)chunks);
   launch_k(k_split_fwd<1>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b, p.row_i, p.HZ,
-           p.T, p.mexp, p.tmaxb, p.Tb, ly.planes, (int64_t)ly.S2 * ly.Np, p.hmaxb, p.zmaxb);
+           p.T, p.mexp, p.tmaxb, p.Tb, ly.planes, (int64_t)ly.S2 * ly.Np, p.hmaxb, p.zmaxb, p.colmax, ly.Pp,
+           ly.G > 1 ? 1 : 0);
 }
 
 void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st) {

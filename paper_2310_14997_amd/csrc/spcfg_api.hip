@@ -63,6 +63,7 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   ly.umaxb = take(i4 * ly.Sall);
   ly.hmaxb = take(i4 * ly.Sall);
   ly.zmaxb = take(i4 * ly.Sall);
+  ly.colmax = take(f4 * 2 * (size_t)(ly.Np + ly.Pp) * ly.G);
   ly.gsc = take(f4 * ly.Sall);
   ly.xs = take(f4 * S1);
   // One arrival counter per output tile of the largest launch: at most max(S1, S2) rows (one width; grouped
@@ -115,7 +116,7 @@ Ptrs resolve(const Layout& ly, void* ws) {
   p.row_b = (int32_t*)(b + ly.row_b); p.row_i = (int32_t*)(b + ly.row_i); p.rootmask = (int32_t*)(b + ly.rootmask);
   p.mexp = (int32_t*)(b + ly.mexp); p.uexp = (int32_t*)(b + ly.uexp);
   p.tmaxb = (uint32_t*)(b + ly.tmaxb); p.umaxb = (uint32_t*)(b + ly.umaxb);
-  p.hmaxb = (uint32_t*)(b + ly.hmaxb); p.zmaxb = (uint32_t*)(b + ly.zmaxb);
+  p.hmaxb = (int32_t*)(b + ly.hmaxb); p.zmaxb = (int32_t*)(b + ly.zmaxb); p.colmax = (float*)(b + ly.colmax);
   p.gsc = (float*)(b + ly.gsc); p.xs = (float*)(b + ly.xs);
   p.ztil = (float*)(b + ly.ztil); p.rmax = (float*)(b + ly.rmax);
   p.leafE = (float*)(b + ly.leafE); p.T = (float*)(b + ly.T); p.HZ = (float*)(b + ly.HZ);
@@ -282,7 +283,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     if (ly.bf16) { a.A = p.leafEb; a.a_bf16 = 1; }
     if (ly.planes == 3) { a.A3 = p.leafEb; a.Bm3 = p.Wp3; a.planes3 = 1; a.a_plane = ly.S1 * Pp; a.b_plane = 2 * Np * Pp; }
     a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
-    a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb; a.hmaxb = p.hmaxb; a.zmaxb = p.zmaxb; a.Np = (int)Np;
+    a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb;
     set_groups(a, plan, ly, p, 1, 0, 2 * Np * Pp);
     launch_gemm_nt(a, st);
   }
@@ -305,7 +306,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     }
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
     a.rows = (int)rows; a.cols = (int)(2 * Np); a.K = (int)Np;
-    a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb + row0; a.hmaxb = p.hmaxb + row0; a.zmaxb = p.zmaxb + row0; a.Np = (int)Np;
+    a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb + row0;
     // eta for the prefix and middle rows, zeta for the middle and suffix rows (when Np is not a whole number of
     // 128-column tiles the two column blocks would each pad their last tile: one product of 2Np columns then)
     if (use_parts(ly, w) && Np % 128 == 0) {

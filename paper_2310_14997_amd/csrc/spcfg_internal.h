@@ -7,9 +7,11 @@
 //   leaf row r:        leafE[r] = exp(e_i - max e_i)          (exponent 0; the max is added back into logZ)
 //   span row r (w>=2): T[r]     = sum_k 2^(d_k - m) * eta_ik * zeta_kj,  m = max_k d_k   (exponent mexp[r] = m)
 //   every non-root row: HZ[r]   = [eta | zeta] = 2^-f * [L;R] * (leafE[r] or T[r])        (exponent mexp[r] + f)
-//                      eta and zeta each have a normalising shift of their own on top (from hmaxb[r], zmaxb[r], the
-//                      largest entry of each half, recorded by the GEMM epilogue): a grammar whose weights are tiny
-//                      everywhere gives tiny projections, and the split products eta * zeta must not underflow
+//                      eta and zeta each have a normalising shift of their own on top: the producer of the inside
+//                      vector records hmaxb[r] = max_B (exponent of max_A L[A,B]) + (exponent of its entry B), zmaxb
+//                      likewise with R, which bounds the largest entry of eta (zeta) from below to within a factor 4N.
+//                      A grammar whose weights are tiny everywhere gives tiny projections, and with these shifts the
+//                      split products eta * zeta stay inside the fp32 range
 //   reverse pass:      UV[r]    = unnormalised adjoints of [eta | zeta]                   (exponent uexp[r])
 //                      BH[r]    = 2^-f' * UV[r] * [L;R]  = scaled adjoint of beta         (exponent uexp[r] + f')
 // f (f') is the shift that brings the largest magnitude of T[r] (UV[r]) into [0.5, 1).  The split kernels
@@ -48,6 +50,7 @@ struct Layout {
   // byte offsets into the workspace
   size_t lens, rowbase, row_b, row_i, rootmask, rootrow, mexp, uexp, tmaxb, umaxb, hmaxb, zmaxb, gsc, xs, ztil, rmax;
   size_t leafE, T, HZ, UV, BH, Wn, Wp, Wtn, Wtp, partial, counters;
+  size_t colmax;  // [G][2][Np + Pp]: largest entry of every column of L (then of R), nonterminal columns first
   size_t Wn3, Wp3, Wtn3, Wtp3;  // planes == 3: the packed panels once more, cut into three bf16 planes
   size_t UVt_n, Tt, UVt_p, Et;  // bf16 mode only
   size_t Tb, UVb, leafEb;       // planes > 0: bf16 planes of T, UV, leafE ([planes][rows][cols]), written by their producers
@@ -59,7 +62,9 @@ struct Layout {
 
 struct Ptrs {  // device pointers resolved from a Layout
   int32_t *lens, *rowbase, *row_b, *row_i, *rootmask, *rootrow, *mexp, *uexp;
-  uint32_t *tmaxb, *umaxb, *hmaxb, *zmaxb;
+  uint32_t *tmaxb, *umaxb;
+  int32_t *hmaxb, *zmaxb;  // biased-exponent sums (see above); 0 = the projection is all zero
+  float* colmax;
   float *gsc, *xs, *ztil, *rmax;
   float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp, *partial;  // W* hold bf16 data in bf16 mode
   void *UVt_n, *Tt, *UVt_p, *Et;
@@ -130,9 +135,6 @@ struct NtArgs {
   int epilogue;
   const uint32_t* rowmaxb;  // ROWSCALE, MASKROWS: C = 2^-f(rowmaxb[r]) * acc (normalising shift of the A row)
   const int32_t* rowmask;   // MASKROWS: rows with rowmask[r] != 0 are left untouched
-  // ROWSCALE with hmaxb != null: the bit pattern of the largest value written to columns [0, Np) of row r is
-  // max-ed into hmaxb[r], that of columns [Np, 2 Np) into zmaxb[r] (integer atomicMax: exact, order-independent)
-  uint32_t* hmaxb; uint32_t* zmaxb;
   // LEAF_EMIT: C[dst[r] * ldc + c] = acc * E[r][c] * 2^rowexp[r], c < cols
   const float* E; int64_t lde;
   const int32_t* rowexp;
