@@ -128,6 +128,84 @@ def time_decode(wl, steps):
     return res
 
 
+def measure(d, bf16, fp32_mfma, steps, warmup, profile_steps, graph=False):
+    """Times `steps` forward+backward steps on the batch `d` (inputs resident in HBM), then repeats `profile_steps`
+    steps with HIP events bound to every kernel's own dispatch for the per-class times."""
+    import torch
+    from paper_2310_14997_amd import binding as bd
+    from paper_2310_14997_amd import synth
+    wl = bd.Workload(d, precision=bd.PRECISION_BF16 if bf16 else bd.PRECISION_FP32,
+                     flags=bd.FLAG_FP32_MFMA if fp32_mfma else 0)
+    peak = PEAK_BF16_MFMA_TFLOPS if bf16 else (PEAK_FP32_MFMA_TFLOPS if fp32_mfma else PEAK_SPLIT_TFLOPS)
+    if bf16:
+        kernel_name, mfma = "k_gemm_nt16 (bf16 operands, bf16 MFMA", "bf16"
+    elif fp32_mfma:
+        kernel_name, mfma = "k_gemm_nt (fp32 MFMA", "f32"
+    else:
+        kernel_name, mfma = ("k_gemm_nt3 / k_gemm_nt (fp32 operands as 3 bf16 pieces, 6 bf16 MFMA products per fp32 "
+                             "product; pre-cut planes for 128-row tiles, cut in the kernel for shorter ones"), "bf16 x6"
+    wc = synth.work_counts(d["lengths"], d["N"], d["P"])
+    stream = torch.cuda.current_stream()
+    step = wl.forward_backward
+    if graph:  # the step only enqueues kernels, so it can be captured once and replayed
+        wl.forward_backward()
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            wl.forward_backward()
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            wl.forward_backward()
+        step = g.replay
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    logz = wl.logZ.cpu().numpy()
+    assert np.all(np.isfinite(logz)), "non-finite log Z in the benchmark batch"
+    res = dict(wl=wl, wc=wc, ms_per_step=dt / steps * 1e3, sentences_per_s=d["B"] / (dt / steps), classes=None,
+               roofline=None, gemm_grad=None, split_reduction=None)
+    psteps = steps if profile_steps is None else profile_steps
+    if psteps <= 0:
+        return res
+    # per-kernel-class device time: the same steps again, every launch carrying start/stop HIP events bound to
+    # its own dispatch on the launch stream (kept out of the timed region above: the events perturb the schedule)
+    bd.spcfg_profile_enable(True)
+    for _ in range(psteps):
+        wl.forward_backward()
+    torch.cuda.synchronize()
+    prof = bd.spcfg_profile_read()
+    bd.spcfg_profile_enable(False)
+    classes = {k: dict(ms_per_step=v["ms"] / psteps, launches_per_step=v["launches"] / psteps,
+                       work_per_step=v["work"] / psteps) for k, v in prof.items()}
+    proj_ms = classes["gemm_fwd"]["ms_per_step"] + classes["gemm_bwd"]["ms_per_step"]
+    proj_flop = classes["gemm_fwd"]["work_per_step"] + classes["gemm_bwd"]["work_per_step"]
+    proj_launches = classes["gemm_fwd"]["launches_per_step"] + classes["gemm_bwd"]["launches_per_step"]
+    achieved = proj_flop / (proj_ms * 1e-3) / 1e12
+    split_ms = classes["split_fwd"]["ms_per_step"] + classes["split_bwd"]["ms_per_step"]
+    split_bytes = classes["split_fwd"]["work_per_step"] + classes["split_bwd"]["work_per_step"]
+    gg = classes["gemm_grad"]
+    gg_tflops = gg["work_per_step"] / (gg["ms_per_step"] * 1e-3) / 1e12
+    res["classes"] = classes
+    res["roofline"] = {"bound": "mfma", "kernel": kernel_name + "; stacked projection, forward + reverse)", "mfma": mfma,
+                       "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                       "launches_per_step": proj_launches, "avg_launch_us": proj_ms * 1e3 / max(proj_launches, 1),
+                       "flop_per_launch": proj_flop / max(proj_launches, 1)}
+    res["gemm_grad"] = {"bound": "mfma", "kernel": "rule-gradient product (k_gemm_tn; bf16 mode: transposes + k_gemm_nt16)",
+                        "mfma": mfma, "achieved": gg_tflops, "peak": peak, "unit": "TFLOP/s", "frac": gg_tflops / peak,
+                        "ms_per_step": gg["ms_per_step"]}
+    res["split_reduction"] = {"bound": "hbm", "achieved": split_bytes / (split_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                              "unit": "GB/s", "frac": split_bytes / (split_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                              "ms_per_step": split_ms}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,6 +231,9 @@ def main():
     ap.add_argument("--decode", action="store_true",
                     help="also time the span-posterior export and the best-tree decoder on the step's workspace; "
                          "reported under \"decode\", not part of the step")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the extra measurements of the default run (fp32-matrix-instruction variant, other seeds "
+                         "of the length law, the other configurations): for profiler runs")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of known size (1 GiB read + 1 GiB written per launch, 5 "
                          "launches): the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -179,61 +260,8 @@ def main():
     d = synth.make_inputs_per_sentence(args.workload) if args.per_sentence else synth.make_inputs(args.workload)
     precision = args.precision or d["precision"]
     bf16 = precision == "bf16"
-    wl = bd.Workload(d, precision=bd.PRECISION_BF16 if bf16 else bd.PRECISION_FP32,
-                     flags=bd.FLAG_FP32_MFMA if args.fp32_mfma else 0)
-    peak = PEAK_BF16_MFMA_TFLOPS if bf16 else (PEAK_FP32_MFMA_TFLOPS if args.fp32_mfma else PEAK_SPLIT_TFLOPS)
-    if bf16:
-        kernel_name, mfma = "k_gemm_nt16 (bf16 operands, bf16 MFMA", "bf16"
-    elif args.fp32_mfma:
-        kernel_name, mfma = "k_gemm_nt (fp32 MFMA", "f32"
-    else:
-        kernel_name, mfma = "k_gemm_nt (fp32 operands cut into 3 bf16 pieces, 6 bf16 MFMA products per fp32 product", "bf16 x6"
-    wc = synth.work_counts(d["lengths"], d["N"], d["P"])
-    stream = torch.cuda.current_stream()
-
-    step = wl.forward_backward
-    if args.graph:  # the step only enqueues kernels, so it can be captured once and replayed
-        wl.forward_backward()
-        side = torch.cuda.Stream()
-        side.wait_stream(stream)
-        with torch.cuda.stream(side):
-            wl.forward_backward()
-        stream.wait_stream(side)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=side):
-            wl.forward_backward()
-        step = graph.replay
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    sent_per_s = d["B"] / (dt / args.steps)
-    logz = wl.logZ.cpu().numpy()
-    assert np.all(np.isfinite(logz)), "non-finite log Z in the benchmark batch"
-
-    # per-kernel-class device time: the same steps again, every launch carrying start/stop HIP events bound to
-    # its own dispatch on the launch stream (kept out of the timed region above: the events perturb the schedule)
-    bd.spcfg_profile_enable(True)
-    psteps = max(args.profile_steps if args.profile_steps is not None else args.steps, 1)
-    for _ in range(psteps):
-        wl.forward_backward()
-    torch.cuda.synchronize()
-    prof = bd.spcfg_profile_read()
-    bd.spcfg_profile_enable(False)
-    classes = {k: dict(ms_per_step=v["ms"] / psteps, launches_per_step=v["launches"] / psteps,
-                       work_per_step=v["work"] / psteps) for k, v in prof.items()}
-    proj_ms = classes["gemm_fwd"]["ms_per_step"] + classes["gemm_bwd"]["ms_per_step"]
-    proj_flop = classes["gemm_fwd"]["work_per_step"] + classes["gemm_bwd"]["work_per_step"]
-    proj_launches = classes["gemm_fwd"]["launches_per_step"] + classes["gemm_bwd"]["launches_per_step"]
-    achieved_tflops = proj_flop / (proj_ms * 1e-3) / 1e12
-    split_ms = classes["split_fwd"]["ms_per_step"] + classes["split_bwd"]["ms_per_step"]
-    split_bytes = classes["split_fwd"]["work_per_step"] + classes["split_bwd"]["work_per_step"]
+    m = measure(d, bf16, args.fp32_mfma, args.steps, args.warmup, args.profile_steps, graph=args.graph)
+    wl, wc, classes = m["wl"], m["wc"], m["classes"]
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
@@ -245,25 +273,48 @@ def main():
         # the headline metric's name for the headline workload; `value` is its sentences/s part, the two
         # fractions it also names are `roofline.frac` (MFMA) and `split_reduction.frac` (HBM)
         "metric": f"sentences/sec inside fwd+bwd at N=P={d['N']}, n<={d['n_max']}; % MFMA peak, % HBM peak",
-        "value": sent_per_s, "unit": "sentences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": m["sentences_per_s"], "unit": "sentences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic", "launch": "hip graph replay" if args.graph else "eager",
         "grammars": "one per sentence" if args.per_sentence else "shared",
         "config": {"workload": f"{args.workload}: B={d['B']}, N={d['N']}, P={d['P']}, n_max={d['n_max']}, "
                                f"sum_n={wc['leaves']}, projected_spans={wc['proj_spans']}, "
                                f"split_terms={wc['split_terms']}, seed={d['seed']}",
-                   "flop_fwd_bwd": wc["flop_fwd_bwd"], "tflops_fwd_bwd": wc["flop_fwd_bwd"] / (dt / args.steps) / 1e12},
-        "roofline": {"bound": "mfma",
-                     "kernel": kernel_name + "; stacked projection, forward + reverse)", "mfma": mfma,
-                     "achieved": achieved_tflops, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved_tflops / peak, "traffic": traffic,
-                     "launches_per_step": proj_launches, "avg_launch_us": proj_ms * 1e3 / max(proj_launches, 1),
-                     "flop_per_launch": proj_flop / max(proj_launches, 1)},
-        "split_reduction": {"bound": "hbm", "achieved": split_bytes / (split_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                            "unit": "GB/s", "frac": split_bytes / (split_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                            "ms_per_step": split_ms},
+                   "flop_fwd_bwd": wc["flop_fwd_bwd"], "tflops_fwd_bwd": wc["flop_fwd_bwd"] / (m["ms_per_step"] * 1e-3) / 1e12},
+        "roofline": dict(m["roofline"], traffic=traffic),
+        "gemm_grad": m["gemm_grad"],
+        "split_reduction": m["split_reduction"],
         "kernel_classes": classes,
     }
+    if args.workload == "ptb" and not args.headline_only and not (bf16 or args.fp32_mfma or args.per_sentence or args.graph):
+        # the same batch on fp32 matrix instructions (SPCFG_FLAG_FP32_MFMA), against that instruction's own peak
+        v = measure(d, False, True, 5, 2, 5)
+        out["variants"] = {"fp32_mfma": {"ms_per_step": v["ms_per_step"], "sentences_per_s": v["sentences_per_s"],
+                                         "roofline": v["roofline"], "gemm_grad": v["gemm_grad"]}}
+        del v
+        # other draws of the same length law (the headline seed is one draw; its batch is lighter than the mean)
+        vals, flops, toks = [], [], []
+        for i in range(8):
+            di = synth.make_inputs("ptb", seed=d["seed"] + 1000 + i)
+            mi = measure(di, False, False, 5, 2, 0)
+            vals.append(mi["sentences_per_s"]); flops.append(mi["wc"]["flop_fwd_bwd"]); toks.append(mi["wc"]["leaves"])
+            del mi, di
+        out["law_mean"] = {"seeds": 8, "sentences_per_s": float(np.mean(vals)), "sentences_per_s_min": float(np.min(vals)),
+                           "sentences_per_s_max": float(np.max(vals)), "flop_fwd_bwd": float(np.mean(flops)),
+                           "tokens_per_batch": float(np.mean(toks)),
+                           "note": "mean over 8 further seeds of the PTB length law, 5 timed steps each"}
+        # the other configurations, each in the launch configuration its parity test uses
+        out["workloads"] = {}
+        for name in ("small", "scaled", "long"):
+            dn = synth.make_inputs(name)
+            mn = measure(dn, dn["precision"] == "bf16", False, 5, 2, 5)
+            out["workloads"][name] = {"dtype": "bf16" if dn["precision"] == "bf16" else "f32",
+                                      "ms_per_step": mn["ms_per_step"], "sentences_per_s": mn["sentences_per_s"],
+                                      "mfma_frac": mn["roofline"]["frac"], "mfma_peak": mn["roofline"]["peak"],
+                                      "projection_tflops": mn["roofline"]["achieved"],
+                                      "hbm_frac": mn["split_reduction"]["frac"],
+                                      "split_GBps": mn["split_reduction"]["achieved"]}
+            del mn, dn
     if args.frontend:
         out["frontend"] = time_frontend(args.workload, wl, args.steps)
     if args.decode:
