@@ -329,12 +329,16 @@ bool gemm_nt_keep_parts(NtArgs& a) {
   return false;
 }
 
+bool gemm_nt_reads_planes(const NtArgs& a) {
+  return a.planes3 && !a.b_bf16 && a.rows > 0 && a.cols > 0 && nt::chosen_bm(a) == 128;
+}
+
 void launch_gemm_nt(const NtArgs& a, hipStream_t st) {
   if (a.rows <= 0 || a.cols <= 0) return;
   if (a.b_bf16) { launch_gemm_nt16(a, st); return; }
   if (a.planes3) {
     // tall row tiles: the kernel on pre-cut operands; short ones keep the fp32 operands (fewer panel bytes)
-    if (nt::chosen_bm(a) == 128) { launch_gemm_nt3(a, st); return; }
+    if (gemm_nt_reads_planes(a)) { launch_gemm_nt3(a, st); return; }
     NtArgs b = a;
     b.planes3 = 0;
     launch_gemm_nt(b, st);

@@ -817,25 +817,27 @@ void launch_transpose_bf16(const float* X, int64_t ldx, int cols, const float* s
   launch_k(k_transpose_bf16, grid, dim3(256), 0, st, X, ldx, sc, S, Spad, (__bf16*)Xt);
 }
 
-void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hipStream_t st) {
+void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, bool write_planes, hipStream_t st) {
   launch_k(k_leaf_prep, dim3((unsigned)ly.S1), dim3(256), 0, st, log_emit, ly.P, ly.Pp, ly.n_max, p.row_b,
-                     p.row_i, p.leafE, p.xs, p.mexp, p.tmaxb, static_cast<uint16_t*>(p.leafEb), ly.planes,
+                     p.row_i, p.leafE, p.xs, p.mexp, p.tmaxb, static_cast<uint16_t*>(write_planes ? p.leafEb : nullptr), ly.planes,
                      (int64_t)ly.S1 * ly.Pp, p.colmax, ly.Np, ly.G > 1 ? 1 : 0, p.hmaxb, p.zmaxb);
 }
 
-void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
+void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, bool write_planes,
+                      hipStream_t st) {
+  void* Tb = write_planes ? p.Tb : nullptr;
   const size_t sh = (size_t)(w - 1) * 16;
   const int chunks = (ly.Np + kChunk - 1) / kChunk;
   if (rows * chunks < 1024 && w - 1 >= 64) {  // fewer than one wavefront per SIMD, long chains of split points
     const dim3 grid((unsigned)rows, (unsigned)(ly.Np / 64));
     launch_k(k_split_fwd<4>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b, p.row_i, p.HZ,
-             p.T, p.mexp, p.tmaxb, p.Tb, ly.planes, (int64_t)ly.S2 * ly.Np, p.hmaxb, p.zmaxb, p.colmax, ly.Pp,
+             p.T, p.mexp, p.tmaxb, Tb, ly.planes, (int64_t)ly.S2 * ly.Np, p.hmaxb, p.zmaxb, p.colmax, ly.Pp,
              ly.G > 1 ? 1 : 0);
     return;
   }
   const dim3 grid((unsigned)rows, (unsigned)chunks);
   launch_k(k_split_fwd<1>, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b, p.row_i, p.HZ,
-           p.T, p.mexp, p.tmaxb, p.Tb, ly.planes, (int64_t)ly.S2 * ly.Np, p.hmaxb, p.zmaxb, p.colmax, ly.Pp,
+           p.T, p.mexp, p.tmaxb, Tb, ly.planes, (int64_t)ly.S2 * ly.Np, p.hmaxb, p.zmaxb, p.colmax, ly.Pp,
            ly.G > 1 ? 1 : 0);
 }
 
@@ -856,11 +858,12 @@ void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, con
                      accumulate, ly.G > 1 ? 1 : 0);
 }
 
-void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st) {
+void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, bool write_planes,
+                      hipStream_t st) {
   const size_t sh = (size_t)ly.n_max * 16;
   const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
   launch_k(k_split_bwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b,
-                     p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc, p.UVb, ly.planes,
+                     p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc, write_planes ? p.UVb : nullptr, ly.planes,
                      (int64_t)ly.Sall * 2 * ly.Np, p.hmaxb, p.zmaxb);
 }
 

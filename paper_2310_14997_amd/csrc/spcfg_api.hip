@@ -268,35 +268,38 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
   const int n_max = ly.n_max;
   const int64_t Np = ly.Np, Pp = ly.Pp;
   const int fp32_mfma = (cfg->flags & SPCFG_FLAG_FP32_MFMA) ? 1 : 0;
+  // width 1: [eta | zeta] = [L_P ; R_P] * emission vector
+  NtArgs leaf{};
+  leaf.partial = p.partial; leaf.counters = p.counters; leaf.max_wgs = ly.gemm_wgs; leaf.n_counters = ly.n_counters; leaf.b_bf16 = ly.bf16; leaf.fp32_mfma = fp32_mfma;
+  leaf.A = p.leafE; leaf.lda = Pp; leaf.Bm = p.Wp; leaf.ldb = Pp; leaf.C = p.HZ; leaf.ldc = 2 * Np;
+  if (ly.bf16) { leaf.A = p.leafEb; leaf.a_bf16 = 1; }
+  if (ly.planes == 3) { leaf.A3 = p.leafEb; leaf.Bm3 = p.Wp3; leaf.planes3 = 1; leaf.a_plane = ly.S1 * Pp; leaf.b_plane = 2 * Np * Pp; }
+  leaf.rows = (int)ly.S1; leaf.cols = (int)(2 * Np); leaf.K = (int)Pp;
+  leaf.epilogue = NT_EPI_ROWSCALE; leaf.rowmaxb = p.tmaxb;
+  set_groups(leaf, plan, ly, p, 1, 0, 2 * Np * Pp);
   {
     Scope s(st, SPCFG_PROF_SETUP, 4.0 * 2 * (double)ly.N * (ly.N + ly.P) * 3 + 8.0 * ly.S1 * ly.P, 4);
     launch_plan(ly, p, plan.lens, st);
     if (ly.G > 1) launch_plan_sentrows(ly, p, st);
     launch_pack_weights(ly, p, L, R, st);
-    launch_leaf_prep(ly, p, log_emit, st);
+    // operand planes are written only for the launches that read them (bf16 mode: all of them)
+    launch_leaf_prep(ly, p, log_emit, ly.bf16 || gemm_nt_reads_planes(leaf), st);
   }
-  {  // width 1: [eta | zeta] = [L_P ; R_P] * emission vector
+  {
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.P * ly.S1);
-    NtArgs a{};
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
-    a.A = p.leafE; a.lda = Pp; a.Bm = p.Wp; a.ldb = Pp; a.C = p.HZ; a.ldc = 2 * Np;
-    if (ly.bf16) { a.A = p.leafEb; a.a_bf16 = 1; }
-    if (ly.planes == 3) { a.A3 = p.leafEb; a.Bm3 = p.Wp3; a.planes3 = 1; a.a_plane = ly.S1 * Pp; a.b_plane = 2 * Np * Pp; }
-    a.rows = (int)ly.S1; a.cols = (int)(2 * Np); a.K = (int)Pp;
-    a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb;
-    set_groups(a, plan, ly, p, 1, 0, 2 * Np * Pp);
-    launch_gemm_nt(a, st);
+    launch_gemm_nt(leaf, st);
   }
   for (int w = 2; w <= n_max; ++w) {
     const int64_t row0 = plan.off[w], rows = plan.cnt[w];
     if (rows == 0) continue;
-    {
-      Scope s(st, SPCFG_PROF_SPLIT_FWD, 4.0 * ly.N * (double)rows * (2.0 * (w - 1) + 1.0));
-      launch_split_fwd(ly, p, w, row0, rows, st);
+    const double split_bytes = 4.0 * ly.N * (double)rows * (2.0 * (w - 1) + 1.0);
+    if (w == n_max) {  // every span of the largest width is a root span: never a child, not projected
+      Scope s(st, SPCFG_PROF_SPLIT_FWD, split_bytes);
+      launch_split_fwd(ly, p, w, row0, rows, false, st);
+      break;
     }
-    if (w == n_max) break;  // every span of the largest width is a root span: never a child, not projected
-    Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.N * rows);
     NtArgs a{};
+    double skipped = 0.0;
     a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.a_bf16 = 1; }
@@ -313,12 +316,17 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
       const WidthBlocks k = width_blocks(plan, ly, w);
       const int kt = (int)(Np / 32);
       // the profile counts the executed flop: one of the two projections is left out for k.nP + k.nS rows
-      if (g_prof.on) g_prof.work[SPCFG_PROF_GEMM_FWD] -= 2.0 * ly.N * (double)ly.N * (k.nP + k.nS);
+      skipped = 2.0 * ly.N * (double)ly.N * (k.nP + k.nS);
       a.parts = 2; a.cols = (int)Np;
       set_part(a, 0, 0, k.nP + k.nM, 0, 0, kt);
       set_part(a, 1, k.nP, k.nM + k.nS, (int)Np, 0, kt);
     }
     set_groups(a, plan, ly, p, w, row0, 2 * Np * Np);
+    {
+      Scope s(st, SPCFG_PROF_SPLIT_FWD, split_bytes);
+      launch_split_fwd(ly, p, w, row0, rows, ly.bf16 || gemm_nt_reads_planes(a), st);
+    }
+    Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.N * rows - skipped);
     launch_gemm_nt(a, st);
   }
   {
@@ -344,17 +352,15 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
   for (int w = n_max - 1; w >= 1; --w) {  // spans of width n_max are all roots
     const int64_t row0 = plan.off[w], rows = plan.cnt[w];
     if (rows == 0) continue;
-    {
-      // per span: (n - w) terms, two vector reads each, plus the two output vectors
-      double terms = 0;
-      for (int b = 0; b < ly.B; ++b) {
-        const int n = plan.lens.v[b];
-        if (n > w) terms += (double)(n - w + 1) * (n - w);
-      }
-      Scope s(st, SPCFG_PROF_SPLIT_BWD, 4.0 * ly.N * (2.0 * terms + 2.0 * rows));  // reads + the two output vectors
-      launch_split_bwd(ly, p, w, row0, rows, st);
+    // per span: (n - w) terms, two vector reads each, plus the two output vectors
+    double terms = 0;
+    for (int b = 0; b < ly.B; ++b) {
+      const int n = plan.lens.v[b];
+      if (n > w) terms += (double)(n - w + 1) * (n - w);
     }
+    const double split_bytes = 4.0 * ly.N * (2.0 * terms + 2.0 * rows);  // reads + the two output vectors
     NtArgs a{};
+    double gemm_flop;
     a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.UV + row0 * 2 * Np; a.lda = 2 * Np; a.K = (int)(2 * Np); a.rows = (int)rows;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np; a.a_bf16 = 1; }
@@ -363,7 +369,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       a.planes3 = 1; a.a_plane = ly.Sall * 2 * Np; a.b_plane = 2 * Np * (w >= 2 ? Np : Pp);
     }
     if (w >= 2) {
-      Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.N * rows);
+      gemm_flop = 4.0 * ly.N * (double)ly.N * rows;
       a.Bm = p.Wtn; a.ldb = 2 * Np; a.C = p.BH + (row0 - ly.S1) * Np; a.ldc = Np; a.cols = (int)Np;
       a.epilogue = NT_EPI_MASKROWS; a.rowmask = p.rootmask + row0; a.rowmaxb = p.umaxb + row0;
       if (use_parts(ly, w)) {  // prefix rows: only the eta adjoint (first half of K); suffix rows: only zeta's
@@ -374,16 +380,22 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
         set_part(a, 1, k.nP, k.nM, 0, 0, 2 * kt);
         set_part(a, 2, k.nP + k.nM, k.nS, 0, kt, kt);
         // (the profile counts the executed flop)
-        if (gemm_nt_keep_parts(a) && g_prof.on) g_prof.work[SPCFG_PROF_GEMM_BWD] -= 2.0 * ly.N * (double)ly.N * (k.nP + k.nS);
+        if (gemm_nt_keep_parts(a)) gemm_flop -= 2.0 * ly.N * (double)ly.N * (k.nP + k.nS);
       }
       set_groups(a, plan, ly, p, w, row0, 2 * Np * Np);
-      launch_gemm_nt(a, st);
     } else {
-      Scope s(st, SPCFG_PROF_GEMM_BWD, 4.0 * ly.N * (double)ly.P * rows);
+      gemm_flop = 4.0 * ly.N * (double)ly.P * rows;
       a.Bm = p.Wtp; a.ldb = 2 * Np; a.C = grad_log_emit; a.ldc = ly.P; a.cols = ly.P;
       a.epilogue = NT_EPI_LEAF_EMIT; a.E = p.leafE; a.lde = Pp; a.rowexp = p.uexp;
       a.row_b = p.row_b; a.row_i = p.row_i; a.n_max = n_max;
       set_groups(a, plan, ly, p, 1, 0, 2 * Np * Pp);
+    }
+    {
+      Scope s(st, SPCFG_PROF_SPLIT_BWD, split_bytes);
+      launch_split_bwd(ly, p, w, row0, rows, ly.bf16 || gemm_nt_reads_planes(a), st);
+    }
+    {
+      Scope s(st, SPCFG_PROF_GEMM_BWD, gemm_flop);
       launch_gemm_nt(a, st);
     }
   }

@@ -112,13 +112,16 @@ void launch_plan_sentrows(const Layout& ly, const Ptrs& p, hipStream_t st);
 void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const float* R, hipStream_t st);
 void launch_transpose_bf16(const float* X, int64_t ldx, int cols, const float* sc, int64_t S, int64_t Spad, void* Xt,
                            hipStream_t st);
-void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, hipStream_t st);
-void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st);
+void launch_leaf_prep(const Layout& ly, const Ptrs& p, const float* log_emit, bool write_planes, hipStream_t st);
+// write_planes: also write the operand planes of the rows (the projection launch of this width reads them)
+void launch_split_fwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, bool write_planes,
+                      hipStream_t st);
 // log_root (and grad_log_root) hold one vector per grammar: [G x N]
 void launch_root_fwd(const Layout& ly, const Ptrs& p, const float* log_root, float* logZ, hipStream_t st);
 void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, const float* grad_logZ,
                      float* grad_log_root, int accumulate, hipStream_t st);
-void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, hipStream_t st);
+void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int64_t rows, bool write_planes,
+                      hipStream_t st);
 void launch_zero_pad_emit(const Layout& ly, const Ptrs& p, float* grad_log_emit, hipStream_t st);
 void launch_span_marginals(const Layout& ly, const Ptrs& p, float* mu, int32_t* label, hipStream_t st);
 
@@ -172,6 +175,7 @@ void launch_gemm_nt(const NtArgs& a, hipStream_t st);
 void launch_gemm_nt16(const NtArgs& a, hipStream_t st);  // bf16-operand variant (called through launch_gemm_nt)
 void launch_gemm_nt3(const NtArgs& a, hipStream_t st);   // pre-cut three-plane operands (called through launch_gemm_nt)
 bool gemm_nt_keep_parts(NtArgs& a);             // drops the parts of a launch that would not save work
+bool gemm_nt_reads_planes(const NtArgs& a);     // whether launch_gemm_nt will read the three-plane operands (A3 / Bm3)
 int gemm_nt_tiles(int rows, int cols);           // number of output tiles (= arrival counters needed)
 size_t gemm_nt_partial_bytes(int max_wgs);       // scratch needed for partial tiles
 constexpr int kGemmWgs = 512;                    // workgroups per projection launch: 2 per CU on 256 CUs
