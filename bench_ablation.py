@@ -8,12 +8,13 @@ The paper compares three ways of running the same inside pass (Sec. 3.2, Table 1
     automatic differentiation (every intermediate of every width is kept for the backward pass);
   * the fused, recomputing implementation: here the HIP library (spcfg_inside_forward_backward).
 The first two are written below with plain PyTorch tensor ops on the GPU, as the paper's baselines were; they
-are comparison code, not part of the library, and double as an independent check of log Z.  Sentences all have
+are comparison code beside the benchmark, not part of the library package, and double as an independent check of
+log Z.  Sentences all have
 length l; sizes follow the table (|N| = |P|).  Prints one JSON object per configuration with the time of a
 forward+backward step and the peak device memory of each variant, and the ratios in the table's normalisation
 (speed relative to the slowest variant, memory relative to the fused one).
 
-    python -m paper_2310_14997_amd.ablation --sizes 512:20,512:40 --batch 8
+    python bench_ablation.py --sizes 512:20,512:40 --batch 8
 """
 from __future__ import annotations
 
@@ -22,7 +23,11 @@ import json
 import sys
 import time
 
+import os
+
 import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def inside_torch(log_root, L, R, log_emit, variant):
@@ -82,13 +87,14 @@ def run_torch(d, variant, steps):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) / steps * 1e3
+    g = lambda x: x.grad.detach().cpu().numpy().astype(np.float64)
     return dict(ms=ms, peak_bytes=int(peak), logZ=logZ.detach().cpu().numpy().astype(np.float64),
-                grad_L=L.grad.detach().cpu().numpy().astype(np.float64))
+                grad_L=g(L), grad_R=g(R), grad_log_root=g(log_root), grad_log_emit=g(log_emit))
 
 
 def run_fused(d, steps):
     import torch
-    from . import binding as bd
+    from paper_2310_14997_amd import binding as bd
     torch.cuda.synchronize()
     torch.cuda.reset_peak_memory_stats()
     base = torch.cuda.memory_allocated()
@@ -107,7 +113,7 @@ def run_fused(d, steps):
 
 
 def one_config(N, l, batch, steps, with_logsumexp):
-    from . import synth
+    from paper_2310_14997_amd import synth
     d = synth.make_inputs("tiny", seed=synth.BASE_SEED + 300 + N + l, N=N, P=N, B=batch, lengths=[l] * batch, V=2000)
     out = {"N": N, "P": N, "l": l, "batch": batch, "variants": {}}
     res = {"fused": run_fused(d, steps), "log-einsum-exp": run_torch(d, "logeinsumexp", steps)}

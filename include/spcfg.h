@@ -155,7 +155,8 @@ const char* spcfg_last_hip_error(void);
  *   ms[c]      total device time of the class since spcfg_profile_enable(1)
  *   launches[c] number of launches
  *   work[c]    algorithmic work enqueued: flop for the GEMM classes, bytes for the others
- * and resets the counters.  Arrays must hold SPCFG_PROF_CLASSES entries.
+ * and resets the counters.  Arrays must hold SPCFG_PROF_CLASSES entries.  The counters are the library's only state:
+ * process-wide and guarded by a mutex; launches of all threads made while profiling is enabled add up.
  */
 enum {
   SPCFG_PROF_SETUP = 0,      /* span plan, weight packing, leaf preparation                            */

@@ -9,9 +9,6 @@
 // arrival order) and runs the epilogue.  Nobody waits on anybody: there is no spinning.
 #pragma once
 #include "spcfg_internal.h"
-#ifdef SPCFG_TUNING
-#include <cstdlib>
-#endif
 
 namespace spcfg {
 namespace nt {
@@ -326,11 +323,6 @@ void launch_shared(Kernel kernel, const NtArgs& a, int BM, int BKelems, size_t l
   const int cap = a.max_wgs * (128 / BM);  // the partial-tile scratch holds 2 * max_wgs slots of 128 x 128
   if (Gn > cap) Gn = cap;
   if (Gn > total / 2) Gn = total / 2 > 0 ? total / 2 : 1;  // at least two K-steps per share
-#ifdef SPCFG_TUNING
-  if (getenv("SPCFG_NT_G")) Gn = atoi(getenv("SPCFG_NT_G"));
-  if (Gn > cap) Gn = cap;
-  if (Gn > total) Gn = total;
-#endif
   int ipw = (total + Gn - 1) / Gn;
   Gn = (total + ipw - 1) / ipw;
   launch_k(kernel, dim3(Gn), dim3(256), lds_bytes, st, a, ipw, total);
@@ -339,9 +331,6 @@ void launch_shared(Kernel kernel, const NtArgs& a, int BM, int BKelems, size_t l
 inline int chosen_bm(const NtArgs& a) {
   // wide = more columns than K (the forward projection; a two-part launch is one)
   int bm = pick_bm(a.grouped ? a.grp_max_rows : a.rows, work_of(a), a.a_bf16 != 0, a.parts == 2 || a.cols > a.K);
-#ifdef SPCFG_TUNING
-  if (getenv("SPCFG_NT_BM")) bm = atoi(getenv("SPCFG_NT_BM"));
-#endif
   return bm;
 }
 

@@ -2,6 +2,7 @@
 // span-level parallelism: one launch handles every span of one width across the batch) and optional
 // per-kernel-class timing with HIP events.
 #include <cstdio>
+#include <atomic>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -158,9 +159,12 @@ int make_plan(const spcfg_config* cfg, const int32_t* lengths, int B, int n_max,
 // ---- profiling -------------------------------------------------------------------------------------
 // A Scope names the kernel class of the launches made during its lifetime; every such launch gets its own
 // start/stop event pair (see launch_k), so a class's time is the sum of its kernels' own durations.
+// The counters are process-wide; a mutex guards them, and the class that a thread's launches are charged to is that
+// thread's own, so concurrent callers do not corrupt the records (their launches simply add up).
+thread_local int t_cur_cls = -1;
 struct Prof {
-  bool on = false;
-  int cur_cls = -1;
+  std::atomic<bool> on{false};
+  std::mutex mu;
   struct Rec { hipEvent_t a, b; int cls; };
   std::vector<Rec> recs;
   std::vector<hipEvent_t> pool;
@@ -180,13 +184,14 @@ struct Prof {
 
 struct Scope {
   int prev;
-  Scope(hipStream_t, int c, double work, int nlaunch = 1) : prev(g_prof.cur_cls) {
+  Scope(hipStream_t, int c, double work, int nlaunch = 1) : prev(t_cur_cls) {
     if (!g_prof.on) return;
-    g_prof.cur_cls = c;
+    t_cur_cls = c;
+    std::lock_guard<std::mutex> lock(g_prof.mu);
     g_prof.work[c] += work;
     g_prof.launches[c] += nlaunch;
   }
-  ~Scope() { g_prof.cur_cls = prev; }
+  ~Scope() { t_cur_cls = prev; }
 };
 
 }  // namespace
@@ -195,7 +200,8 @@ void launch_refused(const char* what) { g_refused = what; }
 
 LaunchEvents prof_launch_events() {
   LaunchEvents ev;
-  if (!g_prof.on || g_prof.cur_cls < 0) return ev;
+  if (!g_prof.on || t_cur_cls < 0) return ev;
+  std::lock_guard<std::mutex> lock(g_prof.mu);
   ev.start = g_prof.get();
   ev.stop = g_prof.get();
   if (!ev.start || !ev.stop) {
@@ -203,7 +209,7 @@ LaunchEvents prof_launch_events() {
     if (ev.stop) g_prof.pool.push_back(ev.stop);
     return LaunchEvents{};
   }
-  g_prof.recs.push_back({ev.start, ev.stop, g_prof.cur_cls});
+  g_prof.recs.push_back({ev.start, ev.stop, t_cur_cls});
   return ev;
 }
 
@@ -456,7 +462,9 @@ using namespace spcfg;
 // One array per GPU (every device that loads the library's code object holds its own copy at its own address).
 // In host code the array's name only stands for the symbol: the device address comes from hipGetSymbolAddress,
 // once per device, and that pointer is what the kernels get.
+#ifndef SPCFG_HOST_CHECKS_BUILD  // (the host-only build of tests/sanitize has no device code object to hold it)
 static __device__ __align__(256) unsigned char scratch[SPCFG_STATIC_SCRATCH_BYTES];
+#endif
 
 namespace {
 constexpr int kStaticGemmWgs = 64;   // partial-tile scratch of the static buffer: 2 * 64 slots of 64 KiB = 8 MiB
@@ -476,7 +484,11 @@ void* static_scratch() {
   std::lock_guard<std::mutex> lock(g_scratch_mutex);
   if (!g_scratch_ptr[dev]) {
     void* ptr = nullptr;
+#ifndef SPCFG_HOST_CHECKS_BUILD
     const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+#else
+    const hipError_t e = hipErrorNotSupported;
+#endif
     if (e != hipSuccess || !ptr) {
       snprintf(g_hip_err, sizeof(g_hip_err), "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
       (void)hipGetLastError();
@@ -615,6 +627,7 @@ const char* spcfg_strerror(int code) {
 const char* spcfg_last_hip_error(void) { return g_hip_err; }
 
 int spcfg_profile_enable(int on) {
+  std::lock_guard<std::mutex> lock(g_prof.mu);
   g_prof.on = on != 0;
   if (g_prof.on) {
     g_prof.recycle();
@@ -625,6 +638,7 @@ int spcfg_profile_enable(int on) {
 
 int spcfg_profile_read(double* ms, int64_t* launches, double* work) {
   if (!ms || !launches || !work) return SPCFG_ERR_ARG;
+  std::lock_guard<std::mutex> lock(g_prof.mu);
   for (int c = 0; c < SPCFG_PROF_CLASSES; ++c) ms[c] = 0.0;
   int rc = SPCFG_OK;
   for (auto& r : g_prof.recs) {

@@ -7,7 +7,8 @@ import pytest
 import torch
 
 from oracle import spcfg_oracle as O
-from paper_2310_14997_amd import ablation, synth
+import bench_ablation as ablation
+from paper_2310_14997_amd import synth
 
 
 @pytest.mark.parametrize("variant", ["logsumexp", "logeinsumexp"])
@@ -33,3 +34,18 @@ def test_ablation_runs_and_variants_agree_on_the_gpu():
         assert v["max_abs_logZ_diff_vs_fused"] < 2e-3, name   # the fp32 framework baselines carry their own rounding
         assert v["grad_L_rel_l2_vs_fused"] < 1e-3, name
         assert v["ms_per_step"] > 0 and v["peak_bytes"] > 0
+
+
+@pytest.mark.gpu
+def test_framework_baselines_match_the_oracle_at_table_size():
+    """The two baselines at a size of the paper's Table 1 (|N| = |P| = 512, l = 20) against the oracle: they are fp32
+    framework code (log-space, automatic differentiation), so log Z is held to the fp32 bar and the gradients to the
+    gradient bar."""
+    from parity_util import check_all
+    d = synth.make_inputs("tiny", seed=synth.BASE_SEED + 300 + 512 + 20, pad_value=0.0, N=512, P=512, B=2, lengths=[20, 20],
+                          V=2000)
+    print("case ablation baselines vs oracle, N=512 l=20", flush=True)
+    ref = O.inside_backward(d["log_root"], d["L"], d["R"], d["log_emit"], d["lengths"])
+    for variant in ("logeinsumexp", "logsumexp"):
+        got = ablation.run_torch(d, variant, 1)
+        print(" ", variant, check_all(got, ref), flush=True)

@@ -407,6 +407,32 @@ def test_long_single_sentence_many_widths():
     print(check_all(got, oracle_run(d)))
 
 
+def test_workspace_content_before_the_call_does_not_matter():
+    """The workspace is scratch: nothing the path reads may depend on what the buffer held before the call.  In
+    particular the projection launches of a shared grammar write eta only for rows that are ever a left child and
+    zeta only for rows that are ever a right child (the other halves of [eta | zeta] stay unwritten and are never
+    read).  Every byte is set to 0xFF first: as floats that is NaN, as integers -1."""
+    for kw in (dict(N=128, P=40, B=77, lengths=[2, 3, 3, 4, 2, 5, 3] * 11), dict(N=130, P=70, B=6, lengths=[12, 5, 9, 3, 20, 7])):
+        d = synth.make_inputs("tiny", seed=1234, pad_value=np.nan, V=60, **kw)
+        print("case poisoned workspace", kw["N"], flush=True)
+        ref = oracle_run(d)
+        for precision in (bd.PRECISION_FP32, bd.PRECISION_BF16):
+            wl = bd.Workload(d, precision=precision)
+            wl.workspace.fill_(0xFF)
+            wl.forward_backward()
+            got = wl.results()
+            if precision == bd.PRECISION_FP32:
+                check_all(got, ref)
+            else:
+                assert all(np.all(np.isfinite(got[k])) for k in got)
+                assert np.max(np.abs(got["logZ"] - ref["logZ"])) < 5e-2
+            wl.workspace.zero_()
+            wl.forward_backward()
+            again = wl.results()
+            for k in got:
+                assert np.array_equal(got[k], again[k]), f"{k} depends on the workspace's previous content"
+
+
 def test_workspace_reuse_across_different_batches():
     """The same workspace buffer serves batches of different shapes one after the other."""
     import torch
