@@ -21,9 +21,11 @@ using namespace nt;
 constexpr int BK = 32;
 // Split-product path: the tile lies in LDS already cut into its three bf16 planes (each thread cuts the 32
 // values it stages, so every value is cut once per workgroup and not once per wavefront that multiplies it).
-// One K-step of a row is 32 bf16 = 64 bytes per plane; rows are 80 bytes apart (16-byte aligned, and 16-byte
-// reads of 8 consecutive rows touch every bank once).  One stage: three planes of BM + 128 rows.
-constexpr int PRS = 20;  // plane row stride in 4-byte words
+// One K-step of a row is 32 bf16 = 64 bytes per plane, rows lie back to back, and the 16-byte chunk index of a row
+// is XORed with bits 2..3 of the row number: the 16-byte operand reads of 16 consecutive rows and the 8-byte stores of
+// a wavefront (8 rows of 64 bytes) then touch every bank equally.  One stage: three planes of BM + 128 rows.
+constexpr int PRS = 16;  // plane row stride in 4-byte words
+__device__ __forceinline__ int plane_swz(int row) { return (row >> 2) & 3; }
 template <int BM> constexpr int kPlaneWords = (BM + BN) * PRS;
 template <int BM, bool X3> constexpr size_t kLdsBytesNT = X3 ? (size_t)3 * kPlaneWords<BM> * 4 : Geo<BM>::kLdsBytes;
 
@@ -157,9 +159,12 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
     // of a CU interleave.
     uint32_t* ldsu = reinterpret_cast<uint32_t*>(lds);
     constexpr int PL = kPlaneWords<BM>;
-    const int st_off = lr * PRS + lc4 * 2;                         // this thread's 4 values of row lr (+ 32 q)
-    const int fa_off = (wm * G::MI * 32 + frag_row) * PRS + (lane >> 5) * 4;   // 8 values of chunk c: + 8 c words
-    const int fb_off = (BM + wn * G::NI * 32 + frag_row) * PRS + (lane >> 5) * 4;
+    // this thread's 4 values (half a 16-byte chunk) of row lr (+ 32 q: the same swizzle)
+    const int st_off = lr * PRS + (((lc4 >> 1) ^ plane_swz(lr)) * 4) + (lc4 & 1) * 2;
+    // 8 values of chunk 0; chunk 1 is the offset with bit 3 flipped (the next two 16-byte pieces of the row)
+    const int fsw = (((lane >> 5) ^ plane_swz(frag_row)) * 4);
+    const int fa_off = (wm * G::MI * 32 + frag_row) * PRS + fsw;
+    const int fb_off = (BM + wn * G::NI * 32 + frag_row) * PRS + fsw;
 #define SPCFG_CUT_STORE1(V, ROWOFF)                                                            \
   {                                                                                            \
     unsigned h0_, m0_, l0_, h1_, m1_, l1_;                                                     \
@@ -176,7 +181,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
   if (G::QA > 2) SPCFG_CUT_STORE1(ra3, 96)                          \
   SPCFG_CUT_STORE1(rb0, BM) SPCFG_CUT_STORE1(rb1, BM + 32) SPCFG_CUT_STORE1(rb2, BM + 64) SPCFG_CUT_STORE1(rb3, BM + 96)
 #define SPCFG_OPER(PLANE, OFF, C) \
-  __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(ldsu + (PLANE)*PL + (OFF) + 8 * (C)))
+  __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(ldsu + (PLANE)*PL + ((OFF) ^ (8 * (C)))))
 #define SPCFG_MFMA_T(X, Y)                                                                                    \
   acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0##X, b0##Y, acc[0][0], 0, 0, 0);                        \
   if (G::NI > 1) acc[0][G::NI - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0##X, b1##Y, acc[0][G::NI - 1], 0, 0, 0); \
