@@ -91,6 +91,12 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
     }
     const int k1 = min(KTt, k0 + (wg_end - it));
     const int col0 = tile_n * BN;
+    // Position p of the tile's K loop is K-step (p + krot) mod KTt: the workgroup that owns the tile's first position is
+    // then at K-step (its own step count) mod KTt, so workgroups running side by side on an XCD read the same K range
+    // of the operand rows they share at the same time and that XCD's L2 fetches them once.  Shares and partial tiles are
+    // made of positions; the order of the sum stays fixed by the launch geometry.
+    const int krot = (ustart % ipw) % KTt;
+    auto kstep_of = [&](int p) { const int q = p + krot; return q >= KTt ? q - KTt : q; };
     // parts: the part's column block of Bm (rows of the K-contiguous panel) and its K range
     const float* bmat = static_cast<const float*>(g.Bm) + (int64_t)c_shift * g.ldb + (int64_t)kbeg * BK;
     const float* amat = static_cast<const float*>(g.A) + (int64_t)kbeg * BK;
@@ -131,7 +137,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
   *reinterpret_cast<float4*>((DST) + BM * LDT + 32 * LDT) = rb1;                  \
   *reinterpret_cast<float4*>((DST) + BM * LDT + 64 * LDT) = rb2;                  \
   *reinterpret_cast<float4*>((DST) + BM * LDT + 96 * LDT) = rb3;
-    SPCFG_LOAD_TILE(k0 * BK)
+    SPCFG_LOAD_TILE(kstep_of(k0) * BK)
     if constexpr (!X3) {
       SPCFG_STORE_TILE(lds + lds_st)
       __syncthreads();
@@ -207,7 +213,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
     __syncthreads();
     for (int kt = k0; kt < k1; ++kt) {
       const bool more = kt + 1 < k1;  // uniform over the workgroup
-      if (more) { SPCFG_LOAD_TILE((kt + 1) * BK) }
+      if (more) { SPCFG_LOAD_TILE(kstep_of(kt + 1) * BK) }
       __builtin_amdgcn_sched_barrier(0);  // keep the prefetch loads at the top of the step
       SPCFG_CHUNK(0)
       SPCFG_CHUNK(1)
@@ -231,7 +237,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm_nt(NtArgs g, int ipw, int total
     for (int kt = k0; kt < k1; ++kt) {
       const int buf = (kt - k0) & 1;
       // prefetch the next K-step into registers (the last iteration re-reads its own step)
-      const int kn = min(kt + 1, k1 - 1) * BK;
+      const int kn = kstep_of(min(kt + 1, k1 - 1)) * BK;
       SPCFG_LOAD_TILE(kn)
       // Pinned schedule (left alone, the compiler sinks the prefetch loads down to their LDS stores and exposes
       // the memory latency in every K-step): loads, chunks 0-2, LDS stores of the prefetched tile (the loads

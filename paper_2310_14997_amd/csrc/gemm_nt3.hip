@@ -79,7 +79,7 @@ __device__ __forceinline__ void tie_registers(uintx4 (&F)[3][NF]) {
 
 // MODE 0: one product; 2: parts (see NtArgs).
 template <int EPI, int BM, int MODE>
-__global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int total_iters) {
+__global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int total_iters, int mgroups) {
   constexpr bool PARTS = MODE == 2;
   using G = Geo<BM>;
   using Q = Geo3<BM>;
@@ -146,11 +146,22 @@ __global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int tota
       tile = it / KT;
       k0 = it - tile * KT;
       ustart = tile * KT;
-      tile_m = tile % tiles_m; tile_n = tile / tiles_m;
+      // tile order: the row tiles in mgroups groups, one group after the other, inside a group row tile fastest: with
+      // consecutive shares on one XCD, that XCD's concurrently running tiles form a block of (row tiles of a group) x
+      // (a slice of the column tiles), whose operand rows its L2 fetches once
+      const int rpg = (tiles_m + mgroups - 1) / mgroups, per = rpg * ((g.cols + BN - 1) / BN);
+      const int gi = tile / per, rem = tile - gi * per, gm = min(rpg, tiles_m - gi * rpg);
+      tile_m = gi * rpg + rem % gm; tile_n = rem / gm;
       row0 = tile_m * BM;
     }
     const int k1 = min(KTt, k0 + (wg_end - it));
     const int col0 = tile_n * BN;
+    // The tile's K-steps are taken in rotated order: position p of the tile's K loop is K-step (p + krot) mod KTt, with
+    // krot chosen so that the workgroup that owns the tile's first position is at K-step (its own step count) mod KTt.
+    // Workgroups that run side by side on an XCD then read the same K range of the operand rows they share at the same
+    // time, whatever the share size is, and that XCD's L2 fetches those rows once.  (Positions, not K-steps, are what
+    // the shares and the partial tiles are made of; the order of the sum is still fixed by the launch geometry.)
+    const int krot = (ustart % ipw) % KTt;
     const uint16_t* amat = static_cast<const uint16_t*>(g.A3) + (int64_t)kbeg * BK3;
     const uint16_t* bmat = static_cast<const uint16_t*>(g.Bm3) + (int64_t)c_shift * g.ldb + (int64_t)kbeg * BK3;
     // global address of this lane's 16 bytes of every load instruction at K-step 0: row rg * 16 + lane / 4 of the
@@ -176,8 +187,9 @@ __global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int tota
 
     // operand registers of two chunks: [plane][fragment], fragments 0..MI-1 of A, MI..MI+NI-1 of Bm
     uintx4 X[3][NF], Y[3][NF];
-    auto load_stage = [&](int stage, int kstep) {  // all of this wavefront's loads of one K-step
-      const int64_t koff = (int64_t)kstep * 64;
+    auto load_stage = [&](int stage, int kpos) {  // all of this wavefront's loads of one K-step
+      const int kr = kpos + krot;
+      const int64_t koff = (int64_t)(kr >= KTt ? kr - KTt : kr) * 64;
       static_for<0, ND>([&](auto j) { dma16(gp[j] + koff, lds0 + stage * Q::STAGE + e_lds[j]); });
     };
     auto read_one = [&](uintx4(&F)[3][NF], auto r, unsigned aa, unsigned ba) {
@@ -213,8 +225,8 @@ __global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int tota
     for (int kt = k0; kt < k1; ++kt) {
       const int nxt = cur + 1 == NS ? 0 : cur + 1;
       const int fill = cur == 0 ? NS - 1 : cur - 1;   // the stage of step kt - 1: free since that step's barrier
-      const int kfill = min(kt + NS - 1, k1 - 1);
-      const int64_t koff = (int64_t)kfill * 64;
+      const int kfill = min(kt + NS - 1, k1 - 1) + krot;
+      const int64_t koff = (int64_t)(kfill >= KTt ? kfill - KTt : kfill) * 64;
       const unsigned fill_lds = lds0 + fill * Q::STAGE;
       const unsigned aa1 = a_frag1 + cur * Q::STAGE, ba1 = b_frag1 + cur * Q::STAGE;
       const unsigned aa0 = a_frag + nxt * Q::STAGE, ba0 = b_frag + nxt * Q::STAGE;
@@ -295,7 +307,20 @@ void launch3(const NtArgs& a, hipStream_t st) {
   if (Gn > total / 2) Gn = total / 2 > 0 ? total / 2 : 1;  // at least two K-steps per share
   int ipw = (total + Gn - 1) / Gn;
   Gn = (total + ipw - 1) / ipw;
-  launch_k(k_gemm_nt3<EPI, BM, MODE>, dim3(Gn), dim3(256), Q::kLds, st, a, ipw, total);
+  // Every XCD has an L2 of its own and runs consecutive shares, so what the launch fetches past L2 is, per XCD, the
+  // operand rows of the block of tiles it runs at a time: (a + b) row panels for a block of a row tiles x b column tiles.
+  // Row-tile groups (1, 2 or 4) make that block as square as the tile counts allow.
+  int mgroups = 1;
+  if (a.parts == 0) {
+    const int tiles_m = (a.rows + BM - 1) / BM, passes = tiles / 256 > 0 ? tiles / 256 : 1;
+    int best = 1 << 30;
+    for (int mg = 1; mg <= 4; mg *= 2) {
+      if (mg > 1 && tiles_m < 2 * mg) break;
+      const int am = tiles_m / (mg * passes) > 0 ? tiles_m / (mg * passes) : 1, bn = tiles_n * mg / 8 > 0 ? tiles_n * mg / 8 : 1;
+      if (am + bn < best) { best = am + bn; mgroups = mg; }
+    }
+  }
+  launch_k(k_gemm_nt3<EPI, BM, MODE>, dim3(Gn), dim3(256), Q::kLds, st, a, ipw, total, mgroups);
 }
 
 template <int EPI>
