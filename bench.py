@@ -128,17 +128,18 @@ def time_decode(wl, steps):
     return res
 
 
-def measure(d, bf16, fp32_mfma, steps, warmup, profile_steps, graph=False):
+def measure(d, bf16, fp32_mfma, steps, warmup, profile_steps, graph=False, extra_flags=0):
     """Times `steps` forward+backward steps on the batch `d` (inputs resident in HBM), then repeats `profile_steps`
     steps with HIP events bound to every kernel's own dispatch for the per-class times."""
     import torch
     from paper_2310_14997_amd import binding as bd
     from paper_2310_14997_amd import synth
     wl = bd.Workload(d, precision=bd.PRECISION_BF16 if bf16 else bd.PRECISION_FP32,
-                     flags=bd.FLAG_FP32_MFMA if fp32_mfma else 0)
+                     flags=(bd.FLAG_FP32_MFMA if fp32_mfma else 0) | extra_flags)
     peak = PEAK_BF16_MFMA_TFLOPS if bf16 else (PEAK_FP32_MFMA_TFLOPS if fp32_mfma else PEAK_SPLIT_TFLOPS)
     if bf16:
-        kernel_name, mfma = "k_gemm_nt16 (bf16 operands, bf16 MFMA", "bf16"
+        kernel_name, mfma = ("k_gemm_nt3 (forward: operands as two bf16 pieces, 3 bf16 MFMA products, not counted in "
+                             "the flop) / k_gemm_nt16 (reverse: single bf16 operands", "bf16")
     elif fp32_mfma:
         kernel_name, mfma = "k_gemm_nt (fp32 MFMA", "f32"
     else:
@@ -314,7 +315,17 @@ def main():
                                       "projection_tflops": mn["roofline"]["achieved"],
                                       "hbm_frac": mn["split_reduction"]["frac"],
                                       "split_GBps": mn["split_reduction"]["achieved"]}
-            del mn, dn
+            del mn
+            if name == "scaled":  # the same with single bf16 operands in the forward products as well
+                import paper_2310_14997_amd.binding as bd_
+                m1 = measure(dn, True, False, 5, 2, 5, extra_flags=bd_.FLAG_BF16_SINGLE_FORWARD)
+                out["workloads"]["scaled_single_bf16_forward"] = {
+                    "dtype": "bf16", "ms_per_step": m1["ms_per_step"], "sentences_per_s": m1["sentences_per_s"],
+                    "mfma_frac": m1["roofline"]["frac"], "mfma_peak": m1["roofline"]["peak"],
+                    "projection_tflops": m1["roofline"]["achieved"], "hbm_frac": m1["split_reduction"]["frac"],
+                    "split_GBps": m1["split_reduction"]["achieved"]}
+                del m1
+            del dn
     if args.frontend:
         out["frontend"] = time_frontend(args.workload, wl, args.steps)
     if args.decode:

@@ -60,7 +60,16 @@ enum {
      the accuracy of an fp32 product (the dropped terms are below 2^-23 of it) at a fraction of the cost of
      fp32 matrix instructions.  This flag selects fp32 matrix instructions instead.  It has no effect on products
      whose operands are bf16 (SPCFG_PRECISION_BF16). */
-  SPCFG_FLAG_FP32_MFMA = 4u
+  SPCFG_FLAG_FP32_MFMA = 4u,
+  /* SPCFG_PRECISION_BF16 with a shared grammar forms its forward projection products -- the ones log Z depends on --
+     from operands cut into two bf16 pieces (hi + lo, three piece products, operands good to 2^-17), so that log Z
+     stays within about 1e-3 of exact arithmetic whatever the grammar and the sentence length.  This flag rounds those
+     operands to a single bf16 instead, as the reverse and rule-gradient products always do: a third of the matrix
+     work in the forward products (the Scaled configuration runs 15 % faster), but roundings of 2^-9 per projection
+     then add up along a tree: measured up to 0.07 absolute in log Z on small peaked grammars with sentences of
+     60-100 words, 0.6e-3 to 1.5e-3 on large unpeaked ones at n = 40.  No effect with SPCFG_PRECISION_FP32 or with
+     one grammar per sentence (single bf16 operands there). */
+  SPCFG_FLAG_BF16_SINGLE_FORWARD = 8u
 };
 
 /* Plain-old-data configuration; set struct_size = sizeof(spcfg_config). */
@@ -72,8 +81,11 @@ typedef struct {
   int32_t max_n;     /* capacity: largest sentence length the workspace is sized for              */
   int32_t precision; /* SPCFG_PRECISION_FP32: fp32 operands on the matrix cores, fp32 accumulate;
                         SPCFG_PRECISION_BF16: the operands of the projection and rule-gradient
-                        products are rounded to bf16, fp32 accumulate; everything else stays fp32.
-                        log Z then agrees with exact arithmetic to about 1e-3 absolute at n = 40 */
+                        products are bf16 (two bf16 pieces per value in the forward projections of a
+                        shared grammar, see SPCFG_FLAG_BF16_SINGLE_FORWARD), fp32 accumulate; everything
+                        else stays fp32.  Gradients carry the single-bf16 roundings of the reverse
+                        products: relative L2 error 1e-4 .. 1e-2 per tensor on large unpeaked grammars,
+                        up to a few 1e-2 on small peaked ones */
   uint32_t flags;    /* SPCFG_FLAG_*                                                              */
 } spcfg_config;
 

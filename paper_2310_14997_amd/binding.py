@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libspcfg.so")
 
 PRECISION_FP32, PRECISION_BF16 = 0, 1
-FLAG_ACCUMULATE_GRADS, FLAG_PER_SENTENCE_GRAMMAR, FLAG_FP32_MFMA = 1, 2, 4
+FLAG_ACCUMULATE_GRADS, FLAG_PER_SENTENCE_GRAMMAR, FLAG_FP32_MFMA, FLAG_BF16_SINGLE_FORWARD = 1, 2, 4, 8
 PROF_CLASSES = 7
 
 

@@ -341,7 +341,8 @@ bool gemm_nt_keep_parts(NtArgs& a) {
 }
 
 bool gemm_nt_reads_planes(const NtArgs& a) {
-  return a.planes3 && !a.b_bf16 && a.rows > 0 && a.cols > 0 && nt::chosen_bm(a) == 128;
+  if (!a.planes3 || a.b_bf16 || a.rows <= 0 || a.cols <= 0 || a.grouped) return false;
+  return a.planes3 == 2 || nt::chosen_bm(a) == 128;
 }
 
 void launch_gemm_nt(const NtArgs& a, hipStream_t st) {

@@ -1,6 +1,9 @@
-// Projection GEMM on operands that arrive already cut into three bf16 planes (Sec. 3.2: [eta | zeta] = [L;R] * beta
-// for all spans of one width at once, and the reverse product):  C[r][c] = sum_k A[r][k] * Bm[c][k] with
-// A = Ah + Am + Al, Bm = Bh + Bm + Bl exactly (nt::Split3) and the six significant piece products accumulated in fp32.
+// Projection GEMM on operands that arrive already cut into bf16 planes (Sec. 3.2: [eta | zeta] = [L;R] * beta
+// for all spans of one width at once, and the reverse product):  C[r][c] = sum_k A[r][k] * Bm[c][k].
+// Three planes (fp32 mode): A = Ah + Am + Al, Bm = Bh + Bm + Bl exactly (nt::Split3) and the six significant piece
+// products accumulated in fp32.  Two planes (forward products of the bf16 mode): hi = bf16(x), lo = bf16(x - hi), products
+// lo*hi, hi*lo, hi*hi: operands good to 2^-17 instead of 2^-9, which keeps log Z inside its bound on peaked grammars
+// and long sentences, where single bf16 roundings add up over the hundreds of projections of a tree.
 // The producers of the chart rows and the weight packing write the planes, so this kernel does no conversion work:
 //
 //  * tiles go straight from global memory into LDS (global_load_lds_dwordx4, 1 KB per wavefront instruction = 16 rows of
@@ -26,16 +29,17 @@ using namespace nt;
 
 constexpr int BK3 = 32;  // K values per step: one 64-byte row per plane
 
-template <int BM> struct Geo3 {
+template <int BM, int NPL> struct Geo3 {
   using G = Geo<BM>;
   static constexpr int PTA = BM * 64, PTB = BN * 64;        // bytes of one plane tile of A / of Bm
-  static constexpr int STAGE = 3 * (PTA + PTB);              // [A hi | A mid | A lo | B hi | B mid | B lo]
-  static constexpr int NS = BM == 128 ? 3 : (BM == 64 ? 4 : 5);
-  static constexpr int NDT = 3 * (BM / 16) + 3 * (BN / 16);  // 1 KB load instructions per stage
+  static constexpr int STAGE = NPL * (PTA + PTB);            // [A hi | A mid | A lo | B hi | B mid | B lo]
+  static constexpr int NS = (BM == 128 ? 3 : (BM == 64 ? 4 : 5)) + (NPL == 2 ? 1 : 0);
+  static constexpr int NDT = NPL * (BM / 16) + NPL * (BN / 16);  // 1 KB load instructions per stage
   static constexpr int ND = (NDT + 3) / 4;                   // per wavefront (the last ones repeat when uneven)
   static constexpr int NF = G::MI + G::NI;                   // operand fragments per plane and 16-wide chunk
-  static constexpr int NR = 3 * NF;                          // operand reads per chunk
-  static constexpr int NM = 6 * G::MI * G::NI;               // matrix instructions per chunk
+  static constexpr int NR = NPL * NF;                        // operand reads per chunk
+  static constexpr int NM = (NPL == 3 ? 6 : 3) * G::MI * G::NI;  // matrix instructions per chunk
+  static constexpr int RPF = (NR + NM - 1) / NM;             // operand reads behind each of them in the first half
   static constexpr int NB = NM >= 12 ? 2 : 1;                // matrix instructions ahead of the barrier
   static constexpr size_t kLds = (size_t)NS * STAGE;
 };
@@ -66,23 +70,23 @@ __device__ __forceinline__ unsigned lds_address(const void* p) {
 }
 __device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 
-// Makes every register of F[3][NF] an in/out operand of an empty statement: instructions that use them stay behind it.
-template <int NF, int R = 0>
-__device__ __forceinline__ void tie_registers(uintx4 (&F)[3][NF]) {
-  if constexpr (R < 3 * NF) {
+// Makes every register of F[NPL][NF] an in/out operand of an empty statement: instructions that use them stay behind it.
+template <int NPL, int NF, int R = 0>
+__device__ __forceinline__ void tie_registers(uintx4 (&F)[NPL][NF]) {
+  if constexpr (R < NPL * NF) {
     asm volatile("" : "+v"(F[R / NF][R % NF]));
-    tie_registers<NF, R + 1>(F);
+    tie_registers<NPL, NF, R + 1>(F);
   }
 }
 
 #define SPCFG_SB __builtin_amdgcn_sched_barrier(0);
 
 // MODE 0: one product; 2: parts (see NtArgs).
-template <int EPI, int BM, int MODE>
+template <int EPI, int BM, int MODE, int NPL>
 __global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int total_iters, int mgroups) {
   constexpr bool PARTS = MODE == 2;
   using G = Geo<BM>;
-  using Q = Geo3<BM>;
+  using Q = Geo3<BM, NPL>;
   constexpr int MI = G::MI, NI = G::NI, NS = Q::NS, ND = Q::ND, NF = Q::NF, NR = Q::NR, NM = Q::NM, NB = Q::NB;
   extern __shared__ __align__(16) unsigned char lds3[];
   __shared__ int s_last;
@@ -98,7 +102,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int tota
   const unsigned frag_sw = (unsigned)((fh ^ swz(fr)) * 16);
   // byte offsets inside a stage of chunk 0; chunk 1 flips bit 5 of the offset (the next two 16-byte pieces of the row)
   const unsigned a_rel = (wm * MI * 32 + fr) * 64 + frag_sw;
-  const unsigned b_rel = 3 * Q::PTA + (wn * NI * 32 + fr) * 64 + frag_sw;
+  const unsigned b_rel = NPL * Q::PTA + (wn * NI * 32 + fr) * 64 + frag_sw;
   const unsigned a_frag = lds0 + a_rel, b_frag = lds0 + b_rel;
   const unsigned a_frag1 = lds0 + (a_rel ^ 32u), b_frag1 = lds0 + (b_rel ^ 32u);
   // this wavefront's load instructions: entry e = uw + 4 j of the stage's list (A planes first, then Bm planes)
@@ -107,11 +111,11 @@ __global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int tota
 #pragma unroll
   for (int j = 0; j < ND; ++j) {
     const int e = min(uw + 4 * j, Q::NDT - 1);
-    const bool isA = e < 3 * (BM / 16);
-    const int ee = isA ? e : e - 3 * (BM / 16);
+    const bool isA = e < NPL * (BM / 16);
+    const int ee = isA ? e : e - NPL * (BM / 16);
     const int per = isA ? BM / 16 : BN / 16;
     e_isA[j] = isA; e_plane[j] = ee / per; e_rg[j] = ee % per;
-    e_lds[j] = (isA ? e_plane[j] * Q::PTA : 3 * Q::PTA + e_plane[j] * Q::PTB) + e_rg[j] * 1024;
+    e_lds[j] = (isA ? e_plane[j] * Q::PTA : NPL * Q::PTA + e_plane[j] * Q::PTB) + e_rg[j] * 1024;
   }
 
   const int wg = renumbered_wg();
@@ -186,13 +190,13 @@ __global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int tota
         for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
     // operand registers of two chunks: [plane][fragment], fragments 0..MI-1 of A, MI..MI+NI-1 of Bm
-    uintx4 X[3][NF], Y[3][NF];
+    uintx4 X[NPL][NF], Y[NPL][NF];
     auto load_stage = [&](int stage, int kpos) {  // all of this wavefront's loads of one K-step
       const int kr = kpos + krot;
       const int64_t koff = (int64_t)(kr >= KTt ? kr - KTt : kr) * 64;
       static_for<0, ND>([&](auto j) { dma16(gp[j] + koff, lds0 + stage * Q::STAGE + e_lds[j]); });
     };
-    auto read_one = [&](uintx4(&F)[3][NF], auto r, unsigned aa, unsigned ba) {
+    auto read_one = [&](uintx4(&F)[NPL][NF], auto r, unsigned aa, unsigned ba) {
       constexpr int pl = decltype(r)::value / NF, f = decltype(r)::value % NF;
       if constexpr (f < MI) {
         asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(F[pl][f]) : "v"(aa), "n"(pl * Q::PTA + f * 2048));
@@ -200,18 +204,19 @@ __global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int tota
         asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(F[pl][f]) : "v"(ba), "n"(pl * Q::PTB + (f - MI) * 2048));
       }
     };
-    auto mfma_one = [&](uintx4(&F)[3][NF], auto i) {
-      // piece products, small terms first: lo*hi, hi*lo, mid*mid, mid*hi, hi*mid, hi*hi (planes: 0 hi, 1 mid, 2 lo)
+    auto mfma_one = [&](uintx4(&F)[NPL][NF], auto i) {
+      // piece products, small terms first.  Three planes (0 hi, 1 mid, 2 lo): lo*hi, hi*lo, mid*mid, mid*hi, hi*mid,
+      // hi*hi; two planes (0 hi, 1 lo): lo*hi, hi*lo, hi*hi
       constexpr int pp = decltype(i)::value / (MI * NI), rem = decltype(i)::value % (MI * NI);
       constexpr int mi = rem / NI, ni = rem % NI;
-      constexpr int pa = pp == 0 ? 2 : (pp == 2 || pp == 3 ? 1 : 0);
-      constexpr int pb = pp == 1 ? 2 : (pp == 2 || pp == 4 ? 1 : 0);
+      constexpr int pa = NPL == 3 ? (pp == 0 ? 2 : (pp == 2 || pp == 3 ? 1 : 0)) : (pp == 0 ? 1 : 0);
+      constexpr int pb = NPL == 3 ? (pp == 1 ? 2 : (pp == 2 || pp == 4 ? 1 : 0)) : (pp == 1 ? 1 : 0);
       acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, F[pa][mi]),
                                                            __builtin_bit_cast(bf16x8, F[pb][MI + ni]), acc[mi][ni], 0, 0, 0);
     };
-    auto wait_reads = [&](uintx4(&F)[3][NF]) {  // every operand read has landed; ties the registers to the wait
+    auto wait_reads = [&](uintx4(&F)[NPL][NF]) {  // every operand read has landed; ties the registers to the wait
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      tie_registers<NF>(F);
+      tie_registers<NPL, NF>(F);
     };
 
     // prologue: the first NS - 1 steps in flight (steps past the end repeat the last one: the count of loads in flight
@@ -238,7 +243,10 @@ __global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int tota
         constexpr int iv = decltype(i)::value;
         mfma_one(X, i);
         SPCFG_SB
-        if constexpr (iv < NR) read_one(Y, std::integral_constant<int, iv>{}, aa1, ba1);
+        static_for<0, Q::RPF>([&](auto q) {
+          constexpr int r = iv * Q::RPF + decltype(q)::value;
+          if constexpr (r < NR) read_one(Y, std::integral_constant<int, r>{}, aa1, ba1);
+        });
         static_for<0, ND>([&](auto j) {
           if constexpr ((decltype(j)::value * NM) / ND == iv) dma16(gp[decltype(j)::value] + koff, fill_lds + e_lds[decltype(j)::value]);
         });
@@ -277,12 +285,12 @@ __global__ void __launch_bounds__(256, 1) k_gemm_nt3(NtArgs g, int ipw, int tota
   }
 }
 
-template <int EPI, int BM, int MODE>
+template <int EPI, int BM, int MODE, int NPL>
 void launch3(const NtArgs& a, hipStream_t st) {
-  using Q = Geo3<BM>;
+  using Q = Geo3<BM, NPL>;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt3<EPI, BM, MODE>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt3<EPI, BM, MODE, NPL>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)Q::kLds);
     attr_set = true;
   }
@@ -320,35 +328,47 @@ void launch3(const NtArgs& a, hipStream_t st) {
       if (am + bn < best) { best = am + bn; mgroups = mg; }
     }
   }
-  launch_k(k_gemm_nt3<EPI, BM, MODE>, dim3(Gn), dim3(256), Q::kLds, st, a, ipw, total, mgroups);
+  launch_k(k_gemm_nt3<EPI, BM, MODE, NPL>, dim3(Gn), dim3(256), Q::kLds, st, a, ipw, total, mgroups);
 }
 
-template <int EPI>
+template <int EPI, int NPL>
 void launch_bm3(const NtArgs& a, hipStream_t st) {
   const int bm = chosen_bm(a);
   if (a.parts > 0) {
     switch (bm) {
-      case 32: launch3<EPI, 32, 2>(a, st); break;
-      case 64: launch3<EPI, 64, 2>(a, st); break;
-      default: launch3<EPI, 128, 2>(a, st); break;
+      case 32: launch3<EPI, 32, 2, NPL>(a, st); break;
+      case 64: launch3<EPI, 64, 2, NPL>(a, st); break;
+      default: launch3<EPI, 128, 2, NPL>(a, st); break;
     }
     return;
   }
   switch (bm) {
-    case 32: launch3<EPI, 32, 0>(a, st); break;
-    case 64: launch3<EPI, 64, 0>(a, st); break;
-    default: launch3<EPI, 128, 0>(a, st); break;
+    case 32: launch3<EPI, 32, 0, NPL>(a, st); break;
+    case 64: launch3<EPI, 64, 0, NPL>(a, st); break;
+    default: launch3<EPI, 128, 0, NPL>(a, st); break;
   }
+}
+
+template <int EPI>
+void launch_tall3(const NtArgs& a, hipStream_t st) {
+  if (a.parts > 0) launch3<EPI, 128, 2, 3>(a, st); else launch3<EPI, 128, 0, 3>(a, st);
 }
 
 }  // namespace
 
+// planes3 == 3: the launches with 128-row tiles of the fp32 mode (gemm_nt_reads_planes); planes3 == 2: every forward
+// product of the bf16 mode.
 void launch_gemm_nt3(const NtArgs& a, hipStream_t st) {
   if (a.rows <= 0 || a.cols <= 0 || !a.planes3 || a.grouped) return;
+  if (a.planes3 == 2) {
+    if (a.epilogue != NT_EPI_ROWSCALE) { launch_refused("two-plane projection product: forward epilogue only"); return; }
+    launch_bm3<NT_EPI_ROWSCALE, 2>(a, st);
+    return;
+  }
   switch (a.epilogue) {
-    case NT_EPI_ROWSCALE: launch_bm3<NT_EPI_ROWSCALE>(a, st); break;
-    case NT_EPI_MASKROWS: launch_bm3<NT_EPI_MASKROWS>(a, st); break;
-    default: launch_bm3<NT_EPI_LEAF_EMIT>(a, st); break;
+    case NT_EPI_ROWSCALE: launch_tall3<NT_EPI_ROWSCALE>(a, st); break;
+    case NT_EPI_MASKROWS: launch_tall3<NT_EPI_MASKROWS>(a, st); break;
+    default: launch_tall3<NT_EPI_LEAF_EMIT>(a, st); break;
   }
 }
 

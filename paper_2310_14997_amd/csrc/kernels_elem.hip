@@ -66,17 +66,17 @@ __device__ __forceinline__ void store_bf16x4(void* base, int64_t idx, float4 v) 
 }
 
 // Operand planes of four consecutive values for the projection products: with three planes the exact cut
-// x = hi + mid + lo into bf16 pieces (nt::Split3), with one plane the bf16 rounding.  Plane p starts at
-// base + p * plane_stride elements.
+// x = hi + mid + lo into bf16 pieces (nt::Split3), with two planes hi = bf16(x) and lo = bf16(x - hi) (the first two
+// pieces of the same cut), with one plane the bf16 rounding.  Plane p starts at base + p * plane_stride elements.
 __device__ __forceinline__ void store_planes4(void* base, int planes, int64_t plane_stride, int64_t idx, float4 v) {
-  if (planes == 3) {
+  if (planes >= 2) {
     unsigned h0, m0, l0, h1, m1, l1;
     nt::Split3::cut2(v.x, v.y, h0, m0, l0);
     nt::Split3::cut2(v.z, v.w, h1, m1, l1);
     uint16_t* b = static_cast<uint16_t*>(base) + idx;
     *reinterpret_cast<uint2*>(b) = uint2{h0, h1};
     *reinterpret_cast<uint2*>(b + plane_stride) = uint2{m0, m1};
-    *reinterpret_cast<uint2*>(b + 2 * plane_stride) = uint2{l0, l1};
+    if (planes == 3) *reinterpret_cast<uint2*>(b + 2 * plane_stride) = uint2{l0, l1};
   } else {
     store_bf16x4(base, idx, v);
   }
@@ -235,28 +235,33 @@ __global__ void k_plan_sentrows(int B, int stride, const int32_t* __restrict__ l
 // Stacks [L;R] (Sec. 3.2, kernel fusion: one matrix product for both projections) into zero-padded,
 // K-contiguous operands: Wn [2Np x Np] / Wp [2Np x Pp] for the forward products and their transposes
 // Wtn [Np x 2Np] / Wtp [Pp x 2Np] for the reverse products.
-// Element store of a packed panel: OutT float or __bf16 writes the value; uint16_t writes the three bf16 pieces of
-// the exact cut (nt::Split3) into three planes `stride` elements apart.
-template <typename OutT> __device__ __forceinline__ void put_w(OutT* w, int64_t, int64_t at, float v) { w[at] = (OutT)v; }
-__device__ __forceinline__ void put_w(uint16_t* w, int64_t stride, int64_t at, float v) {
+// Element store of a packed panel: OutT float or __bf16 writes the value; uint16_t writes the first NPL bf16 pieces
+// of the cut (nt::Split3) into planes `stride` elements apart.  A null panel is skipped.
+template <int NPL, typename OutT> __device__ __forceinline__ void put_w(OutT* w, int64_t, int64_t at, float v) {
+  if (w != nullptr) w[at] = (OutT)v;
+}
+template <int NPL> __device__ __forceinline__ void put_w(uint16_t* w, int64_t stride, int64_t at, float v) {
+  if (w == nullptr) return;
   unsigned h, m, l;
   nt::Split3::cut2(v, 0.0f, h, m, l);
-  w[at] = (uint16_t)h; w[stride + at] = (uint16_t)m; w[2 * stride + at] = (uint16_t)l;
+  w[at] = (uint16_t)h; w[stride + at] = (uint16_t)m;
+  if (NPL == 3) w[2 * stride + at] = (uint16_t)l;
 }
-// OutT = uint16_t: three bf16 planes per panel (plane strides 2Np*Np resp. 2Np*Pp elements; a grammar's panel set
-// is then three times as long)
-template <typename OutT>
+// OutT = uint16_t: NPL (2 or 3) bf16 planes per panel (plane strides 2Np*Np resp. 2Np*Pp elements; a grammar's
+// panel set is then NPL times as long)
+template <typename OutT, int NPL>
 __global__ void k_pack_weights(const float* __restrict__ L, const float* __restrict__ R, int N, int P, int Np,
                                int Pp, OutT* __restrict__ Wn, OutT* __restrict__ Wp, OutT* __restrict__ Wtn,
                                OutT* __restrict__ Wtp, uint32_t* __restrict__ colmax) {
-  constexpr int NPL = std::is_same<OutT, uint16_t>::value ? 3 : 1;
   const int64_t sn = 2 * (int64_t)Np * Np, sp = 2 * (int64_t)Np * Pp;
   __shared__ float tile[32][33];
   const int M = N + P;
   const int gi = blockIdx.z >> 1, lr = blockIdx.z & 1;  // grammar, left / right factor
   const float* src = (lr ? R : L) + (int64_t)gi * N * M;
-  Wn += (int64_t)gi * NPL * sn; Wtn += (int64_t)gi * NPL * sn;
-  Wp += (int64_t)gi * NPL * sp; Wtp += (int64_t)gi * NPL * sp;
+  if (Wn) Wn += (int64_t)gi * NPL * sn;
+  if (Wtn) Wtn += (int64_t)gi * NPL * sn;
+  if (Wp) Wp += (int64_t)gi * NPL * sp;
+  if (Wtp) Wtp += (int64_t)gi * NPL * sp;
   const int half = lr * Np;
   const int c0 = blockIdx.x * 32;  // padded column: [0,Np) nonterminal part, [Np, Np+Pp) preterminal part
   const int a0 = blockIdx.y * 32;
@@ -269,7 +274,7 @@ __global__ void k_pack_weights(const float* __restrict__ L, const float* __restr
     float v = 0.0f;
     if (a < N && c < (ppart ? P : N)) v = src[(int64_t)a * M + (ppart ? N + c : c)];
     tile[ty + 8 * q][tx] = v;
-    if (ppart) put_w(Wp, sp, (int64_t)(half + a) * Pp + c, v); else put_w(Wn, sn, (int64_t)(half + a) * Np + c, v);
+    if (ppart) put_w<NPL>(Wp, sp, (int64_t)(half + a) * Pp + c, v); else put_w<NPL>(Wn, sn, (int64_t)(half + a) * Np + c, v);
   }
   __syncthreads();
   if (colmax != nullptr && ty == 0) {
@@ -285,7 +290,7 @@ __global__ void k_pack_weights(const float* __restrict__ L, const float* __restr
   for (int q = 0; q < 4; ++q) {
     const int c = cc0 + ty + 8 * q, a = a0 + tx;
     const float v = tile[tx][ty + 8 * q];
-    if (ppart) put_w(Wtp, sp, (int64_t)c * (2 * Np) + half + a, v); else put_w(Wtn, sn, (int64_t)c * (2 * Np) + half + a, v);
+    if (ppart) put_w<NPL>(Wtp, sp, (int64_t)c * (2 * Np) + half + a, v); else put_w<NPL>(Wtn, sn, (int64_t)c * (2 * Np) + half + a, v);
   }
 }
 
@@ -343,7 +348,8 @@ __global__ void k_leaf_prep(const float* __restrict__ log_emit, int P, int Pp, i
     hs = max(hs, bexp_sum(cmL[t], v));
     zs = max(zs, bexp_sum(cmR[t], v));
     if (leafEb) {
-      if (planes == 3) put_w(leafEb, plane_stride, (int64_t)r * Pp + t, v);
+      if (planes == 3) put_w<3>(leafEb, plane_stride, (int64_t)r * Pp + t, v);
+      else if (planes == 2) put_w<2>(leafEb, plane_stride, (int64_t)r * Pp + t, v);
       else reinterpret_cast<__bf16*>(leafEb)[(int64_t)r * Pp + t] = (__bf16)v;
     }
   }
@@ -801,13 +807,19 @@ void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const 
   const int64_t ncm = 2 * (int64_t)(ly.Np + ly.Pp) * ly.G;
   launch_k(k_zero_u32, dim3((unsigned)((ncm + 255) / 256 < 1024 ? (ncm + 255) / 256 : 1024)), dim3(256), 0, st, cm, ncm);
   if (ly.planes == 3)  // the panels once more as three bf16 planes
-    launch_k(k_pack_weights<uint16_t>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
+    launch_k(k_pack_weights<uint16_t, 3>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
                        (uint16_t*)p.Wn3, (uint16_t*)p.Wp3, (uint16_t*)p.Wtn3, (uint16_t*)p.Wtp3, (uint32_t*)nullptr);
-  if (ly.bf16)
-    launch_k(k_pack_weights<__bf16>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
+  if (ly.planes == 2)  // the panels of the forward products as two bf16 planes
+    launch_k(k_pack_weights<uint16_t, 2>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
+                       (uint16_t*)p.Wn3, (uint16_t*)p.Wp3, (uint16_t*)nullptr, (uint16_t*)nullptr, (uint32_t*)nullptr);
+  if (ly.planes == 2)  // single bf16 panels of the reverse products only
+    launch_k(k_pack_weights<__bf16, 1>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
+                       (__bf16*)nullptr, (__bf16*)nullptr, (__bf16*)p.Wtn, (__bf16*)p.Wtp, cm);
+  else if (ly.bf16)
+    launch_k(k_pack_weights<__bf16, 1>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
                        (__bf16*)p.Wn, (__bf16*)p.Wp, (__bf16*)p.Wtn, (__bf16*)p.Wtp, cm);
   else
-    launch_k(k_pack_weights<float>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp, p.Wn, p.Wp,
+    launch_k(k_pack_weights<float, 1>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp, p.Wn, p.Wp,
                        p.Wtn, p.Wtp, cm);
 }
 
@@ -851,7 +863,7 @@ void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, con
                      float* grad_log_root, int accumulate, hipStream_t st) {
   launch_k(k_root_bwd, dim3(ly.B), dim3(256), 0, st, ly.N, ly.Np, ly.S1, p.rootrow, log_root, grad_logZ,
                      p.ztil, p.rmax, p.mexp, p.tmaxb, p.BH, p.UV, p.uexp, p.umaxb, p.gsc,
-                     (int64_t)(ly.G > 1 ? ly.N : 0), static_cast<uint16_t*>(p.UVb), ly.planes,
+                     (int64_t)(ly.G > 1 ? ly.N : 0), static_cast<uint16_t*>(p.UVb), ly.planes_bwd,
                      (int64_t)ly.Sall * 2 * ly.Np);
   launch_k(k_grad_log_root, dim3((ly.N + 255) / 256, ly.G > 1 ? ly.B : 1), dim3(256), 0, st, ly.B, ly.N,
                      ly.Np, ly.S1, p.rootrow, log_root, grad_logZ, p.ztil, p.rmax, p.T, p.tmaxb, grad_log_root,
@@ -863,7 +875,7 @@ void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int6
   const size_t sh = (size_t)ly.n_max * 16;
   const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
   launch_k(k_split_bwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b,
-                     p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc, write_planes ? p.UVb : nullptr, ly.planes,
+                     p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc, write_planes ? p.UVb : nullptr, ly.planes_bwd,
                      (int64_t)ly.Sall * 2 * ly.Np, p.hmaxb, p.zmaxb);
 }
 

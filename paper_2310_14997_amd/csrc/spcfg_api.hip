@@ -29,18 +29,23 @@ int check_cfg(const spcfg_config* c) {
   if (c->N < 1 || c->P < 1 || c->N > (1 << 16) || c->P > (1 << 16)) return SPCFG_ERR_SHAPE;
   if (c->max_B < 1 || c->max_B > kMaxB || c->max_n < 2 || c->max_n > kMaxLen) return SPCFG_ERR_SHAPE;
   if (c->precision != SPCFG_PRECISION_FP32 && c->precision != SPCFG_PRECISION_BF16) return SPCFG_ERR_UNSUPPORTED;
-  if (c->flags & ~(uint32_t)(SPCFG_FLAG_ACCUMULATE_GRADS | SPCFG_FLAG_PER_SENTENCE_GRAMMAR | SPCFG_FLAG_FP32_MFMA)) return SPCFG_ERR_UNSUPPORTED;
+  if (c->flags & ~(uint32_t)(SPCFG_FLAG_ACCUMULATE_GRADS | SPCFG_FLAG_PER_SENTENCE_GRAMMAR | SPCFG_FLAG_FP32_MFMA |
+                              SPCFG_FLAG_BF16_SINGLE_FORWARD)) return SPCFG_ERR_UNSUPPORTED;
   return SPCFG_OK;
 }
 
 // Byte layout of the workspace for a batch with S1 leaf rows and S2 rows of width >= 2.
 Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int bf16, int per_sentence, int fp32_mfma,
-                   int gemm_wgs = kGemmWgs) {
+                   int bf16_single, int gemm_wgs = kGemmWgs) {
   Layout ly{};
   ly.gemm_wgs = gemm_wgs;
-  // operand planes for the projection products: the bf16 rounding in bf16 mode; in fp32 mode with a shared grammar
-  // the exact three-piece cut (the products then never cut operands themselves)
-  ly.planes = bf16 ? 1 : ((per_sentence && B > 1) || fp32_mfma ? 0 : 3);
+  // Operand planes for the projection products.  fp32 mode with a shared grammar: the exact three-piece cut, forward
+  // and reverse (the products then never cut operands themselves).  bf16 mode with a shared grammar: two pieces
+  // (hi + lo) for the forward products, which decide log Z, the plain bf16 rounding for the reverse ones; with one
+  // grammar per sentence, or when the caller asks for single bf16 operands, one plane both ways.
+  const bool shared = !(per_sentence && B > 1);
+  ly.planes = bf16 ? (shared && !bf16_single ? 2 : 1) : (!shared || fp32_mfma ? 0 : 3);
+  ly.planes_bwd = bf16 ? 1 : ly.planes;
   ly.N = N; ly.P = P; ly.B = B; ly.n_max = n_max; ly.bf16 = bf16;
   ly.G = per_sentence ? B : 1;
   ly.S1pad = (S1 + 63) / 64 * 64; ly.S2pad = (S2 + 63) / 64 * 64;
@@ -85,8 +90,10 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   ly.Wp = take(w4 * 2 * (size_t)ly.Np * ly.Pp * ly.G);
   ly.Wtn = take(w4 * 2 * (size_t)ly.Np * ly.Np * ly.G);
   ly.Wtp = take(w4 * 2 * (size_t)ly.Np * ly.Pp * ly.G);
-  if (ly.planes == 3) {
-    ly.Wn3 = take(6 * 2 * (size_t)ly.Np * ly.Np); ly.Wp3 = take(6 * 2 * (size_t)ly.Np * ly.Pp);
+  if (ly.planes >= 2) {
+    ly.Wn3 = take(2 * (size_t)ly.planes * 2 * ly.Np * ly.Np); ly.Wp3 = take(2 * (size_t)ly.planes * 2 * ly.Np * ly.Pp);
+  }
+  if (ly.planes_bwd == 3) {
     ly.Wtn3 = take(6 * 2 * (size_t)ly.Np * ly.Np); ly.Wtp3 = take(6 * 2 * (size_t)ly.Np * ly.Pp);
   }
   if (per_sentence) { ly.sentrows = take(i4 * (size_t)S2); ly.sentoff = take(i4 * (size_t)B); }
@@ -98,7 +105,7 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   }
   if (ly.planes > 0) {
     ly.Tb = take(2 * (size_t)ly.planes * S2 * ly.Np);
-    ly.UVb = take(2 * (size_t)ly.planes * ly.Sall * 2 * ly.Np);
+    ly.UVb = take(2 * (size_t)ly.planes_bwd * ly.Sall * 2 * ly.Np);
     ly.leafEb = take(2 * (size_t)ly.planes * S1 * ly.Pp);
   }
   ly.leafE = take(f4 * (size_t)S1 * ly.Pp);
@@ -124,7 +131,7 @@ Ptrs resolve(const Layout& ly, void* ws) {
   p.UV = (float*)(b + ly.UV); p.BH = (float*)(b + ly.BH);
   p.partial = (float*)(b + ly.partial); p.counters = (int32_t*)(b + ly.counters);
   p.sentrows = (int32_t*)(b + ly.sentrows); p.sentoff = (int32_t*)(b + ly.sentoff);
-  p.Tb = ly.planes ? b + ly.Tb : nullptr; p.UVb = ly.planes ? b + ly.UVb : nullptr; p.leafEb = ly.planes ? b + ly.leafEb : nullptr;
+  p.Tb = ly.planes ? b + ly.Tb : nullptr; p.UVb = ly.planes_bwd ? b + ly.UVb : nullptr; p.leafEb = ly.planes ? b + ly.leafEb : nullptr;
   p.UVt_n = b + ly.UVt_n; p.Tt = b + ly.Tt; p.UVt_p = b + ly.UVt_p; p.Et = b + ly.Et;
   p.Wn3 = b + ly.Wn3; p.Wp3 = b + ly.Wp3; p.Wtn3 = b + ly.Wtn3; p.Wtp3 = b + ly.Wtp3;
   p.Wn = (float*)(b + ly.Wn); p.Wp = (float*)(b + ly.Wp); p.Wtn = (float*)(b + ly.Wtn); p.Wtp = (float*)(b + ly.Wtp);
@@ -152,7 +159,7 @@ int make_plan(const spcfg_config* cfg, const int32_t* lengths, int B, int n_max,
   if (Sall >= (int64_t)1 << 30) return SPCFG_ERR_SHAPE;
   *ly = make_layout(cfg->N, cfg->P, B, n_max, S1, Sall - S1, cfg->precision == SPCFG_PRECISION_BF16,
                     (cfg->flags & SPCFG_FLAG_PER_SENTENCE_GRAMMAR) != 0, (cfg->flags & SPCFG_FLAG_FP32_MFMA) != 0,
-                    gemm_wgs);
+                    (cfg->flags & SPCFG_FLAG_BF16_SINGLE_FORWARD) != 0, gemm_wgs);
   return SPCFG_OK;
 }
 
@@ -249,7 +256,10 @@ WidthBlocks width_blocks(const Plan& plan, const Layout& ly, int w) {
   }
   return k;
 }
-bool use_parts(const Layout& ly, int w) { return ly.G == 1 && !ly.bf16 && w >= 2; }
+// (the bf16 mode has a kernel with parts for its forward products only)
+bool use_parts(const Layout& ly, int w, bool forward_product) {
+  return ly.G == 1 && (!ly.bf16 || (forward_product && ly.planes == 2)) && w >= 2;
+}
 void set_part(NtArgs& a, int i, int row0, int rows, int c0, int kbeg, int kt) {
   a.prt_row0[i] = row0; a.prt_rows[i] = rows; a.prt_c0[i] = c0; a.prt_kbeg[i] = kbeg; a.prt_kt[i] = kt;
 }
@@ -279,7 +289,10 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
   leaf.partial = p.partial; leaf.counters = p.counters; leaf.max_wgs = ly.gemm_wgs; leaf.n_counters = ly.n_counters; leaf.b_bf16 = ly.bf16; leaf.fp32_mfma = fp32_mfma;
   leaf.A = p.leafE; leaf.lda = Pp; leaf.Bm = p.Wp; leaf.ldb = Pp; leaf.C = p.HZ; leaf.ldc = 2 * Np;
   if (ly.bf16) { leaf.A = p.leafEb; leaf.a_bf16 = 1; }
-  if (ly.planes == 3) { leaf.A3 = p.leafEb; leaf.Bm3 = p.Wp3; leaf.planes3 = 1; leaf.a_plane = ly.S1 * Pp; leaf.b_plane = 2 * Np * Pp; }
+  if (ly.planes >= 2) {
+    leaf.A3 = p.leafEb; leaf.Bm3 = p.Wp3; leaf.planes3 = ly.planes; leaf.a_plane = ly.S1 * Pp; leaf.b_plane = 2 * Np * Pp;
+    leaf.a_bf16 = 0; leaf.b_bf16 = 0;
+  }
   leaf.rows = (int)ly.S1; leaf.cols = (int)(2 * Np); leaf.K = (int)Pp;
   leaf.epilogue = NT_EPI_ROWSCALE; leaf.rowmaxb = p.tmaxb;
   set_groups(leaf, plan, ly, p, 1, 0, 2 * Np * Pp);
@@ -309,16 +322,17 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.a_bf16 = 1; }
-    if (ly.planes == 3) {
+    if (ly.planes >= 2) {
       a.A3 = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.Bm3 = p.Wn3;
-      a.planes3 = 1; a.a_plane = ly.S2 * Np; a.b_plane = 2 * Np * Np;
+      a.planes3 = ly.planes; a.a_plane = ly.S2 * Np; a.b_plane = 2 * Np * Np;
+      a.a_bf16 = 0; a.b_bf16 = 0;
     }
     a.C = p.HZ + row0 * 2 * Np; a.ldc = 2 * Np;
     a.rows = (int)rows; a.cols = (int)(2 * Np); a.K = (int)Np;
     a.epilogue = NT_EPI_ROWSCALE; a.rowmaxb = p.tmaxb + row0;
     // eta for the prefix and middle rows, zeta for the middle and suffix rows (when Np is not a whole number of
     // 128-column tiles the two column blocks would each pad their last tile: one product of 2Np columns then)
-    if (use_parts(ly, w) && Np % 128 == 0) {
+    if (use_parts(ly, w, true) && Np % 128 == 0) {
       const WidthBlocks k = width_blocks(plan, ly, w);
       const int kt = (int)(Np / 32);
       // the profile counts the executed flop: one of the two projections is left out for k.nP + k.nS rows
@@ -370,15 +384,15 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
     a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
     a.A = p.UV + row0 * 2 * Np; a.lda = 2 * Np; a.K = (int)(2 * Np); a.rows = (int)rows;
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np; a.a_bf16 = 1; }
-    if (ly.planes == 3) {
+    if (ly.planes_bwd == 3) {
       a.A3 = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np; a.Bm3 = w >= 2 ? p.Wtn3 : p.Wtp3;
-      a.planes3 = 1; a.a_plane = ly.Sall * 2 * Np; a.b_plane = 2 * Np * (w >= 2 ? Np : Pp);
+      a.planes3 = 3; a.a_plane = ly.Sall * 2 * Np; a.b_plane = 2 * Np * (w >= 2 ? Np : Pp);
     }
     if (w >= 2) {
       gemm_flop = 4.0 * ly.N * (double)ly.N * rows;
       a.Bm = p.Wtn; a.ldb = 2 * Np; a.C = p.BH + (row0 - ly.S1) * Np; a.ldc = Np; a.cols = (int)Np;
       a.epilogue = NT_EPI_MASKROWS; a.rowmask = p.rootmask + row0; a.rowmaxb = p.umaxb + row0;
-      if (use_parts(ly, w)) {  // prefix rows: only the eta adjoint (first half of K); suffix rows: only zeta's
+      if (use_parts(ly, w, false)) {  // prefix rows: only the eta adjoint (first half of K); suffix rows: only zeta's
         const WidthBlocks k = width_blocks(plan, ly, w);
         const int kt = (int)(Np / 32);
         a.parts = 3;
@@ -527,7 +541,8 @@ int spcfg_workspace_bytes(const spcfg_config* cfg, size_t* out_bytes) {
   *out_bytes = make_layout(cfg->N, cfg->P, cfg->max_B, cfg->max_n, S1, Sall - S1,
                            cfg->precision == SPCFG_PRECISION_BF16,
                            (cfg->flags & SPCFG_FLAG_PER_SENTENCE_GRAMMAR) != 0,
-                           (cfg->flags & SPCFG_FLAG_FP32_MFMA) != 0).total;
+                           (cfg->flags & SPCFG_FLAG_FP32_MFMA) != 0,
+                           (cfg->flags & SPCFG_FLAG_BF16_SINGLE_FORWARD) != 0).total;
   return SPCFG_OK;
 }
 

@@ -42,16 +42,18 @@ struct Layout {
   int N, P, Np, Pp, B, n_max;
   int G;                 // number of grammars: 1 (shared by the batch) or B (one per sentence)
   int bf16;              // projections with bf16 operands: packed weights are bf16, transposed bf16 copies for the rule gradients
-  int planes;            // bf16 planes that producers write beside every fp32 chart row for the projection products:
-                         // 0 none (fp32 operands are staged and cut in the kernel), 1 the bf16 rounding (bf16 mode),
-                         // 3 the exact cut hi + mid + lo of every fp32 value (fp32 mode, shared grammar)
+  int planes;            // bf16 planes that producers write beside every fp32 chart row for the forward projection products:
+                         // 0 none (fp32 operands are staged and cut in the kernel), 1 the bf16 rounding (bf16 mode, one
+                         // grammar per sentence), 2 hi + lo (bf16 mode, shared grammar), 3 the exact cut hi + mid + lo
+                         // of every fp32 value (fp32 mode, shared grammar)
+  int planes_bwd;        // the same for the adjoint rows of the reverse products: 0, 1 (bf16 mode) or 3
   int64_t S1pad, S2pad;  // row counts rounded up to 64 (K of the bf16 rule-gradient product)
   int64_t S1, S2, Sall;  // leaf rows, rows of width >= 2, all rows
   // byte offsets into the workspace
   size_t lens, rowbase, row_b, row_i, rootmask, rootrow, mexp, uexp, tmaxb, umaxb, hmaxb, zmaxb, gsc, xs, ztil, rmax;
   size_t leafE, T, HZ, UV, BH, Wn, Wp, Wtn, Wtp, partial, counters;
   size_t colmax;  // [G][2][Np + Pp]: largest entry of every column of L (then of R), nonterminal columns first
-  size_t Wn3, Wp3, Wtn3, Wtp3;  // planes == 3: the packed panels once more, cut into three bf16 planes
+  size_t Wn3, Wp3, Wtn3, Wtp3;  // the packed panels once more, cut into bf16 planes: Wn3 / Wp3 `planes` of them (if >= 2), Wtn3 / Wtp3 three (planes_bwd == 3)
   size_t UVt_n, Tt, UVt_p, Et;  // bf16 mode only
   size_t Tb, UVb, leafEb;       // planes > 0: bf16 planes of T, UV, leafE ([planes][rows][cols]), written by their producers
   size_t sentrows, sentoff;     // per-sentence grammars only: rows of width >= 2 listed sentence by sentence, first entry of each
@@ -161,11 +163,12 @@ struct NtArgs {
   // column block each) and "prefix / middle / suffix rows" (reverse: the adjoint of zeta resp. eta is zero, half
   // of K is skipped) are contiguous ranges.
   int fp32_mfma;  // 1: fp32 matrix instructions instead of the split-bf16 scheme (fp32 operands only)
-  // planes3 = 1: both operands are given as three bf16 planes (the exact cut hi + mid + lo of every fp32 value,
-  // nt::Split3), written by their producers: A = [3][..][lda] with planes a_plane elements apart, Bm likewise with
-  // b_plane; A and Bm then point to bf16 data and the product runs in gemm_nt3.hip.
-  // A3 / Bm3 are those planes; A / Bm stay the fp32 operands, which the launches with short row tiles use (their time
-  // goes into reading the panel once, and the fp32 panel is a third shorter than its three planes).
+  // planes3 = 3: both operands are also given as three bf16 planes (the exact cut hi + mid + lo of every fp32 value,
+  // nt::Split3), written by their producers: A3 = [3][..][lda] with planes a_plane elements apart, Bm3 likewise with
+  // b_plane; the launches with tall row tiles run on them in gemm_nt3.hip.  A / Bm stay the fp32 operands, which the
+  // launches with short row tiles use (their time goes into reading the panel once, and the fp32 panel is a third
+  // shorter than its three planes).  planes3 = 2: two planes (hi, lo) and every launch runs on them (forward products
+  // of the bf16 mode).
   int planes3; int64_t a_plane, b_plane;
   const void* A3; const void* Bm3;
   int parts;
@@ -175,7 +178,7 @@ void launch_gemm_nt(const NtArgs& a, hipStream_t st);
 void launch_gemm_nt16(const NtArgs& a, hipStream_t st);  // bf16-operand variant (called through launch_gemm_nt)
 void launch_gemm_nt3(const NtArgs& a, hipStream_t st);   // pre-cut three-plane operands (called through launch_gemm_nt)
 bool gemm_nt_keep_parts(NtArgs& a);             // drops the parts of a launch that would not save work
-bool gemm_nt_reads_planes(const NtArgs& a);     // whether launch_gemm_nt will read the three-plane operands (A3 / Bm3)
+bool gemm_nt_reads_planes(const NtArgs& a);     // whether launch_gemm_nt will read the plane operands (A3 / Bm3)
 int gemm_nt_tiles(int rows, int cols);           // number of output tiles (= arrival counters needed)
 size_t gemm_nt_partial_bytes(int max_wgs);       // scratch needed for partial tiles
 constexpr int kGemmWgs = 512;                    // workgroups per projection launch: 2 per CU on 256 CUs

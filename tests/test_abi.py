@@ -43,7 +43,7 @@ def test_workspace_query_and_monotonicity():
 
 @pytest.mark.parametrize("kwargs,code", [
     (dict(N=0), -2), (dict(P=0), -2), (dict(max_B=0), -2), (dict(max_B=5000), -2), (dict(max_n=1), -2),
-    (dict(precision=7), -5), (dict(flags=64), -5), (dict(flags=8), -5),
+    (dict(precision=7), -5), (dict(flags=64), -5), (dict(flags=16), -5),
 ])
 def test_bad_config_is_rejected(kwargs, code):
     base = dict(N=8, P=8, max_B=2, max_n=6, precision=0, flags=0)
@@ -56,7 +56,8 @@ def test_bad_config_is_rejected(kwargs, code):
 
 def test_every_documented_flag_is_accepted():
     for flags in (0, bd.FLAG_ACCUMULATE_GRADS, bd.FLAG_PER_SENTENCE_GRAMMAR, bd.FLAG_FP32_MFMA,
-                  bd.FLAG_ACCUMULATE_GRADS | bd.FLAG_PER_SENTENCE_GRAMMAR | bd.FLAG_FP32_MFMA):
+                  bd.FLAG_BF16_SINGLE_FORWARD,
+                  bd.FLAG_ACCUMULATE_GRADS | bd.FLAG_PER_SENTENCE_GRAMMAR | bd.FLAG_FP32_MFMA | bd.FLAG_BF16_SINGLE_FORWARD):
         for precision in (bd.PRECISION_FP32, bd.PRECISION_BF16):
             cfg = bd.make_config(8, 8, 2, 6, precision, flags)
             assert bd.spcfg_workspace_bytes(cfg) > 0
