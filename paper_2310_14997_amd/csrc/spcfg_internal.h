@@ -12,6 +12,11 @@
 //                      likewise with R, which bounds the largest entry of eta (zeta) from below to within a factor 4N.
 //                      A grammar whose weights are tiny everywhere gives tiny projections, and with these shifts the
 //                      split products eta * zeta stay inside the fp32 range
+//                      Halves that no span ever reads are left unwritten when the launch is cut into parts (shared
+//                      grammar, width >= 2, Np a multiple of 128): zeta of the prefix rows (i = 0) and eta of the
+//                      suffix rows (j = n) of HZ hold whatever the workspace held before the call.  No kernel reads them (the split kernels pick a child's half by
+//                      its position); anything added later that walks HZ must do the same.  A test runs with a
+//                      workspace pre-filled with 0xFF bytes to catch a read of such a half.
 //   reverse pass:      UV[r]    = unnormalised adjoints of [eta | zeta]                   (exponent uexp[r])
 //                      BH[r]    = 2^-f' * UV[r] * [L;R]  = scaled adjoint of beta         (exponent uexp[r] + f')
 // f (f') is the shift that brings the largest magnitude of T[r] (UV[r]) into [0.5, 1).  The split kernels
