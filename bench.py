@@ -128,6 +128,19 @@ def time_decode(wl, steps):
     return res
 
 
+def mfma_sustained():
+    """What a register-only loop of the products' matrix instruction sustains on this GPU right now (bench_mfma_ceiling.hip,
+    built beside the library): the published peak assumes 2.4 GHz, and the chip lowers its clock under matrix load,
+    the more the more the operands change.  Context for roofline.frac, which stays priced against the published peak."""
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2310_14997_amd", "mfma_ceiling.bin")
+    try:
+        res = subprocess.run([exe], capture_output=True, text=True, timeout=60, check=True)
+        return json.loads(res.stdout.strip().splitlines()[-1])
+    except Exception as e:  # the probe is optional: report why it is missing rather than fail the benchmark
+        return {"error": repr(e)[:200]}
+
+
 def measure(d, bf16, fp32_mfma, steps, warmup, profile_steps, graph=False, extra_flags=0):
     """Times `steps` forward+backward steps on the batch `d` (inputs resident in HBM), then repeats `profile_steps`
     steps with HIP events bound to every kernel's own dispatch for the per-class times."""
@@ -220,6 +233,8 @@ def main():
     ap.add_argument("--cpu-sentences", type=int, default=64,
                     help="sentences of the batch the CPU oracle is timed on (stops after about 25 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="skip the short register-only matrix-instruction loop reported under \"mfma_sustained\"")
     ap.add_argument("--frontend", action="store_true",
                     help="also time the rule-probability front-end (softmaxes + emission gather) and its backward "
                          "at the workload's shape; reported under \"frontend\", not part of the step")
@@ -330,6 +345,8 @@ def main():
         out["frontend"] = time_frontend(args.workload, wl, args.steps)
     if args.decode:
         out["decode"] = time_decode(wl, args.steps)
+    if args.workload == "ptb" and not args.no_mfma_probe:
+        out["mfma_sustained"] = mfma_sustained()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(d, args.cpu_sentences)
     print(json.dumps(out))
