@@ -65,7 +65,7 @@ enum {
      from operands cut into two bf16 pieces (hi + lo, three piece products, operands good to 2^-17), so that log Z
      stays within about 1e-3 of exact arithmetic whatever the grammar and the sentence length.  This flag rounds those
      operands to a single bf16 instead, as the reverse and rule-gradient products always do: a third of the matrix
-     work in the forward products (the Scaled configuration runs 15 % faster), but roundings of 2^-9 per projection
+     work in the forward products (the Scaled configuration takes 16 % less time), but roundings of 2^-9 per projection
      then add up along a tree: measured up to 0.07 absolute in log Z on small peaked grammars with sentences of
      60-100 words, 0.6e-3 to 1.5e-3 on large unpeaked ones at n = 40.  No effect with SPCFG_PRECISION_FP32 or with
      one grammar per sentence (single bf16 operands there). */
