@@ -276,10 +276,9 @@ __device__ __forceinline__ void finish_tile(float* partial, int32_t* counters, f
   }
 }
 
-// Tile height and workgroup count per launch, from a sweep on MI355X (256 CUs): what matters is the amount
-// of work relative to the machine, so the thresholds are in multiply-accumulates (rows * cols * K).  Small
-// launches want short tiles (finer shares, less padding) and one workgroup per CU; large ones tall tiles
-// (less LDS and L2 traffic per flop) and two workgroups per CU.
+// Tile height per launch, from a sweep on MI355X (256 CUs): what matters is the amount of work relative to the
+// machine, so the thresholds are in multiply-accumulates (rows * cols * K).  Small launches want short tiles
+// (finer shares, less padding), large ones tall tiles (less LDS and L2 traffic per flop).
 inline double work_of(const NtArgs& a) {
   if (a.parts == 0) return (double)(a.grouped ? a.grp_max_rows : a.rows) * a.cols * a.K;
   double w = 0;
@@ -297,8 +296,13 @@ inline int pick_bm(int rows, double work, bool bf16, bool wide) {
   if (rows <= 64 || work <= t128) return 64;
   return 128;
 }
-inline int pick_wgs(double work) {
-  return work <= 8e7 ? 128 : (work <= 4.5e8 ? 256 : 512);
+// Workgroups of a launch from its (tile, K-step) units (counted in steps of 32 K values): few units want few
+// workgroups (every further share of a tile is one more partial tile for the reducing workgroup to read), many want
+// two workgroups per CU.  Sweeps at N = 1024 and 2048, 4 to 150 rows, forward and reverse shapes: 128 workgroups are
+// best below 1024 units, 256 below 4096, 512 above (each within 3 % of the best of the three everywhere).
+inline int pick_wgs(int total_units, int bk_elems) {
+  const int64_t u = (int64_t)total_units * bk_elems / 32;
+  return u < 1024 ? 128 : (u < 4096 ? 256 : 512);
 }
 
 
@@ -319,7 +323,7 @@ void launch_shared(Kernel kernel, const NtArgs& a, int BM, int BKelems, size_t l
     if (total == 0) return;
   }
   if (tiles > a.n_counters) { launch_refused("projection product: more output tiles than arrival counters"); return; }
-  int Gn = pick_wgs(a.parts ? work_of(a) : (double)a.rows * a.cols * a.K);
+  int Gn = pick_wgs(total, BKelems);
   const int cap = a.max_wgs * (128 / BM);  // the partial-tile scratch holds 2 * max_wgs slots of 128 x 128
   if (Gn > cap) Gn = cap;
   if (Gn > total / 2) Gn = total / 2 > 0 ? total / 2 : 1;  // at least two K-steps per share
