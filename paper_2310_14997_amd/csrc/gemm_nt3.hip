@@ -11,7 +11,7 @@
 //  * LDS rows are 64 bytes (32 bf16) without padding; the 16-byte chunk index is XORed with bits 2..3 of the row, which
 //    makes the 16-byte operand reads of 16 consecutive rows conflict-free (the loads apply the same permutation on the
 //    global side, four lanes per row);
-//  * one 256-thread workgroup per CU (the ring takes 144-150 KB of LDS), 4 wavefronts as in the other projection kernels;
+//  * one 256-thread workgroup per CU (the ring takes 120-150 KB of LDS), 4 wavefronts as in the other projection kernels;
 //  * the instruction order of a K-step is written out: operand reads are inline assembly (so every wait is placed by
 //    hand), matrix instructions, reads and loads alternate, and the one barrier per step sits behind the first matrix
 //    instructions of the step's second half, so the matrix pipe has work while the wavefronts meet.
