@@ -52,8 +52,8 @@ enum {
      depend on a per-sentence latent vector).  log_root is then [B x N], L and R are [B x N x M], and
      grad_log_root, grad_L, grad_R have the same per-sentence shapes (no sum over the batch).  The projections
      become grouped products: each sentence's spans meet that sentence's [L;R] panel.  With
-     SPCFG_PRECISION_BF16 the projections round their operands to bf16 as usual; the per-sentence rule
-     gradients are then reduced with fp32 operands. */
+     SPCFG_PRECISION_BF16 the forward projections then read fp32 operands (so that log Z keeps its bound), the
+     reverse projections bf16 ones, and the per-sentence rule gradients are reduced with fp32 operands. */
   SPCFG_FLAG_PER_SENTENCE_GRAMMAR = 2u,
   /* SPCFG_PRECISION_FP32 forms its matrix products from bf16 matrix instructions by default: every fp32
      operand is cut exactly into three bf16 pieces and six piece products are accumulated in fp32, which keeps
@@ -67,8 +67,8 @@ enum {
      operands to a single bf16 instead, as the reverse and rule-gradient products always do: a third of the matrix
      work in the forward products (the Scaled configuration takes 16 % less time), but roundings of 2^-9 per projection
      then add up along a tree: measured up to 0.07 absolute in log Z on small peaked grammars with sentences of
-     60-100 words, 0.6e-3 to 1.5e-3 on large unpeaked ones at n = 40.  No effect with SPCFG_PRECISION_FP32 or with
-     one grammar per sentence (single bf16 operands there). */
+     60-100 words, 0.6e-3 to 1.5e-3 on large unpeaked ones at n = 40.  With one grammar per sentence the flag replaces
+     the fp32 operands of the forward products by single bf16 ones.  No effect with SPCFG_PRECISION_FP32. */
   SPCFG_FLAG_BF16_SINGLE_FORWARD = 8u
 };
 

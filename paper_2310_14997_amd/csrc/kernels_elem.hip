@@ -812,6 +812,13 @@ void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const 
   if (ly.planes == 2)  // the panels of the forward products as two bf16 planes
     launch_k(k_pack_weights<uint16_t, 2>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
                        (uint16_t*)p.Wn3, (uint16_t*)p.Wp3, (uint16_t*)nullptr, (uint16_t*)nullptr, (uint32_t*)nullptr);
+  if (ly.fwd_fp32) {  // fp32 panels for the forward products, bf16 panels for the reverse ones
+    launch_k(k_pack_weights<float, 1>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp, p.Wn, p.Wp,
+                       (float*)nullptr, (float*)nullptr, cm);
+    launch_k(k_pack_weights<__bf16, 1>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
+                       (__bf16*)nullptr, (__bf16*)nullptr, (__bf16*)p.Wtn, (__bf16*)p.Wtp, (uint32_t*)nullptr);
+    return;
+  }
   if (ly.planes == 2)  // single bf16 panels of the reverse products only
     launch_k(k_pack_weights<__bf16, 1>, grid, dim3(32, 8), 0, st, L, R, ly.N, ly.P, ly.Np, ly.Pp,
                        (__bf16*)nullptr, (__bf16*)nullptr, (__bf16*)p.Wtn, (__bf16*)p.Wtp, cm);

@@ -42,9 +42,12 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   // Operand planes for the projection products.  fp32 mode with a shared grammar: the exact three-piece cut, forward
   // and reverse (the products then never cut operands themselves).  bf16 mode with a shared grammar: two pieces
   // (hi + lo) for the forward products, which decide log Z, the plain bf16 rounding for the reverse ones; with one
-  // grammar per sentence, or when the caller asks for single bf16 operands, one plane both ways.
+  // grammar per sentence the forward products run on fp32 operands instead (the grouped kernel cuts them itself; there
+  // is no grouped kernel on planes), the reverse ones on one plane; one plane both ways when the caller asks for single
+  // bf16 operands.
   const bool shared = !(per_sentence && B > 1);
-  ly.planes = bf16 ? (shared && !bf16_single ? 2 : 1) : (!shared || fp32_mfma ? 0 : 3);
+  ly.fwd_fp32 = bf16 && !shared && !bf16_single;
+  ly.planes = bf16 ? (bf16_single ? 1 : (shared ? 2 : 0)) : (!shared || fp32_mfma ? 0 : 3);
   ly.planes_bwd = bf16 ? 1 : ly.planes;
   ly.N = N; ly.P = P; ly.B = B; ly.n_max = n_max; ly.bf16 = bf16;
   ly.G = per_sentence ? B : 1;
@@ -86,8 +89,9 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   ly.counters = take(i4 * (size_t)ly.n_counters);
   ly.partial = take(gemm_nt_partial_bytes(gemm_wgs));
   const size_t w4 = bf16 ? 2 : 4;  // bytes per packed weight
-  ly.Wn = take(w4 * 2 * (size_t)ly.Np * ly.Np * ly.G);
-  ly.Wp = take(w4 * 2 * (size_t)ly.Np * ly.Pp * ly.G);
+  const size_t w4f = (bf16 && !ly.fwd_fp32) ? 2 : 4;  // ... of the forward panels
+  ly.Wn = take(w4f * 2 * (size_t)ly.Np * ly.Np * ly.G);
+  ly.Wp = take(w4f * 2 * (size_t)ly.Np * ly.Pp * ly.G);
   ly.Wtn = take(w4 * 2 * (size_t)ly.Np * ly.Np * ly.G);
   ly.Wtp = take(w4 * 2 * (size_t)ly.Np * ly.Pp * ly.G);
   if (ly.planes >= 2) {
@@ -105,9 +109,9 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
   }
   if (ly.planes > 0) {
     ly.Tb = take(2 * (size_t)ly.planes * S2 * ly.Np);
-    ly.UVb = take(2 * (size_t)ly.planes_bwd * ly.Sall * 2 * ly.Np);
     ly.leafEb = take(2 * (size_t)ly.planes * S1 * ly.Pp);
   }
+  if (ly.planes_bwd > 0) ly.UVb = take(2 * (size_t)ly.planes_bwd * ly.Sall * 2 * ly.Np);
   ly.leafE = take(f4 * (size_t)S1 * ly.Pp);
   ly.T = take(f4 * (size_t)S2 * ly.Np);
   ly.BH = take(f4 * (size_t)S2 * ly.Np);
@@ -286,9 +290,9 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
   const int fp32_mfma = (cfg->flags & SPCFG_FLAG_FP32_MFMA) ? 1 : 0;
   // width 1: [eta | zeta] = [L_P ; R_P] * emission vector
   NtArgs leaf{};
-  leaf.partial = p.partial; leaf.counters = p.counters; leaf.max_wgs = ly.gemm_wgs; leaf.n_counters = ly.n_counters; leaf.b_bf16 = ly.bf16; leaf.fp32_mfma = fp32_mfma;
+  leaf.partial = p.partial; leaf.counters = p.counters; leaf.max_wgs = ly.gemm_wgs; leaf.n_counters = ly.n_counters; leaf.b_bf16 = ly.bf16 && !ly.fwd_fp32; leaf.fp32_mfma = fp32_mfma;
   leaf.A = p.leafE; leaf.lda = Pp; leaf.Bm = p.Wp; leaf.ldb = Pp; leaf.C = p.HZ; leaf.ldc = 2 * Np;
-  if (ly.bf16) { leaf.A = p.leafEb; leaf.a_bf16 = 1; }
+  if (ly.bf16 && !ly.fwd_fp32) { leaf.A = p.leafEb; leaf.a_bf16 = 1; }
   if (ly.planes >= 2) {
     leaf.A3 = p.leafEb; leaf.Bm3 = p.Wp3; leaf.planes3 = ly.planes; leaf.a_plane = ly.S1 * Pp; leaf.b_plane = 2 * Np * Pp;
     leaf.a_bf16 = 0; leaf.b_bf16 = 0;
@@ -302,7 +306,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     if (ly.G > 1) launch_plan_sentrows(ly, p, st);
     launch_pack_weights(ly, p, L, R, st);
     // operand planes are written only for the launches that read them (bf16 mode: all of them)
-    launch_leaf_prep(ly, p, log_emit, ly.bf16 || gemm_nt_reads_planes(leaf), st);
+    launch_leaf_prep(ly, p, log_emit, (ly.bf16 && !ly.fwd_fp32) || gemm_nt_reads_planes(leaf), st);
   }
   {
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.P * ly.S1);
@@ -319,9 +323,9 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     }
     NtArgs a{};
     double skipped = 0.0;
-    a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16; a.fp32_mfma = fp32_mfma;
+    a.partial = p.partial; a.counters = p.counters; a.max_wgs = ly.gemm_wgs; a.n_counters = ly.n_counters; a.b_bf16 = ly.bf16 && !ly.fwd_fp32; a.fp32_mfma = fp32_mfma;
     a.A = p.T + (row0 - ly.S1) * Np; a.lda = Np; a.Bm = p.Wn; a.ldb = Np;
-    if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.a_bf16 = 1; }
+    if (ly.bf16 && !ly.fwd_fp32) { a.A = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.a_bf16 = 1; }
     if (ly.planes >= 2) {
       a.A3 = static_cast<const uint16_t*>(p.Tb) + (row0 - ly.S1) * Np; a.Bm3 = p.Wn3;
       a.planes3 = ly.planes; a.a_plane = ly.S2 * Np; a.b_plane = 2 * Np * Np;
@@ -344,7 +348,7 @@ int forward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const P
     set_groups(a, plan, ly, p, w, row0, 2 * Np * Np);
     {
       Scope s(st, SPCFG_PROF_SPLIT_FWD, split_bytes);
-      launch_split_fwd(ly, p, w, row0, rows, ly.bf16 || gemm_nt_reads_planes(a), st);
+      launch_split_fwd(ly, p, w, row0, rows, (ly.bf16 && !ly.fwd_fp32) || gemm_nt_reads_planes(a), st);
     }
     Scope s(st, SPCFG_PROF_GEMM_FWD, 4.0 * ly.N * (double)ly.N * rows - skipped);
     launch_gemm_nt(a, st);

@@ -52,6 +52,8 @@ struct Layout {
                          // grammar per sentence), 2 hi + lo (bf16 mode, shared grammar), 3 the exact cut hi + mid + lo
                          // of every fp32 value (fp32 mode, shared grammar)
   int planes_bwd;        // the same for the adjoint rows of the reverse products: 0, 1 (bf16 mode) or 3
+  int fwd_fp32;          // bf16 mode with one grammar per sentence: the forward products read fp32 operands (Wn / Wp are
+                         // fp32 then, Wtn / Wtp bf16)
   int64_t S1pad, S2pad;  // row counts rounded up to 64 (K of the bf16 rule-gradient product)
   int64_t S1, S2, Sall;  // leaf rows, rows of width >= 2, all rows
   // byte offsets into the workspace
