@@ -211,7 +211,7 @@ def measure(d, bf16, fp32_mfma, steps, warmup, profile_steps, graph=False, extra
                        "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                        "launches_per_step": proj_launches, "avg_launch_us": proj_ms * 1e3 / max(proj_launches, 1),
                        "flop_per_launch": proj_flop / max(proj_launches, 1)}
-    res["gemm_grad"] = {"bound": "mfma", "kernel": "rule-gradient product (k_gemm_tn; bf16 mode: transposes + k_gemm_nt16)",
+    res["gemm_grad"] = {"bound": "mfma", "kernel": "rule-gradient product (fp32 mode: k_gemm_tn3 on pre-cut bf16 planes incl. the kernel that scales and cuts the inside vectors; fp32 matrix instructions or per-sentence grammars: k_gemm_tn; bf16 mode: transposes + k_gemm_nt16)",
                         "mfma": mfma, "achieved": gg_tflops, "peak": peak, "unit": "TFLOP/s", "frac": gg_tflops / peak,
                         "ms_per_step": gg["ms_per_step"]}
     res["split_reduction"] = {"bound": "hbm", "achieved": split_bytes / (split_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,

@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libspcfg.so")
 CLIENT = os.path.join(HERE, "abi_client.bin")  # plain C program that uses the library through its C ABI only
 CEILING_SRC = os.path.join(os.path.dirname(HERE), "bench_mfma_ceiling.hip")  # measurement aid of bench.py
 CEILING = os.path.join(HERE, "mfma_ceiling.bin")
-SOURCES = ["spcfg_api.hip", "kernels_elem.hip", "gemm_nt.hip", "gemm_nt16.hip", "gemm_nt3.hip", "gemm_tn.hip", "rules_frontend.hip", "decode.hip"]
+SOURCES = ["spcfg_api.hip", "kernels_elem.hip", "gemm_nt.hip", "gemm_nt16.hip", "gemm_nt3.hip", "gemm_tn.hip", "gemm_tn3.hip", "rules_frontend.hip", "decode.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
          # packed fp32 ops are kept off for all device code on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -294,6 +294,28 @@ __global__ void k_pack_weights(const float* __restrict__ L, const float* __restr
   }
 }
 
+// Operand planes of the rule-gradient product on planes: the three bf16 pieces of sc[s] * X[s][.] for s < S, zero for
+// the rows up to the end of the last 32-row step (the product reads whole steps).  One thread per four columns.
+__global__ void k_scaled_planes(const float* __restrict__ X, int64_t ld, const float* __restrict__ sc, int64_t S,
+                                uint16_t* __restrict__ planes, int64_t plane_stride) {
+  const int64_t s = blockIdx.x;
+  const int c = (blockIdx.y * blockDim.x + threadIdx.x) * 4;
+  if (c >= ld) return;
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (s < S) {
+    const float f = sc[s];
+    const float4 x = *reinterpret_cast<const float4*>(X + s * ld + c);
+    v = make_float4(f * x.x, f * x.y, f * x.z, f * x.w);
+  }
+  store_planes4(planes, 3, plane_stride, s * ld + c, v);
+}
+
+__global__ void k_zero_plane_rows(uint16_t* __restrict__ planes, int64_t plane_stride, int64_t first, int64_t count) {
+  uint16_t* p = planes + (int64_t)blockIdx.y * plane_stride + first;
+  for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8; i < count; i += (int64_t)gridDim.x * blockDim.x * 8)
+    *reinterpret_cast<uint4*>(p + i) = uint4{0u, 0u, 0u, 0u};  // count and first are multiples of 8 elements
+}
+
 __global__ void k_zero_u32(uint32_t* __restrict__ p, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
@@ -830,6 +852,19 @@ void launch_pack_weights(const Layout& ly, const Ptrs& p, const float* L, const 
                        p.Wtn, p.Wtp, cm);
 }
 
+void launch_scaled_planes(const float* X, int64_t ld, const float* sc, int64_t S, int64_t Srows, void* planes,
+                          int64_t plane_stride, hipStream_t st) {
+  if (Srows <= 0) return;
+  const dim3 grid((unsigned)Srows, (unsigned)((ld / 4 + 255) / 256));
+  launch_k(k_scaled_planes, grid, dim3(256), 0, st, X, ld, sc, S, static_cast<uint16_t*>(planes), plane_stride);
+}
+
+void launch_zero_plane_rows(void* planes, int64_t plane_stride, int64_t ld, int64_t row0, int64_t rows, hipStream_t st) {
+  const int64_t count = rows * ld;  // ld is a multiple of 64
+  launch_k(k_zero_plane_rows, dim3((unsigned)((count / 8 + 255) / 256 < 256 ? (count / 8 + 255) / 256 : 256), 3), dim3(256), 0, st,
+           static_cast<uint16_t*>(planes), plane_stride, row0 * ld, count);
+}
+
 void launch_transpose_bf16(const float* X, int64_t ldx, int cols, const float* sc, int64_t S, int64_t Spad, void* Xt,
                            hipStream_t st) {
   dim3 grid((unsigned)(Spad / 64), (unsigned)(cols / 64));
@@ -871,7 +906,7 @@ void launch_root_bwd(const Layout& ly, const Ptrs& p, const float* log_root, con
   launch_k(k_root_bwd, dim3(ly.B), dim3(256), 0, st, ly.N, ly.Np, ly.S1, p.rootrow, log_root, grad_logZ,
                      p.ztil, p.rmax, p.mexp, p.tmaxb, p.BH, p.UV, p.uexp, p.umaxb, p.gsc,
                      (int64_t)(ly.G > 1 ? ly.N : 0), static_cast<uint16_t*>(p.UVb), ly.planes_bwd,
-                     (int64_t)ly.Sall * 2 * ly.Np);
+                     ly.uvb_plane);
   launch_k(k_grad_log_root, dim3((ly.N + 255) / 256, ly.G > 1 ? ly.B : 1), dim3(256), 0, st, ly.B, ly.N,
                      ly.Np, ly.S1, p.rootrow, log_root, grad_logZ, p.ztil, p.rmax, p.T, p.tmaxb, grad_log_root,
                      accumulate, ly.G > 1 ? 1 : 0);
@@ -883,7 +918,7 @@ void launch_split_bwd(const Layout& ly, const Ptrs& p, int w, int64_t row0, int6
   const dim3 grid((unsigned)rows, (unsigned)((ly.Np + kChunk - 1) / kChunk));
   launch_k(k_split_bwd, grid, dim3(64), sh, st, w, row0, ly.B, ly.Np, ly.S1, (ly.n_max + 1) * ly.B, p.lens, p.rowbase, p.row_b,
                      p.row_i, p.rootmask, p.HZ, p.BH, p.mexp, p.tmaxb, p.UV, p.uexp, p.umaxb, p.gsc, write_planes ? p.UVb : nullptr, ly.planes_bwd,
-                     (int64_t)ly.Sall * 2 * ly.Np, p.hmaxb, p.zmaxb);
+                     ly.uvb_plane, p.hmaxb, p.zmaxb);
 }
 
 void launch_zero_pad_emit(const Layout& ly, const Ptrs& p, float* grad_log_emit, hipStream_t st) {

@@ -111,7 +111,16 @@ Layout make_layout(int N, int P, int B, int n_max, int64_t S1, int64_t S2, int b
     ly.Tb = take(2 * (size_t)ly.planes * S2 * ly.Np);
     ly.leafEb = take(2 * (size_t)ly.planes * S1 * ly.Pp);
   }
-  if (ly.planes_bwd > 0) ly.UVb = take(2 * (size_t)ly.planes_bwd * ly.Sall * 2 * ly.Np);
+  // rule gradients on planes (fp32 mode, shared grammar): the adjoint planes get 32 zeroed rows behind the last row (the
+  // product reads whole 32-row steps), and the scaled inside vectors get planes of their own, padded to whole steps
+  ly.tn3 = ly.planes_bwd == 3;
+  ly.S1p32 = (S1 + 31) / 32 * 32; ly.S2p32 = (S2 + 31) / 32 * 32;
+  ly.uvb_plane = (ly.Sall + (ly.tn3 ? 32 : 0)) * 2 * ly.Np;
+  if (ly.planes_bwd > 0) ly.UVb = take(2 * (size_t)ly.planes_bwd * ly.uvb_plane);
+  if (ly.tn3) {
+    ly.Tg3 = take(6 * (size_t)ly.S2p32 * ly.Np);
+    ly.Eg3 = take(6 * (size_t)ly.S1p32 * ly.Pp);
+  }
   ly.leafE = take(f4 * (size_t)S1 * ly.Pp);
   ly.T = take(f4 * (size_t)S2 * ly.Np);
   ly.BH = take(f4 * (size_t)S2 * ly.Np);
@@ -137,6 +146,7 @@ Ptrs resolve(const Layout& ly, void* ws) {
   p.sentrows = (int32_t*)(b + ly.sentrows); p.sentoff = (int32_t*)(b + ly.sentoff);
   p.Tb = ly.planes ? b + ly.Tb : nullptr; p.UVb = ly.planes_bwd ? b + ly.UVb : nullptr; p.leafEb = ly.planes ? b + ly.leafEb : nullptr;
   p.UVt_n = b + ly.UVt_n; p.Tt = b + ly.Tt; p.UVt_p = b + ly.UVt_p; p.Et = b + ly.Et;
+  p.Tg3 = b + ly.Tg3; p.Eg3 = b + ly.Eg3;
   p.Wn3 = b + ly.Wn3; p.Wp3 = b + ly.Wp3; p.Wtn3 = b + ly.Wtn3; p.Wtp3 = b + ly.Wtp3;
   p.Wn = (float*)(b + ly.Wn); p.Wp = (float*)(b + ly.Wp); p.Wtn = (float*)(b + ly.Wtn); p.Wtp = (float*)(b + ly.Wtp);
   return p;
@@ -390,7 +400,7 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
     if (ly.bf16) { a.A = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np; a.a_bf16 = 1; }
     if (ly.planes_bwd == 3) {
       a.A3 = static_cast<const uint16_t*>(p.UVb) + row0 * 2 * Np; a.Bm3 = w >= 2 ? p.Wtn3 : p.Wtp3;
-      a.planes3 = 3; a.a_plane = ly.Sall * 2 * Np; a.b_plane = 2 * Np * (w >= 2 ? Np : Pp);
+      a.planes3 = 3; a.a_plane = ly.uvb_plane; a.b_plane = 2 * Np * (w >= 2 ? Np : Pp);
     }
     if (w >= 2) {
       gemm_flop = 4.0 * ly.N * (double)ly.N * rows;
@@ -416,7 +426,8 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
     }
     {
       Scope s(st, SPCFG_PROF_SPLIT_BWD, split_bytes);
-      launch_split_bwd(ly, p, w, row0, rows, ly.bf16 || gemm_nt_reads_planes(a), st);
+      // (the rule-gradient product on planes reads the adjoint planes of every row)
+      launch_split_bwd(ly, p, w, row0, rows, ly.bf16 || (ly.tn3 && !fp32_mfma) || gemm_nt_reads_planes(a), st);
     }
     {
       Scope s(st, SPCFG_PROF_GEMM_BWD, gemm_flop);
@@ -442,6 +453,21 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
       t.Bm = p.leafE; t.ldb = Pp; t.cols = ly.P; t.col0 = ly.N;
       t.grp_kt_max = (n_longest + 31) / 32;
       launch_gemm_tn(t, st);
+    } else if (ly.tn3 && !fp32_mfma) {
+      // on planes: the adjoint rows as their producers cut them, the inside vectors times the span scale cut here
+      launch_scaled_planes(p.T, Np, p.gsc + ly.S1, ly.S2, ly.S2p32, p.Tg3, ly.S2p32 * Np, st);
+      launch_scaled_planes(p.leafE, Pp, p.gsc, ly.S1, ly.S1p32, p.Eg3, ly.S1p32 * Pp, st);
+      launch_zero_plane_rows(p.UVb, ly.uvb_plane, 2 * Np, ly.Sall, 32, st);
+      Tn3Args t{};
+      t.partial = p.partial; t.counters = p.counters; t.max_wgs = ly.gemm_wgs; t.n_counters = ly.n_counters;
+      t.Np = (int)Np; t.N = ly.N; t.gL = grad_L; t.gR = grad_R; t.ldg = ly.N + ly.P; t.accumulate = acc;
+      t.a_plane = ly.uvb_plane; t.lda = 2 * Np;
+      t.A3 = static_cast<const uint16_t*>(p.UVb) + ly.S1 * 2 * Np; t.B3 = static_cast<const uint16_t*>(p.Tg3);
+      t.b_plane = ly.S2p32 * Np; t.ldb = Np; t.KT = (int)(ly.S2p32 / 32); t.cols = ly.N; t.col0 = 0;
+      launch_gemm_tn3(t, st);
+      t.A3 = static_cast<const uint16_t*>(p.UVb); t.B3 = static_cast<const uint16_t*>(p.Eg3);
+      t.b_plane = ly.S1p32 * Pp; t.ldb = Pp; t.KT = (int)(ly.S1p32 / 32); t.cols = ly.P; t.col0 = ly.N;
+      launch_gemm_tn3(t, st);
     } else if (!ly.bf16) {
       TnArgs t{};
       t.fp32_mfma = fp32_mfma;

@@ -52,6 +52,9 @@ struct Layout {
                          // grammar per sentence), 2 hi + lo (bf16 mode, shared grammar), 3 the exact cut hi + mid + lo
                          // of every fp32 value (fp32 mode, shared grammar)
   int planes_bwd;        // the same for the adjoint rows of the reverse products: 0, 1 (bf16 mode) or 3
+  int tn3;               // rule gradients on operand planes (fp32 mode, shared grammar): Tg3 / Eg3 below, padded UVb
+  int64_t S1p32, S2p32;  // row counts rounded up to whole 32-row steps of that product
+  int64_t uvb_plane;     // elements between the planes of UVb: (Sall [+ 32 zeroed rows]) * 2Np
   int fwd_fp32;          // bf16 mode with one grammar per sentence: the forward products read fp32 operands (Wn / Wp are
                          // fp32 then, Wtn / Wtp bf16)
   int64_t S1pad, S2pad;  // row counts rounded up to 64 (K of the bf16 rule-gradient product)
@@ -62,6 +65,7 @@ struct Layout {
   size_t colmax;  // [G][2][Np + Pp]: largest entry of every column of L (then of R), nonterminal columns first
   size_t Wn3, Wp3, Wtn3, Wtp3;  // the packed panels once more, cut into bf16 planes: Wn3 / Wp3 `planes` of them (if >= 2), Wtn3 / Wtp3 three (planes_bwd == 3)
   size_t UVt_n, Tt, UVt_p, Et;  // bf16 mode only
+  size_t Tg3, Eg3;              // tn3: three bf16 planes of gsc[s] * T[s] ([3][S2p32][Np]) and of gsc[s] * leafE[s] ([3][S1p32][Pp])
   size_t Tb, UVb, leafEb;       // planes > 0: bf16 planes of T, UV, leafE ([planes][rows][cols]), written by their producers
   size_t sentrows, sentoff;     // per-sentence grammars only: rows of width >= 2 listed sentence by sentence, first entry of each
   int n_counters;
@@ -77,6 +81,7 @@ struct Ptrs {  // device pointers resolved from a Layout
   float *gsc, *xs, *ztil, *rmax;
   float *leafE, *T, *HZ, *UV, *BH, *Wn, *Wp, *Wtn, *Wtp, *partial;  // W* hold bf16 data in bf16 mode
   void *UVt_n, *Tt, *UVt_p, *Et;
+  void *Tg3, *Eg3;
   void *Tb, *UVb, *leafEb;  // null when the layout has no planes
   void *Wn3, *Wp3, *Wtn3, *Wtp3;
   int32_t* counters;
@@ -214,5 +219,25 @@ struct TnArgs {
   int grp_kt_max;  // number of 32-row steps of the longest per-sentence reduction
 };
 void launch_gemm_tn(const TnArgs& a, hipStream_t st);
+
+// The same product on operands that their producers have cut into three bf16 planes (gemm_tn3.hip): A3 = planes of the
+// adjoint rows UV ([3][..][lda], planes a_plane elements apart, pointing at the first row of the block), B3 = planes of
+// scale[s] * (inside vector of row s), zero from row S to the end of the last 32-row step.  A3 must be readable (and
+// finite) for 31 rows past the end of the reduction.
+struct Tn3Args {
+  const uint16_t* A3; int64_t a_plane, lda;
+  const uint16_t* B3; int64_t b_plane, ldb;
+  int KT;                           // 32-row steps of the reduction: ceil(S / 32)
+  int Np, N, cols;                  // as in TnArgs
+  float* gL; float* gR; int64_t ldg; int col0;
+  int accumulate;
+  float* partial; int32_t* counters; int max_wgs, n_counters;
+};
+void launch_gemm_tn3(const Tn3Args& a, hipStream_t st);
+// planes of sc[s] * X[s][.] for s < S and of zero for S <= s < Srows (X is [S x ld], ld a multiple of 4)
+void launch_scaled_planes(const float* X, int64_t ld, const float* sc, int64_t S, int64_t Srows, void* planes,
+                          int64_t plane_stride, hipStream_t st);
+// zeroes rows [row0, row0 + rows) of every plane of a [3][..][ld] array of bf16
+void launch_zero_plane_rows(void* planes, int64_t plane_stride, int64_t ld, int64_t row0, int64_t rows, hipStream_t st);
 
 }  // namespace spcfg

@@ -22,6 +22,12 @@ void launch_gemm_nt(const NtArgs& a, hipStream_t) {
   ++g_launches;
 }
 void launch_gemm_tn(const TnArgs&, hipStream_t) { ++g_launches; }
+void launch_gemm_tn3(const Tn3Args& a, hipStream_t) { if (a.KT < 0) __builtin_trap(); ++g_launches; }
+void launch_scaled_planes(const float*, int64_t, const float*, int64_t S, int64_t Srows, void*, int64_t, hipStream_t) {
+  if (Srows < S || Srows % 32 != 0) __builtin_trap();  // the product reads whole 32-row steps
+  ++g_launches;
+}
+void launch_zero_plane_rows(void*, int64_t, int64_t, int64_t, int64_t, hipStream_t) { ++g_launches; }
 bool gemm_nt_keep_parts(NtArgs& a) { return a.parts != 0; }
 bool gemm_nt_reads_planes(const NtArgs& a) { return a.planes3 != 0 && a.rows >= 380; }
 int gemm_nt_tiles(int rows, int cols) { return ((rows + 31) / 32) * ((cols + 127) / 128); }
