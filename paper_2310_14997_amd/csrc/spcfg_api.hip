@@ -435,7 +435,9 @@ int backward(const spcfg_config* cfg, const Plan& plan, const Layout& ly, const 
     }
   }
   {
-    Scope s(st, SPCFG_PROF_GEMM_GRAD, 4.0 * ly.N * ((double)ly.N * ly.S2 + (double)ly.P * ly.S1), 2);
+    // (launches of the class: the two products, plus what prepares their operands: planes or transposes)
+    Scope s(st, SPCFG_PROF_GEMM_GRAD, 4.0 * ly.N * ((double)ly.N * ly.S2 + (double)ly.P * ly.S1),
+            (ly.tn3 && !fp32_mfma && ly.G == 1) ? 5 : ((ly.bf16 && ly.G == 1) ? 6 : 2));
     if (ly.G > 1) {
       // one reduction per sentence over its own spans of width >= 2 (listed in sentrows), one over its leaves
       int n_longest = 2;
