@@ -212,7 +212,10 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tn3(Tn3Args g, int ipw, int tot
         constexpr int iv = decltype(i)::value;
         mfma_one(X, i);
         SPCFG_SB
-        read_one(Y, i, chunk1);
+        static_for<0, 2>([&](auto q) {  // two reads behind each of the first twelve: all have landed by the end of the half
+          constexpr int r = iv * 2 + decltype(q)::value;
+          if constexpr (r < kNR) read_one(Y, std::integral_constant<int, r>{}, chunk1);
+        });
         static_for<0, kND>([&](auto t) {
           constexpr int tv = decltype(t)::value;
           if constexpr ((tv * kNM) / kND == iv) dma16(gp[tv] + ((tv % 4) < 2 ? off_a : off_b), fill_lds + e_lds[tv]);
