@@ -606,12 +606,20 @@ __global__ void k_grad_log_root(int B, int N, int Np, int64_t S1, const int32_t*
   }
   const float lr = log_root[a];
   float acc = 0.0f;
-  for (int b = b_lo; b < b_hi; ++b) {
-    const float zt = ztil[b];
-    if (!(zt > 0.0f)) continue;
-    const int64_t r = rootrow[b];
-    const float g = grad_logZ ? grad_logZ[b] : 1.0f;
-    acc += g * expf(lr - rmaxs[b]) * (T[(r - S1) * Np + a] * norm_scale(tmaxb[r])) / zt;
+  for (int b0 = b_lo; b0 < b_hi; b0 += 8) {  // eight sentences' loads in flight; summed in sentence order
+    float t[8], coef[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int b = min(b0 + u, b_hi - 1);
+      const float zt = ztil[b];
+      const int64_t r = rootrow[b];
+      const float g = grad_logZ ? grad_logZ[b] : 1.0f;
+      const bool on = b0 + u < b_hi && zt > 0.0f;
+      t[u] = T[(r - S1) * Np + a] * norm_scale(tmaxb[r]);  // the root span's inside vector: always written, finite
+      coef[u] = on ? g * expf(lr - rmaxs[b]) / zt : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += coef[u] * t[u];
   }
   grad_log_root[a] = accumulate ? grad_log_root[a] + acc : acc;
 }
